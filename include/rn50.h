@@ -1,0 +1,206 @@
+/*
+ * rn50.h -- C ABI of the MI355X (gfx950) library that runs one GPU's share of a
+ * synchronous data-parallel ResNet-50 SGD iteration: forward and backward over
+ * the local mini-batch, label-smoothed softmax cross-entropy, and the
+ * momentum-SGD update of the flat parameter buffer.
+ *
+ * Source of the problem statement: the paper's Sec. 2 (every GPU runs
+ * forward/backward on its own mini-batch, gradients are averaged, weights are
+ * updated), Sec. 2.1 (label smoothing), Sec. 3.2 (ResNet-50; FP16
+ * forward/backward, FP32 optimizer arithmetic, batch normalisation from the
+ * batch mean and batch squared mean in FP32 without moving averages;
+ * per-worker mini-batch 16 or 32, Table 3).  The gradient all-reduce between
+ * backward and update is not part of this library.
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller, 16-byte
+ *     aligned.  The library allocates no device memory.  Descriptor structs
+ *     and out-parameters of the *_bytes / *_layout queries are HOST memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Every
+ *     call only enqueues work on that stream and returns; nothing synchronises.
+ *   - Return value: RN50_OK (0) or a negative rn50_status.  Arguments are
+ *     validated before anything is launched; on error nothing is enqueued.
+ *   - Layouts: activations NHWC, filters KRSC (out-channel, row, col,
+ *     in-channel), all dense.  "half" below is IEEE binary16 (RN50_F16).
+ *   - Workspaces: `ws` must hold at least the number of bytes the matching
+ *     *_workspace_bytes query returns, else RN50_ERR_WORKSPACE.  Contents are
+ *     scratch; two calls that overlap in time must not share a workspace.
+ */
+#ifndef RN50_H
+#define RN50_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RN50_OK = 0,
+    RN50_ERR_NULL = -1,      /* a required pointer is NULL */
+    RN50_ERR_SHAPE = -2,     /* a size is non-positive or unsupported by the kernels */
+    RN50_ERR_DTYPE = -3,     /* storage type not supported */
+    RN50_ERR_WORKSPACE = -4, /* workspace missing or too small */
+    RN50_ERR_ALIGN = -5,     /* a pointer is not 16-byte aligned */
+    RN50_ERR_HIP = -6        /* a HIP runtime call failed (see rn50_last_hip_error) */
+} rn50_status;
+
+typedef enum { RN50_F16 = 0, RN50_BF16 = 1 } rn50_dtype; /* only RN50_F16 is implemented */
+
+const char* rn50_status_string(int status);
+int rn50_last_hip_error(void); /* hipError_t of the most recent RN50_ERR_HIP on this thread */
+
+/* ------------------------------------------------------------------------------------------
+ * Convolution (Sec. 3.2: the convolutions of ResNet-50, FP16 storage, FP32 accumulation).
+ * x [n,h,w,c] half, w [k,r,s,c] half, y [n,p,q,k] half with p=(h+2*pad-r)/stride+1 (q alike).
+ * Supported: c and k multiples of 64 with r=s in {1,3}, stride in {1,2}; and the stem
+ * shape c=3, r=s=7, stride=2, pad=3 (k multiple of 64; no conv_dgrad for the stem).
+ * ---------------------------------------------------------------------------------------- */
+typedef struct {
+    int n, h, w, c; /* input  NHWC */
+    int k, r, s;    /* filter KRSC */
+    int stride, pad;
+    int dt;         /* rn50_dtype */
+} conv_desc;
+
+enum { RN50_CONV_FWD = 0, RN50_CONV_DGRAD = 1, RN50_CONV_WGRAD = 2 };
+size_t conv_workspace_bytes(const conv_desc* d, int which);
+
+/* y[n,p,q,k] = sum_{r,s,c} x[n,p*stride+r-pad,q*stride+s-pad,c] * w[k,r,s,c]  (zero padding) */
+int conv_fwd(const conv_desc* d, const void* x, const void* w, void* y,
+             void* ws, size_t ws_bytes, void* stream);
+/* dx[n,h,w,c] = sum over (k,r,s) with h+pad-r = p*stride, w+pad-s = q*stride of
+ *               dy[n,p,q,k] * w[k,r,s,c].  Every element of dx is written. */
+int conv_dgrad(const conv_desc* d, const void* dy, const void* w, void* dx,
+               void* ws, size_t ws_bytes, void* stream);
+/* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n,p*stride+r-pad,q*stride+s-pad,c], stored as
+ * half.  FP32 partial sums of different pixel ranges are combined with atomic adds, so
+ * the last bits may differ from run to run. */
+int conv_wgrad(const conv_desc* d, const void* x, const void* dy, void* dw,
+               void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Batch normalisation over m = N*H*W rows of c channels with batch statistics only
+ * (Sec. 3.2, "Batch Normalization without Moving Average": batch mean and batch squared
+ * mean in FP32 => biased variance), optional residual add, optional ReLU.
+ *   mean_c = E[x], var_c = E[x^2]-mean^2 (clamped at 0), invstd = 1/sqrt(var+eps)
+ *   y = gamma*(x-mean)*invstd + beta (+ residual);  y = max(y,0) if relu
+ * c must be a multiple of 8.  x, y, residual, dy, dx, dresidual: half [m,c].
+ * gamma, beta, save_mean, save_invstd: float [c].  dgamma, dbeta: half [c] (slices of
+ * the flat FP16 gradient).
+ * ---------------------------------------------------------------------------------------- */
+typedef struct {
+    long long m;
+    int c;
+    float eps;
+    int relu;         /* 0/1 */
+    int has_residual; /* 0/1 */
+    int dt;           /* rn50_dtype */
+} bn_desc;
+
+size_t bn_workspace_bytes(const bn_desc* d);
+int bn_relu_fwd(const bn_desc* d, const void* x, const float* gamma, const float* beta,
+                const void* residual /* NULL unless has_residual */, void* y,
+                float* save_mean, float* save_invstd, void* ws, size_t ws_bytes, void* stream);
+/* g = dy*[y>0] if relu else dy;  dresidual = g (written iff has_residual);
+ * dbeta = sum g; dgamma = sum g*xhat; dx = gamma*invstd*(g - dbeta/m - xhat*dgamma/m). */
+int bn_relu_bwd(const bn_desc* d, const void* dy, const void* x, const void* y /* NULL unless relu */,
+                const float* gamma, const float* save_mean, const float* save_invstd,
+                void* dx, void* dresidual /* NULL unless has_residual */, void* dgamma, void* dbeta,
+                void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Softmax cross-entropy with label smoothing (Sec. 2.1).  Target q = (1-eps)*onehot + eps/K.
+ *   l_i = -sum_k q_k log softmax(logits_i)_k ; *loss_mean = mean_i l_i
+ *   dlogits[i,k] = (softmax(logits_i)_k - q_k) * grad_scale   (half)
+ * logits float [batch,classes]; labels int32 [batch], each in [0,classes) (not checked on
+ * the device: out-of-range labels are treated as "no true class").  loss_per_sample
+ * (float [batch]) may be NULL.  1 <= batch <= 65536, 2 <= classes <= 65536.
+ * ---------------------------------------------------------------------------------------- */
+int ls_xent_fwd_bwd(int batch, int classes, const float* logits, const int32_t* labels,
+                    float eps, float grad_scale, float* loss_mean, float* loss_per_sample,
+                    void* dlogits, int dlogits_dt, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Momentum SGD over the flat buffer (Sec. 3.2: FP32 optimizer arithmetic on FP16 gradients;
+ * the paper's LARS scaling is not applied).  For every i < n, in FP32:
+ *   g' = float(grad[i])*grad_scale + wd*w[i];  v[i] = mu*v[i] + g';  w[i] -= lr*v[i]
+ *   w_lowp_out[i] = half(w[i])   (skipped if w_lowp_out is NULL)
+ * master_w and momentum are updated in place.
+ * ---------------------------------------------------------------------------------------- */
+int sgd_momentum_flat(size_t n, const void* grad, int grad_dt, float grad_scale,
+                      float* master_w, float* momentum, void* w_lowp_out,
+                      float lr, float mu, float wd, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Whole iteration (Sec. 2 + Sec. 3.2) on a ResNet-50 v1.5 style network:
+ *   [stem 7x7/2 conv 3->base_width, BN, ReLU, 3x3/2 max-pool]  (iff has_stem)
+ *   num_stages stages of blocks[s] bottleneck blocks (1x1, 3x3, 1x1; widths w,w,4w with
+ *   w = base_width<<s; stride 2 on the 3x3 of the first block of stages >= 1; 1x1
+ *   projection shortcut + BN on the first block of every stage; ReLU after the add),
+ *   global average pool, FC to `classes`, label-smoothed loss, backward, momentum SGD.
+ * ResNet-50: has_stem=1, image 224x224, num_stages=4, blocks={3,4,6,3}, base_width=64,
+ * classes=1000.  Without a stem the input is [batch,image_h,image_w,base_width] half and
+ * receives no gradient.
+ *
+ * Flat parameter layout (used by master_w, momentum, w_lowp, grad_lowp alike), network
+ * order: per conv its filter KRSC, then BN gamma, then BN beta; inside a block conv1,
+ * conv2, conv3, projection; then FC weight [classes,C], then FC bias.  rn50_param_layout
+ * walks it.  Forward uses w_lowp for filters and the FC weight, master_w for gamma,
+ * beta and the FC bias.  On entry w_lowp must equal half(master_w) (rn50_cast_params).
+ * ---------------------------------------------------------------------------------------- */
+typedef struct {
+    int batch;
+    int image_h, image_w;
+    int has_stem;
+    int num_stages;   /* 1..4 */
+    int blocks[4];
+    int base_width;   /* multiple of 64 */
+    int classes;      /* multiple of 8 */
+    int dt;           /* rn50_dtype */
+    float bn_eps;
+    float ls_eps;
+    float loss_scale; /* dlogits = loss_scale*(p-q)/batch; the update multiplies by grad_scale */
+} rn50_config;
+
+typedef struct { float lr, momentum, wd, grad_scale; } rn50_hparams;
+
+typedef struct rn50_ctx rn50_ctx; /* host object: descriptors + pointers into the workspace */
+
+enum { RN50_KIND_CONV = 0, RN50_KIND_GAMMA = 1, RN50_KIND_BETA = 2, RN50_KIND_FCW = 3, RN50_KIND_FCB = 4 };
+
+size_t rn50_param_count(const rn50_config* cfg); /* 25557032 for ResNet-50; 0 on a bad config */
+int rn50_num_segments(const rn50_config* cfg);
+/* idx-th segment of the flat layout: element offset, element count, RN50_KIND_*, fan-in
+ * (c*r*s for filters, C for the FC weight, 0 otherwise). */
+int rn50_param_layout(const rn50_config* cfg, int idx, size_t* offset, size_t* count, int* kind, int* fan_in);
+
+size_t rn50_workspace_bytes(const rn50_config* cfg); /* activations, gradients, statistics, scratch */
+/* Binds a context to a caller-owned device workspace (kept until rn50_destroy). */
+int rn50_create(rn50_ctx** out, const rn50_config* cfg, void* workspace, size_t workspace_bytes);
+void rn50_destroy(rn50_ctx* ctx);
+
+/* w_lowp[i] = half(master_w[i]) for the whole flat buffer. */
+int rn50_cast_params(size_t n, const float* master_w, void* w_lowp, int dt, void* stream);
+
+/* One iteration.  images half [batch,image_h,image_w,3] (or [..,base_width] without stem),
+ * labels int32 [batch].  master_w, momentum float [P] updated in place; w_lowp half [P]
+ * read, then overwritten with half(new master_w); grad_lowp half [P] receives the
+ * (loss_scale-scaled) flat gradient; loss_out: one float on the device.
+ * If hp is NULL the update is skipped (forward, loss and backward only). */
+int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* labels,
+              float* master_w, float* momentum, void* w_lowp, void* grad_lowp,
+              const rn50_hparams* hp, float* loss_out, void* stream);
+
+/* Device address of a tensor the last rn50_step left in the workspace, for parity checks.
+ * name: "<conv>.conv" (conv output), "<conv>.out" (BN output), "<conv>.mean",
+ * "<conv>.invstd", "pool.out", "feat", "logits", "dlogits"; <conv> = "stem" or
+ * "s<stage>b<block>{c1,c2,c3,p}" (stage from 1).  *elems = element count,
+ * *elem_bytes = 2 or 4.  Unknown name: RN50_ERR_SHAPE. */
+int rn50_tensor(rn50_ctx* ctx, const char* name, void** ptr, size_t* elems, int* elem_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RN50_H */

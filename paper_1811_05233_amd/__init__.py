@@ -1,0 +1,251 @@
+"""Thin Python binding of librn50.so (hand-written HIP for gfx950).
+
+Argument marshalling only: torch tensors supply device memory and the current
+stream; every step of the path runs inside the library's kernels.  Function
+names and argument order follow include/rn50.h.  There is no fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librn50.so")
+
+RN50_F16, RN50_BF16 = 0, 1
+CONV_FWD, CONV_DGRAD, CONV_WGRAD = 0, 1, 2
+KIND_CONV, KIND_GAMMA, KIND_BETA, KIND_FCW, KIND_FCB = 0, 1, 2, 3, 4
+
+
+class Rn50Error(RuntimeError):
+    pass
+
+
+class conv_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("n", "h", "w", "c", "k", "r", "s", "stride", "pad", "dt")]
+
+
+class bn_desc(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_longlong), ("c", ctypes.c_int), ("eps", ctypes.c_float), ("relu", ctypes.c_int),
+                ("has_residual", ctypes.c_int), ("dt", ctypes.c_int)]
+
+
+class rn50_config(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int), ("image_h", ctypes.c_int), ("image_w", ctypes.c_int),
+                ("has_stem", ctypes.c_int), ("num_stages", ctypes.c_int), ("blocks", ctypes.c_int * 4),
+                ("base_width", ctypes.c_int), ("classes", ctypes.c_int), ("dt", ctypes.c_int),
+                ("bn_eps", ctypes.c_float), ("ls_eps", ctypes.c_float), ("loss_scale", ctypes.c_float)]
+
+
+class rn50_hparams(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float), ("wd", ctypes.c_float),
+                ("grad_scale", ctypes.c_float)]
+
+
+_lib = None
+_vp, _sz, _i, _f = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
+
+_SIGNATURES = {
+    "rn50_status_string": (ctypes.c_char_p, [_i]),
+    "rn50_last_hip_error": (_i, []),
+    "conv_workspace_bytes": (_sz, [ctypes.POINTER(conv_desc), _i]),
+    "conv_fwd": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _vp]),
+    "conv_dgrad": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _vp]),
+    "conv_wgrad": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_workspace_bytes": (_sz, [ctypes.POINTER(bn_desc)]),
+    "bn_relu_fwd": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_relu_bwd": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "ls_xent_fwd_bwd": (_i, [_i, _i, _vp, _vp, _f, _f, _vp, _vp, _vp, _i, _vp]),
+    "sgd_momentum_flat": (_i, [_sz, _vp, _i, _f, _vp, _vp, _vp, _f, _f, _f, _vp]),
+    "rn50_param_count": (_sz, [ctypes.POINTER(rn50_config)]),
+    "rn50_num_segments": (_i, [ctypes.POINTER(rn50_config)]),
+    "rn50_param_layout": (_i, [ctypes.POINTER(rn50_config), _i, ctypes.POINTER(_sz), ctypes.POINTER(_sz),
+                               ctypes.POINTER(_i), ctypes.POINTER(_i)]),
+    "rn50_workspace_bytes": (_sz, [ctypes.POINTER(rn50_config)]),
+    "rn50_create": (_i, [ctypes.POINTER(_vp), ctypes.POINTER(rn50_config), _vp, _sz]),
+    "rn50_destroy": (None, [_vp]),
+    "rn50_cast_params": (_i, [_sz, _vp, _vp, _i, _vp]),
+    "rn50_step": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(rn50_hparams), _vp, _vp]),
+    "rn50_tensor": (_i, [_vp, ctypes.c_char_p, ctypes.POINTER(_vp), ctypes.POINTER(_sz), ctypes.POINTER(_i)]),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+
+def lib():
+    """Load librn50.so (built by paper_1811_05233_amd/build.py).  Raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise Rn50Error("librn50.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        l = ctypes.CDLL(LIB_PATH)
+        missing = []
+        for name, (res, args) in _SIGNATURES.items():
+            try:
+                fn = getattr(l, name)
+            except AttributeError:
+                missing.append(name)
+                continue
+            fn.restype, fn.argtypes = res, args
+        if missing and not os.environ.get("RN50_ALLOW_PARTIAL_LIB"):
+            raise Rn50Error("librn50.so lacks %s: rebuild it" % ", ".join(missing))
+        _lib = l
+    return _lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        l = lib()
+        msg = l.rn50_status_string(rc).decode()
+        if rc == -6:
+            msg += " (hipError %d)" % l.rn50_last_hip_error()
+        raise Rn50Error("%s failed: %s" % (what, msg))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(nbytes, like):
+    import torch
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=like.device)
+
+
+# ------------------------------------------------------------------ kernels
+def make_conv_desc(n, h, w, c, k, r, s, stride, pad, dt=RN50_F16):
+    return conv_desc(n, h, w, c, k, r, s, stride, pad, dt)
+
+
+def conv_workspace_bytes(d, which):
+    return int(lib().conv_workspace_bytes(ctypes.byref(d), which))
+
+
+def conv_fwd(d, x, w, y, ws=None):
+    ws = ws if ws is not None else _ws(conv_workspace_bytes(d, CONV_FWD), x)
+    _check(lib().conv_fwd(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), _ptr(ws), ws.numel(), _stream()), "conv_fwd")
+    return y
+
+
+def conv_dgrad(d, dy, w, dx, ws=None):
+    ws = ws if ws is not None else _ws(conv_workspace_bytes(d, CONV_DGRAD), dy)
+    _check(lib().conv_dgrad(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(dx), _ptr(ws), ws.numel(), _stream()),
+           "conv_dgrad")
+    return dx
+
+
+def conv_wgrad(d, x, dy, dw, ws=None):
+    ws = ws if ws is not None else _ws(conv_workspace_bytes(d, CONV_WGRAD), x)
+    _check(lib().conv_wgrad(ctypes.byref(d), _ptr(x), _ptr(dy), _ptr(dw), _ptr(ws), ws.numel(), _stream()),
+           "conv_wgrad")
+    return dw
+
+
+def make_bn_desc(m, c, eps=1e-5, relu=True, has_residual=False, dt=RN50_F16):
+    return bn_desc(m, c, eps, int(relu), int(has_residual), dt)
+
+
+def bn_workspace_bytes(d):
+    return int(lib().bn_workspace_bytes(ctypes.byref(d)))
+
+
+def bn_relu_fwd(d, x, gamma, beta, residual, y, save_mean, save_invstd, ws=None):
+    ws = ws if ws is not None else _ws(bn_workspace_bytes(d), x)
+    _check(lib().bn_relu_fwd(ctypes.byref(d), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(residual), _ptr(y),
+                             _ptr(save_mean), _ptr(save_invstd), _ptr(ws), ws.numel(), _stream()), "bn_relu_fwd")
+    return y
+
+
+def bn_relu_bwd(d, dy, x, y, gamma, save_mean, save_invstd, dx, dresidual, dgamma, dbeta, ws=None):
+    ws = ws if ws is not None else _ws(bn_workspace_bytes(d), x)
+    _check(lib().bn_relu_bwd(ctypes.byref(d), _ptr(dy), _ptr(x), _ptr(y), _ptr(gamma), _ptr(save_mean),
+                             _ptr(save_invstd), _ptr(dx), _ptr(dresidual), _ptr(dgamma), _ptr(dbeta),
+                             _ptr(ws), ws.numel(), _stream()), "bn_relu_bwd")
+    return dx
+
+
+def ls_xent_fwd_bwd(batch, classes, logits, labels, eps, grad_scale, loss_mean, loss_per_sample, dlogits,
+                    dlogits_dt=RN50_F16):
+    _check(lib().ls_xent_fwd_bwd(batch, classes, _ptr(logits), _ptr(labels), eps, grad_scale, _ptr(loss_mean),
+                                 _ptr(loss_per_sample), _ptr(dlogits), dlogits_dt, _stream()), "ls_xent_fwd_bwd")
+
+
+def sgd_momentum_flat(n, grad, grad_scale, master_w, momentum, w_lowp_out, lr, mu, wd, grad_dt=RN50_F16):
+    _check(lib().sgd_momentum_flat(n, _ptr(grad), grad_dt, grad_scale, _ptr(master_w), _ptr(momentum),
+                                   _ptr(w_lowp_out), lr, mu, wd, _stream()), "sgd_momentum_flat")
+
+
+def rn50_cast_params(n, master_w, w_lowp, dt=RN50_F16):
+    _check(lib().rn50_cast_params(n, _ptr(master_w), _ptr(w_lowp), dt, _stream()), "rn50_cast_params")
+
+
+# ------------------------------------------------------------------ whole step
+def make_config(batch, image_hw=(224, 224), has_stem=True, blocks=(3, 4, 6, 3), base_width=64, classes=1000,
+                bn_eps=1e-5, ls_eps=0.1, loss_scale=1.0, dt=RN50_F16):
+    b = (ctypes.c_int * 4)(*(list(blocks) + [0] * (4 - len(blocks))))
+    return rn50_config(batch, image_hw[0], image_hw[1], int(has_stem), len(blocks), b, base_width, classes, dt,
+                       bn_eps, ls_eps, loss_scale)
+
+
+def rn50_param_count(cfg):
+    return int(lib().rn50_param_count(ctypes.byref(cfg)))
+
+
+def rn50_param_layout(cfg):
+    """List of (kind, offset, count, fan_in) for every segment of the flat layout."""
+    l = lib()
+    out = []
+    for i in range(l.rn50_num_segments(ctypes.byref(cfg))):
+        off, cnt, kind, fan = _sz(), _sz(), _i(), _i()
+        _check(l.rn50_param_layout(ctypes.byref(cfg), i, ctypes.byref(off), ctypes.byref(cnt), ctypes.byref(kind),
+                                   ctypes.byref(fan)), "rn50_param_layout")
+        out.append((kind.value, off.value, cnt.value, fan.value))
+    return out
+
+
+def rn50_workspace_bytes(cfg):
+    return int(lib().rn50_workspace_bytes(ctypes.byref(cfg)))
+
+
+class Rn50Context:
+    """Owns the workspace tensor and the rn50_ctx handle."""
+
+    def __init__(self, cfg, device="cuda:0"):
+        import torch
+        self.cfg = cfg
+        nbytes = rn50_workspace_bytes(cfg)
+        if nbytes == 0:
+            raise Rn50Error("rn50_workspace_bytes: bad configuration")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        h = _vp()
+        _check(lib().rn50_create(ctypes.byref(h), ctypes.byref(cfg), _ptr(self.workspace), nbytes), "rn50_create")
+        self.handle = h
+
+    def step(self, images, labels, master_w, momentum, w_lowp, grad_lowp, hp, loss_out):
+        hpp = None if hp is None else ctypes.byref(hp)
+        _check(lib().rn50_step(self.handle, _ptr(images), _ptr(labels), _ptr(master_w), _ptr(momentum),
+                               _ptr(w_lowp), _ptr(grad_lowp), hpp, _ptr(loss_out), _stream()), "rn50_step")
+
+    def tensor(self, name):
+        """Copy of a workspace tensor left by the last step, as a flat torch tensor (half or float)."""
+        import torch
+        p, n, eb = _vp(), _sz(), _i()
+        _check(lib().rn50_tensor(self.handle, name.encode(), ctypes.byref(p), ctypes.byref(n), ctypes.byref(eb)),
+               "rn50_tensor(%s)" % name)
+        base = self.workspace.data_ptr()
+        off = p.value - base
+        raw = self.workspace[off:off + n.value * eb.value]
+        return raw.view(torch.float16 if eb.value == 2 else torch.float32).clone()
+
+    def close(self):
+        if self.handle:
+            lib().rn50_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

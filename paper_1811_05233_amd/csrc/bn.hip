@@ -1,0 +1,379 @@
+// Fused BatchNorm (+residual) (+ReLU), forward and backward, batch statistics only.
+// Tensors are [m, c] half with c contiguous; a thread owns one group of 8 channels
+// (one 16-byte chunk per row) and walks rows, so every access is a coalesced 16-byte
+// load/store and per-channel parameters stay in registers.
+//
+// Reductions are two-stage and deterministic: every workgroup writes per-channel partial
+// sums to the workspace, a small second kernel combines them in a fixed order (in double).
+// The forward statistics are accumulated around a per-channel pivot (row 0) so that
+// E[x^2]-E[x]^2 does not cancel when |mean| >> sigma.
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxBlocks = 2048;
+
+struct RowMap {
+    int gp;         // 16-byte channel groups per row (c / 8)
+    int gpb;        // channel groups handled by one pass of a workgroup: min(gp, 256)
+    int rows_par;   // rows handled in parallel by a workgroup: 256 / gpb
+};
+
+__host__ __device__ inline RowMap make_rowmap(int c) {
+    RowMap r;
+    r.gp = c / 8;
+    r.gpb = r.gp < kThreads ? r.gp : kThreads;
+    r.rows_par = kThreads / r.gpb;
+    return r;
+}
+
+// Sum the kThreads/gpb row-lanes that share a channel group.  vals: this thread's NV values.
+// After the call thread (row lane 0) holds the totals.
+template <int NV>
+__device__ __forceinline__ void reduce_row_lanes(float (&vals)[NV], float* smem, const RowMap& rm) {
+    if (rm.rows_par == 1) return;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) smem[j * kThreads + tid] = vals[j];
+    __syncthreads();
+    if (tid < rm.gpb) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            float s = 0.f;
+            for (int r = 0; r < rm.rows_par; ++r) s += smem[j * kThreads + r * rm.gpb + tid];
+            vals[j] = s;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ forward statistics
+// part[(blk*2+0)*c + ch] = sum (x - pivot), part[(blk*2+1)*c + ch] = sum (x - pivot)^2
+__global__ __launch_bounds__(kThreads) void bn_stats_kernel(long long m, int c, const h16* __restrict__ x,
+                                                            float* __restrict__ part, int rows_per_block)
+{
+    __shared__ float smem[16 * kThreads];
+    const RowMap rm = make_rowmap(c);
+    const int tid = threadIdx.x;
+    const int cgl = tid % rm.gpb, rl = tid / rm.gpb;
+    const long long row0 = (long long)blockIdx.x * rows_per_block;
+    long long row1 = row0 + rows_per_block;
+    if (row1 > m) row1 = m;
+    for (int cg = cgl; cg < rm.gp; cg += rm.gpb) {
+        const h16x8 pv = *reinterpret_cast<const h16x8*>(x + (size_t)cg * 8);
+        float acc[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+        for (long long r = row0 + rl; r < row1; r += rm.rows_par) {
+            const h16x8 v = *reinterpret_cast<const h16x8*>(x + (size_t)r * c + (size_t)cg * 8);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float d = (float)v[j] - (float)pv[j];
+                acc[j] += d;
+                acc[8 + j] += d * d;
+            }
+        }
+        reduce_row_lanes<16>(acc, smem, rm);
+        if (rl == 0) {
+            float* p0 = part + ((size_t)blockIdx.x * 2) * c + (size_t)cg * 8;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { p0[j] = acc[j]; p0[c + j] = acc[8 + j]; }
+        }
+        if (rm.gp > rm.gpb) __syncthreads();
+    }
+}
+
+// One workgroup per 16 channels; 16 lanes per channel walk the partials, then combine in double.
+__global__ __launch_bounds__(kThreads) void bn_stats_finalize_kernel(long long m, int c, float eps, int nblk,
+                                                                     const h16* __restrict__ x,
+                                                                     const float* __restrict__ part,
+                                                                     float* __restrict__ save_mean,
+                                                                     float* __restrict__ save_invstd)
+{
+    __shared__ double s1[kThreads], s2[kThreads];
+    const int tid = threadIdx.x;
+    const int cl = tid & 15, bl = tid >> 4;
+    const int ch = blockIdx.x * 16 + cl;
+    double a = 0.0, b = 0.0;
+    if (ch < c)
+        for (int k = bl; k < nblk; k += 16) {
+            a += (double)part[((size_t)k * 2) * c + ch];
+            b += (double)part[((size_t)k * 2 + 1) * c + ch];
+        }
+    s1[tid] = a; s2[tid] = b;
+    __syncthreads();
+    if (bl == 0 && ch < c) {
+        for (int k = 1; k < 16; ++k) { a += s1[k * 16 + cl]; b += s2[k * 16 + cl]; }
+        const double pivot = (double)(float)x[ch];
+        const double md = a / (double)m;
+        double var = b / (double)m - md * md;
+        if (var < 0.0) var = 0.0;
+        save_mean[ch] = (float)(pivot + md);
+        save_invstd[ch] = (float)(1.0 / sqrt(var + (double)eps));
+    }
+}
+
+// ------------------------------------------------------------------ forward apply
+template <bool kRelu, bool kRes>
+__global__ __launch_bounds__(kThreads) void bn_apply_kernel(long long m, int c, const h16* __restrict__ x,
+                                                            const float* __restrict__ gamma,
+                                                            const float* __restrict__ beta,
+                                                            const float* __restrict__ mean,
+                                                            const float* __restrict__ invstd,
+                                                            const h16* __restrict__ res, h16* __restrict__ y,
+                                                            int rows_per_block)
+{
+    const RowMap rm = make_rowmap(c);
+    const int tid = threadIdx.x;
+    const int cgl = tid % rm.gpb, rl = tid / rm.gpb;
+    const long long row0 = (long long)blockIdx.x * rows_per_block;
+    long long row1 = row0 + rows_per_block;
+    if (row1 > m) row1 = m;
+    for (int cg = cgl; cg < rm.gp; cg += rm.gpb) {
+        float g[8], b[8], mu[8], is[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            g[j] = gamma[cg * 8 + j]; b[j] = beta[cg * 8 + j];
+            mu[j] = mean[cg * 8 + j]; is[j] = invstd[cg * 8 + j];
+        }
+        for (long long r = row0 + rl; r < row1; r += rm.rows_par) {
+            const size_t off = (size_t)r * c + (size_t)cg * 8;
+            const h16x8 v = *reinterpret_cast<const h16x8*>(x + off);
+            h16x8 rv;
+            if (kRes) rv = *reinterpret_cast<const h16x8*>(res + off);
+            h16x8 o;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                float t = g[j] * (((float)v[j] - mu[j]) * is[j]) + b[j];
+                if (kRes) t += (float)rv[j];
+                if (kRelu) t = t > 0.f ? t : 0.f;
+                o[j] = (h16)t;
+            }
+            *reinterpret_cast<h16x8*>(y + off) = o;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ backward reductions
+// part[(blk*2+0)*c + ch] = sum g, part[(blk*2+1)*c + ch] = sum g*xhat
+template <bool kRelu>
+__global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(long long m, int c, const h16* __restrict__ dy,
+                                                                 const h16* __restrict__ x,
+                                                                 const h16* __restrict__ y,
+                                                                 const float* __restrict__ mean,
+                                                                 const float* __restrict__ invstd,
+                                                                 float* __restrict__ part, int rows_per_block)
+{
+    __shared__ float smem[16 * kThreads];
+    const RowMap rm = make_rowmap(c);
+    const int tid = threadIdx.x;
+    const int cgl = tid % rm.gpb, rl = tid / rm.gpb;
+    const long long row0 = (long long)blockIdx.x * rows_per_block;
+    long long row1 = row0 + rows_per_block;
+    if (row1 > m) row1 = m;
+    for (int cg = cgl; cg < rm.gp; cg += rm.gpb) {
+        float mu[8], is[8], acc[16];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { mu[j] = mean[cg * 8 + j]; is[j] = invstd[cg * 8 + j]; }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+        for (long long r = row0 + rl; r < row1; r += rm.rows_par) {
+            const size_t off = (size_t)r * c + (size_t)cg * 8;
+            const h16x8 d = *reinterpret_cast<const h16x8*>(dy + off);
+            const h16x8 xv = *reinterpret_cast<const h16x8*>(x + off);
+            h16x8 yv;
+            if (kRelu) yv = *reinterpret_cast<const h16x8*>(y + off);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                float g = (float)d[j];
+                if (kRelu) g = (float)yv[j] > 0.f ? g : 0.f;
+                acc[j] += g;
+                acc[8 + j] += g * (((float)xv[j] - mu[j]) * is[j]);
+            }
+        }
+        reduce_row_lanes<16>(acc, smem, rm);
+        if (rl == 0) {
+            float* p0 = part + ((size_t)blockIdx.x * 2) * c + (size_t)cg * 8;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { p0[j] = acc[j]; p0[c + j] = acc[8 + j]; }
+        }
+        if (rm.gp > rm.gpb) __syncthreads();
+    }
+}
+
+// sums[0..c) = dbeta, sums[c..2c) = dgamma (float, kept for the apply pass); also the half copies.
+__global__ __launch_bounds__(kThreads) void bn_bwd_finalize_kernel(int c, int nblk, const float* __restrict__ part,
+                                                                   float* __restrict__ sums,
+                                                                   h16* __restrict__ dgamma, h16* __restrict__ dbeta)
+{
+    __shared__ double s1[kThreads], s2[kThreads];
+    const int tid = threadIdx.x;
+    const int cl = tid & 15, bl = tid >> 4;
+    const int ch = blockIdx.x * 16 + cl;
+    double a = 0.0, b = 0.0;
+    if (ch < c)
+        for (int k = bl; k < nblk; k += 16) {
+            a += (double)part[((size_t)k * 2) * c + ch];
+            b += (double)part[((size_t)k * 2 + 1) * c + ch];
+        }
+    s1[tid] = a; s2[tid] = b;
+    __syncthreads();
+    if (bl == 0 && ch < c) {
+        for (int k = 1; k < 16; ++k) { a += s1[k * 16 + cl]; b += s2[k * 16 + cl]; }
+        sums[ch] = (float)a;
+        sums[c + ch] = (float)b;
+        dbeta[ch] = (h16)(float)a;
+        dgamma[ch] = (h16)(float)b;
+    }
+}
+
+template <bool kRelu, bool kRes>
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(long long m, int c, const h16* __restrict__ dy,
+                                                                const h16* __restrict__ x,
+                                                                const h16* __restrict__ y,
+                                                                const float* __restrict__ gamma,
+                                                                const float* __restrict__ mean,
+                                                                const float* __restrict__ invstd,
+                                                                const float* __restrict__ sums,
+                                                                h16* __restrict__ dx, h16* __restrict__ dres,
+                                                                int rows_per_block)
+{
+    const RowMap rm = make_rowmap(c);
+    const int tid = threadIdx.x;
+    const int cgl = tid % rm.gpb, rl = tid / rm.gpb;
+    const long long row0 = (long long)blockIdx.x * rows_per_block;
+    long long row1 = row0 + rows_per_block;
+    if (row1 > m) row1 = m;
+    const float inv_m = 1.f / (float)m;
+    for (int cg = cgl; cg < rm.gp; cg += rm.gpb) {
+        float mu[8], is[8], sc[8], mb[8], mg[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            mu[j] = mean[cg * 8 + j]; is[j] = invstd[cg * 8 + j];
+            sc[j] = gamma[cg * 8 + j] * is[j];
+            mb[j] = sums[cg * 8 + j] * inv_m;
+            mg[j] = sums[c + cg * 8 + j] * inv_m;
+        }
+        for (long long r = row0 + rl; r < row1; r += rm.rows_par) {
+            const size_t off = (size_t)r * c + (size_t)cg * 8;
+            const h16x8 d = *reinterpret_cast<const h16x8*>(dy + off);
+            const h16x8 xv = *reinterpret_cast<const h16x8*>(x + off);
+            h16x8 yv;
+            if (kRelu) yv = *reinterpret_cast<const h16x8*>(y + off);
+            h16x8 o, go;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                float g = (float)d[j];
+                if (kRelu) g = (float)yv[j] > 0.f ? g : 0.f;
+                go[j] = (h16)g;
+                const float xh = ((float)xv[j] - mu[j]) * is[j];
+                o[j] = (h16)(sc[j] * (g - mb[j] - xh * mg[j]));
+            }
+            *reinterpret_cast<h16x8*>(dx + off) = o;
+            if (kRes) *reinterpret_cast<h16x8*>(dres + off) = go;
+        }
+    }
+}
+
+struct BnPlan { int nblk; int rows_per_block; };
+
+BnPlan plan_rows(long long m, int c)
+{
+    const RowMap rm = make_rowmap(c);
+    // at least 8 row iterations per thread, at most kMaxBlocks workgroups
+    long long rows = (long long)rm.rows_par * 8;
+    long long nblk = (m + rows - 1) / rows;
+    if (nblk > kMaxBlocks) {
+        rows = (m + kMaxBlocks - 1) / kMaxBlocks;
+        rows = (rows + rm.rows_par - 1) / rm.rows_par * rm.rows_par;
+        nblk = (m + rows - 1) / rows;
+    }
+    BnPlan p;
+    p.nblk = (int)nblk;
+    p.rows_per_block = (int)rows;
+    return p;
+}
+
+int validate(const bn_desc* d)
+{
+    RN50_REQUIRE_PTR(d);
+    if (d->dt != RN50_F16) return RN50_ERR_DTYPE;
+    if (d->m < 1 || d->c < 8 || d->c % 8 != 0 || d->m > (1ll << 40)) return RN50_ERR_SHAPE;
+    const int gp = d->c / 8;
+    if (!(kThreads % gp == 0 || gp % kThreads == 0)) return RN50_ERR_SHAPE;
+    return RN50_OK;
+}
+
+}  // namespace
+
+extern "C" size_t bn_workspace_bytes(const bn_desc* d)
+{
+    if (validate(d) != RN50_OK) return 0;
+    // partials of up to kMaxBlocks workgroups (2 rows of c floats each) + 2c floats of totals
+    return ((size_t)kMaxBlocks * 2 * d->c + 2 * (size_t)d->c) * sizeof(float);
+}
+
+// Internal entry points, also used by the whole-step driver.
+int rn50_bn_fwd_launch(long long m, int c, float eps, bool relu, const h16* x, const float* gamma, const float* beta,
+                       const h16* res, h16* y, float* save_mean, float* save_invstd, float* ws, hipStream_t s)
+{
+    const BnPlan p = plan_rows(m, c);
+    bn_stats_kernel<<<p.nblk, kThreads, 0, s>>>(m, c, x, ws, p.rows_per_block);
+    bn_stats_finalize_kernel<<<rn50_cdiv(c, 16), kThreads, 0, s>>>(m, c, eps, p.nblk, x, ws, save_mean, save_invstd);
+#define RN50_BN_APPLY(R, Z) bn_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, x, gamma, beta, save_mean, \
+                                                                              save_invstd, res, y, p.rows_per_block)
+    if (relu) { if (res) RN50_BN_APPLY(true, true); else RN50_BN_APPLY(true, false); }
+    else      { if (res) RN50_BN_APPLY(false, true); else RN50_BN_APPLY(false, false); }
+#undef RN50_BN_APPLY
+    return rn50_check_launch();
+}
+
+int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* x, const h16* y, const float* gamma,
+                       const float* save_mean, const float* save_invstd, h16* dx, h16* dres, h16* dgamma, h16* dbeta,
+                       float* ws, hipStream_t s)
+{
+    const BnPlan p = plan_rows(m, c);
+    float* sums = ws + (size_t)kMaxBlocks * 2 * c;
+    if (relu) bn_bwd_reduce_kernel<true><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, save_mean, save_invstd, ws, p.rows_per_block);
+    else      bn_bwd_reduce_kernel<false><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, save_mean, save_invstd, ws, p.rows_per_block);
+    bn_bwd_finalize_kernel<<<rn50_cdiv(c, 16), kThreads, 0, s>>>(c, p.nblk, ws, sums, dgamma, dbeta);
+#define RN50_BN_BWD(R, Z) bn_bwd_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, gamma, save_mean, \
+                                                                                save_invstd, sums, dx, dres, p.rows_per_block)
+    if (relu) { if (dres) RN50_BN_BWD(true, true); else RN50_BN_BWD(true, false); }
+    else      { if (dres) RN50_BN_BWD(false, true); else RN50_BN_BWD(false, false); }
+#undef RN50_BN_BWD
+    return rn50_check_launch();
+}
+
+extern "C" int bn_relu_fwd(const bn_desc* d, const void* x, const float* gamma, const float* beta,
+                           const void* residual, void* y, float* save_mean, float* save_invstd,
+                           void* ws, size_t ws_bytes, void* stream)
+{
+    RN50_TRY(validate(d));
+    RN50_REQUIRE_PTR(x); RN50_REQUIRE_PTR(gamma); RN50_REQUIRE_PTR(beta); RN50_REQUIRE_PTR(y);
+    RN50_REQUIRE_PTR(save_mean); RN50_REQUIRE_PTR(save_invstd);
+    if (d->has_residual) RN50_REQUIRE_PTR(residual);
+    if (!ws || ws_bytes < bn_workspace_bytes(d)) return RN50_ERR_WORKSPACE;
+    RN50_REQUIRE_ALIGNED(x); RN50_REQUIRE_ALIGNED(y); RN50_REQUIRE_ALIGNED(residual); RN50_REQUIRE_ALIGNED(ws);
+    return rn50_bn_fwd_launch(d->m, d->c, d->eps, d->relu != 0, static_cast<const h16*>(x), gamma, beta,
+                              d->has_residual ? static_cast<const h16*>(residual) : nullptr, static_cast<h16*>(y),
+                              save_mean, save_invstd, static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+}
+
+extern "C" int bn_relu_bwd(const bn_desc* d, const void* dy, const void* x, const void* y, const float* gamma,
+                           const float* save_mean, const float* save_invstd, void* dx, void* dresidual,
+                           void* dgamma, void* dbeta, void* ws, size_t ws_bytes, void* stream)
+{
+    RN50_TRY(validate(d));
+    RN50_REQUIRE_PTR(dy); RN50_REQUIRE_PTR(x); RN50_REQUIRE_PTR(gamma); RN50_REQUIRE_PTR(save_mean);
+    RN50_REQUIRE_PTR(save_invstd); RN50_REQUIRE_PTR(dx); RN50_REQUIRE_PTR(dgamma); RN50_REQUIRE_PTR(dbeta);
+    if (d->relu) RN50_REQUIRE_PTR(y);
+    if (d->has_residual) RN50_REQUIRE_PTR(dresidual);
+    if (!ws || ws_bytes < bn_workspace_bytes(d)) return RN50_ERR_WORKSPACE;
+    RN50_REQUIRE_ALIGNED(dy); RN50_REQUIRE_ALIGNED(x); RN50_REQUIRE_ALIGNED(y); RN50_REQUIRE_ALIGNED(dx);
+    RN50_REQUIRE_ALIGNED(dresidual); RN50_REQUIRE_ALIGNED(ws);
+    return rn50_bn_bwd_launch(d->m, d->c, d->relu != 0, static_cast<const h16*>(dy), static_cast<const h16*>(x),
+                              static_cast<const h16*>(y), gamma, save_mean, save_invstd, static_cast<h16*>(dx),
+                              d->has_residual ? static_cast<h16*>(dresidual) : nullptr, static_cast<h16*>(dgamma),
+                              static_cast<h16*>(dbeta), static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+}

@@ -1,0 +1,198 @@
+"""GPU parity: sgd_momentum_flat, ls_xent_fwd_bwd, bn_relu_fwd/bwd against the CPU oracle.
+
+Tolerances: 1e-5 relative for the FP32 loss and update, 2e-2 (relative to
+max(|ref|, 1e-2*max|ref|)) for FP16 tensors; saved BN statistics 1e-4."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import oracle as O                                   # noqa: E402
+import paper_1811_05233_amd as P                     # noqa: E402
+from paper_1811_05233_amd import synth               # noqa: E402
+from gpu_util import DEV, dev_f, dev_h, dev_i, host, rel_err, rel_err_fp32   # noqa: E402
+
+TOL16, TOL32 = 2e-2, 1e-5
+
+
+def _progress(msg):
+    print("[case] " + msg, flush=True)
+
+
+# ------------------------------------------------------------------ sgd
+@pytest.mark.parametrize("n", [0, 1, 7, 8, 1000, 4099, 262144 * 8 + 3])
+def test_sgd_small_and_ragged(n):
+    _progress("sgd n=%d" % n)
+    g = synth.normal_f16(400, (n,), 1e-3)
+    w0 = synth.normal_f32(401, (n,), 0.05)
+    v0 = synth.normal_f32(402, (n,), 0.01)
+    lr, mu, wd, s = 0.1, 0.9, 1e-4, 1.0 / 54000
+    gd, wd_, vd = dev_h(g), dev_f(w0), dev_f(v0)
+    lo = torch.zeros(max(n, 1), dtype=torch.float16, device=DEV)
+    P.sgd_momentum_flat(n, gd, s, wd_, vd, lo, lr, mu, wd)
+    w, v = w0.astype(np.float64), v0.astype(np.float64)
+    low = O.sgd_momentum_flat(g.astype(np.float64), w, v, lr, mu, wd, s)
+    if n:
+        assert rel_err_fp32(host(wd_), w, 1e-3) <= TOL32 and rel_err_fp32(host(vd), v, 1e-3) <= TOL32
+        # the half copy is decided from the FP32 weight: compare with the rounding of the GPU's own FP32 result
+        assert np.array_equal(host(lo)[:n], O.round_binary16(host(wd_)))
+        assert rel_err(host(lo)[:n], low) <= 2e-3
+
+
+def test_sgd_full_size_100_steps():
+    """Flat 25,557,032-element tail, 100 steps on the same gradient; parity after steps 1, 2, 100.
+
+    Against the FP32 oracle (the paper's optimizer precision, same operation order) the result
+    must be bit-identical; against the FP64 oracle within 1e-5 (elements that cancel to less
+    than 1e-3 of the largest weight are measured against that floor)."""
+    n = 25557032
+    _progress("sgd full n=%d" % n)
+    g = synth.normal_f16(400, (n,), 1e-3)
+    w0 = synth.normal_f32(401, (n,), 0.05)
+    lr, mu, wd, s = 0.1, 0.9, 1e-4, 1.0 / 54000
+    gd, wdv, vd = dev_h(g), dev_f(w0), torch.zeros(n, dtype=torch.float32, device=DEV)
+    lo = torch.empty(n, dtype=torch.float16, device=DEV)
+    w, v = w0.astype(np.float32), np.zeros(n, np.float32)
+    w64, v64 = w0.astype(np.float64), np.zeros(n, np.float64)
+    g32, g64 = g.astype(np.float32), g.astype(np.float64)
+    for step in range(1, 101):
+        P.sgd_momentum_flat(n, gd, s, wdv, vd, lo, lr, mu, wd)
+        O.sgd_momentum_flat(g32, w, v, np.float32(lr), np.float32(mu), np.float32(wd), np.float32(s), want_lowp=False)
+        if step <= 2:
+            O.sgd_momentum_flat(g64, w64, v64, float(np.float32(lr)), float(np.float32(mu)), float(np.float32(wd)),
+                                float(np.float32(s)), want_lowp=False)
+        if step in (1, 2, 100):
+            gw, gv = host(wdv), host(vd)
+            _progress("sgd step %d: max|w-w_fp32oracle| = %.3e" % (step, np.max(np.abs(gw - w))))
+            assert np.array_equal(gw, w.astype(np.float64)) and np.array_equal(gv, v.astype(np.float64))
+            if step <= 2:
+                assert rel_err_fp32(gw, w64, 1e-3) <= TOL32 and rel_err_fp32(gv, v64, 1e-3) <= TOL32
+    assert np.array_equal(host(lo), O.round_binary16(host(wdv)))
+
+
+def test_sgd_no_lowp_and_errors():
+    n = 1024
+    g, w, v = dev_h(np.ones(n)), dev_f(np.ones(n)), dev_f(np.zeros(n))
+    P.sgd_momentum_flat(n, g, 1.0, w, v, None, 0.5, 0.0, 0.0)
+    assert np.allclose(host(w), 0.5)
+    with pytest.raises(P.Rn50Error):
+        P.sgd_momentum_flat(n, None, 1.0, w, v, None, 0.5, 0.0, 0.0)
+    with pytest.raises(P.Rn50Error):
+        P.sgd_momentum_flat(n, g, 1.0, w, v, None, 0.5, 0.0, 0.0, grad_dt=P.RN50_BF16)
+
+
+# ------------------------------------------------------------------ loss
+@pytest.mark.parametrize("batch,classes", [(1, 2), (2, 10), (32, 1000), (16, 1000), (128, 1000), (37, 1001), (3, 4096)])
+def test_ls_xent(batch, classes):
+    _progress("ls_xent batch=%d classes=%d" % (batch, classes))
+    z = synth.normal_f32(500 + batch, (batch, classes), 3.0)
+    lab = synth.labels(501 + batch, batch, classes)
+    scale = 128.0 / batch
+    zd, ld = dev_f(z), dev_i(lab)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    per = torch.zeros(batch, dtype=torch.float32, device=DEV)
+    dz = torch.zeros(batch, classes, dtype=torch.float16, device=DEV)
+    P.ls_xent_fwd_bwd(batch, classes, zd, ld, 0.1, scale, loss, per, dz)
+    rl, rper, rdz = O.ls_xent_fwd_bwd(z.astype(np.float64), lab, 0.1, scale)
+    assert rel_err_fp32(host(loss), [rl]) <= TOL32
+    assert rel_err_fp32(host(per), rper) <= TOL32
+    assert rel_err(host(dz), rdz) <= TOL16
+    # deterministic, and loss_per_sample may be NULL
+    loss2 = torch.zeros(1, dtype=torch.float32, device=DEV)
+    P.ls_xent_fwd_bwd(batch, classes, zd, ld, 0.1, scale, loss2, None, dz)
+    assert host(loss2)[0] == host(loss)[0]
+
+
+def test_ls_xent_closed_forms_on_gpu():
+    k = 1000
+    z = dev_f(np.full((32, k), 0.37))
+    lab = dev_i(synth.labels(7, 32, k))
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    dz = torch.zeros(32, k, dtype=torch.float16, device=DEV)
+    P.ls_xent_fwd_bwd(32, k, z, lab, 0.1, 1.0, loss, None, dz)
+    assert abs(host(loss)[0] - np.log(k)) <= TOL32 * np.log(k)
+    big = dev_f(synth.normal_f32(8, (32, k), 3000.0))           # no overflow with huge logits
+    P.ls_xent_fwd_bwd(32, k, big, lab, 0.1, 1.0, loss, None, dz)
+    assert np.isfinite(host(loss)[0]) and np.all(np.isfinite(host(dz)))
+    with pytest.raises(P.Rn50Error):
+        P.ls_xent_fwd_bwd(0, k, z, lab, 0.1, 1.0, loss, None, dz)
+
+
+# ------------------------------------------------------------------ batch norm
+BN_CASES = [  # m, c, relu, residual
+    (1, 8, True, False), (50, 8, False, False), (2 * 56 * 56, 64, True, False), (2 * 56 * 56, 256, True, True),
+    (2 * 56 * 56 + 5, 256, False, False), (3 * 7 * 7, 2048, True, True), (1000, 512, True, False),
+    (3001, 128, True, True), (77, 4096, True, False), (4 * 112 * 112, 64, True, False)]
+
+
+@pytest.mark.parametrize("m,c,relu,res", BN_CASES)
+def test_bn_relu_fwd_bwd(m, c, relu, res):
+    _progress("bn m=%d c=%d relu=%d res=%d" % (m, c, relu, res))
+    x = synth.normal_f16(600, (m, c)) * 1.5
+    x = (x + synth.normal_f32(601, (c,), 0.7)).astype(np.float16).astype(np.float32)
+    gamma = 1.0 + synth.normal_f32(602, (c,), 0.2)
+    beta = synth.normal_f32(603, (c,), 0.3)
+    r = synth.normal_f16(604, (m, c)) if res else None
+    dy = synth.normal_f16(605, (m, c), 0.05)
+    d = P.make_bn_desc(m, c, 1e-5, relu, res)
+    xd, gd, bd = dev_h(x), dev_f(gamma), dev_f(beta)
+    rd = dev_h(r) if res else None
+    y = torch.zeros(m, c, dtype=torch.float16, device=DEV)
+    mean = torch.zeros(c, dtype=torch.float32, device=DEV)
+    invstd = torch.zeros(c, dtype=torch.float32, device=DEV)
+    P.bn_relu_fwd(d, xd, gd, bd, rd, y, mean, invstd)
+    f64 = np.float64
+    ry, rmean, rinv, _ = O.bn_relu_fwd(x.astype(f64), gamma.astype(f64), beta.astype(f64), 1e-5, relu,
+                                       r.astype(f64) if res else None)
+    if m > 1:
+        assert rel_err_fp32(host(invstd), rinv) <= 1e-4
+    assert np.max(np.abs(host(mean) - rmean)) <= 1e-5 * max(1.0, np.max(np.abs(rmean)))
+    assert rel_err(host(y), ry) <= TOL16
+    # backward, fed with the oracle's (rounded) forward output and statistics
+    y16 = O.round_binary16(ry)
+    yd = dev_h(y16)
+    dx = torch.zeros(m, c, dtype=torch.float16, device=DEV)
+    dres = torch.zeros(m, c, dtype=torch.float16, device=DEV) if res else None
+    dg = torch.zeros(c, dtype=torch.float16, device=DEV)
+    db = torch.zeros(c, dtype=torch.float16, device=DEV)
+    P.bn_relu_bwd(d, dev_h(dy), xd, yd if relu else None, gd, dev_f(rmean), dev_f(rinv), dx, dres, dg, db)
+    rdx, rdres, rdg, rdb = O.bn_relu_bwd(dy.astype(f64), x.astype(f64), y16, gamma.astype(f64),
+                                         rmean.astype(np.float32).astype(f64), rinv.astype(np.float32).astype(f64),
+                                         relu, res)
+    assert rel_err(host(dx), rdx) <= TOL16
+    assert rel_err(host(dg), rdg) <= TOL16 and rel_err(host(db), rdb) <= TOL16
+    if res:
+        assert np.array_equal(host(dres), rdres)          # pure masking of FP16 values: exact
+
+
+def test_bn_large_mean_channel_and_determinism():
+    m, c = 5000, 64
+    x = synth.normal_f16(610, (m, c))
+    x[:, 3] = (100.0 + x[:, 3]).astype(np.float16).astype(np.float32)     # mean = 100 sigma
+    d = P.make_bn_desc(m, c, 1e-5, True, False)
+    xd = dev_h(x)
+    g, b = dev_f(np.ones(c)), dev_f(np.zeros(c))
+    outs = []
+    for _ in range(2):
+        y = torch.zeros(m, c, dtype=torch.float16, device=DEV)
+        mean = torch.zeros(c, dtype=torch.float32, device=DEV)
+        invstd = torch.zeros(c, dtype=torch.float32, device=DEV)
+        P.bn_relu_fwd(d, xd, g, b, None, y, mean, invstd)
+        outs.append((host(y), host(mean), host(invstd)))
+    assert all(np.array_equal(a, b_) for a, b_ in zip(outs[0], outs[1]))
+    _, rmean, rinv, _ = O.bn_relu_fwd(x.astype(np.float64), np.ones(c), np.zeros(c), 1e-5, True)
+    assert rel_err_fp32(outs[0][2], rinv) <= 1e-4
+    # mean: absolute error measured against the channel's scale (sigma = 1 here, or |mean| if larger)
+    assert np.max(np.abs(outs[0][1] - rmean) / np.maximum(np.abs(rmean), 1.0)) <= 1e-5
+
+
+def test_bn_error_paths():
+    d = P.make_bn_desc(10, 12)                      # c not a multiple of 8
+    t = torch.zeros(256, dtype=torch.float16, device=DEV)
+    f = torch.zeros(64, dtype=torch.float32, device=DEV)
+    with pytest.raises(P.Rn50Error):
+        P.bn_relu_fwd(d, t, f, f, None, t, f, f, ws=torch.zeros(1 << 20, dtype=torch.uint8, device=DEV))
+    d = P.make_bn_desc(10, 16)
+    with pytest.raises(P.Rn50Error):                # workspace too small
+        P.bn_relu_fwd(d, t, f, f, None, t, f, f, ws=torch.zeros(16, dtype=torch.uint8, device=DEV))
