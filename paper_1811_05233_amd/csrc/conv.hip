@@ -1,0 +1,732 @@
+// Convolution forward / data-gradient / filter-gradient as implicit GEMM on the gfx950 matrix
+// cores (v_mfma_f32_32x32x16_f16: FP16 operands, FP32 accumulation), LDS-staged NHWC tiles.
+//
+// Forward and data-gradient share one "gather GEMM":
+//     out[m, j] = sum_{tap} sum_{c < CR} A[pixel(m, tap), c] * B[j, tap, c]
+// where m enumerates output pixels, A is an NHWC tensor whose pixel rows are gathered with zero
+// fill outside the image, and B is [NO][T][CR] (reduction index contiguous).
+//   forward:        A = x,  B = w (KRSC as given),        pixel = (n, p*stride - pad + r, q*stride - pad + s)
+//   data-gradient:  A = dy, B = w transposed to CRSK,     pixel = (n, (h + pad - r)/stride, (w + pad - s)/stride)
+// For stride 2 the data-gradient rows are split into the four (h%2, w%2) parity classes; each
+// class only visits the filter taps that can reach it, so no multiply hits an inserted zero.
+//
+// The filter gradient reduces over pixels, which is the strided dimension of both operands; its
+// loader transposes 8x8 half blocks in registers on the way into LDS, after which the same MFMA
+// loop applies.  The pixel range is split over workgroups and combined with FP32 atomic adds.
+#include "common.h"
+#include "conv_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ int xcd_remap(int bid, int nblk) {
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give each XCD a
+    // contiguous range of logical tiles so that tiles sharing operands share an L2.
+    const int full = nblk & ~7;
+    if (bid >= full) return bid;
+    return (bid & 7) * (full >> 3) + (bid >> 3);
+}
+
+// LDS tile of ROWS rows x KW halfs (KW = 32, 64 or 128), addressed in 16-byte chunks with an XOR
+// swizzle that keeps both the row-wise MFMA operand reads and the transposing writes conflict-free.
+template <int KW>
+__device__ __forceinline__ int lds_off(int row, int chunk) {
+    const int sw = (row ^ (row >> 3)) & 7;
+    if (KW == 32) {
+        // two rows share a 128-byte line
+        const int line = row >> 1;
+        const int slot = ((row & 1) << 2) | ((chunk ^ (line & 3)) & 3);
+        return line * 64 + slot * 8;
+    }
+    return row * KW + ((chunk ^ sw)) * 8;   // XOR touches only the low 3 bits of the chunk index
+}
+
+// ------------------------------------------------------------------------------------------------
+// gather GEMM (forward, data-gradient)
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int BK, int WR, int WC>
+__global__ __launch_bounds__(kThreads) void gather_gemm_kernel(const GatherArgs a)
+{
+    constexpr int CPR = BK / 8;            // 16-byte chunks per tile row
+    constexpr int RPP = kThreads / CPR;    // tile rows covered by one pass of the workgroup
+    constexpr int NA = BM / RPP, NB = BN / RPP;
+    constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
+    constexpr int KS = BK / 16;
+    constexpr int STAGE = (BM + BN) * BK;
+    constexpr int EP = BN + 8;             // epilogue row pitch in halfs
+    constexpr int LDS_HALFS = (2 * STAGE > BM * EP) ? 2 * STAGE : BM * EP;
+    __shared__ __attribute__((aligned(16))) h16 lds[LDS_HALFS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lg = lane >> 5;
+    const int wm0 = (wave / WC) * WM, wn0 = (wave % WC) * WN;
+
+    // ---- which tile ----
+    const int bid = xcd_remap(blockIdx.x, gridDim.x);
+    const int n_tiles = a.NO / BN;
+    const int nt = bid % n_tiles;
+    int mt = bid / n_tiles;
+    int cls = 0;
+    while (cls < a.ncls - 1 && mt >= a.mt_end[cls]) ++cls;
+    if (cls > 0) mt -= a.mt_end[cls - 1];
+    const int OHs = a.cOHs[cls], OWs = a.cOWs[cls];
+    const int M = a.NB * OHs * OWs;
+    const int ntaps = a.ntaps[cls];
+
+    // ---- per-thread load coordinates ----
+    const int chunk = tid % CPR, rowl = tid / CPR;
+    int a_h0[NA], a_w0[NA], a_nb[NA];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int m = mt * BM + rowl + i * RPP;
+        if (m < M) {
+            const int wq = m % OWs, t = m / OWs;
+            const int hq = t % OHs, n = t / OHs;
+            a_h0[i] = hq * a.a_mul + a.a_off;
+            a_w0[i] = wq * a.a_mul + a.a_off;
+            a_nb[i] = n * a.IH * a.IW;
+        } else {
+            a_h0[i] = -(1 << 20); a_w0[i] = 0; a_nb[i] = 0;
+        }
+    }
+    const h16* b_base = a.B + ((size_t)(nt * BN + rowl) * a.T) * a.CR + chunk * 8;
+    const size_t b_rowstep = (size_t)RPP * a.T * a.CR;
+
+    f32x16 acc[TM][TN];
+    if (a.addend) {
+        // accumulators start from the addend (out = addend + A*B, rounded once)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int m = mt * BM + wm0 + tm * 32 + li;
+            size_t opix = 0;
+            const bool ok = m < M;
+            if (ok) {
+                const int wq = m % OWs, t = m / OWs;
+                const int hq = t % OHs, n = t / OHs;
+                opix = ((size_t)n * a.OH + hq * a.o_mul + a.oph[cls]) * a.OW + wq * a.o_mul + a.opw[cls];
+            }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    h16x4 v = {0, 0, 0, 0};
+                    if (ok) v = *reinterpret_cast<const h16x4*>(a.addend + opix * a.NO + nt * BN + wn0 + tn * 32 + q * 8 + lg * 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[tm][tn][q * 4 + e] = (float)v[e];
+                }
+        }
+    } else {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+    }
+
+    const int KC = a.CR / BK;
+    const int kiters = ntaps * KC;
+    h16x8 ra[NA], rb[NB];
+
+    auto load_tile = [&](int kit) {
+        const int ti = kit / KC, cc = kit - ti * KC;
+        const int dh = a.dh[cls][ti], dw = a.dw[cls][ti], bt = a.bt[cls][ti];
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int ih = a_h0[i] + dh, iw = a_w0[i] + dw;
+            h16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+            if ((unsigned)ih < (unsigned)a.IH && (unsigned)iw < (unsigned)a.IW)
+                v = *reinterpret_cast<const h16x8*>(a.A + (size_t)(a_nb[i] + ih * a.IW + iw) * a.lda + cc * BK + chunk * 8);
+            ra[i] = v;
+        }
+        const h16* bp = b_base + (size_t)bt * a.CR + cc * BK;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) rb[i] = *reinterpret_cast<const h16x8*>(bp + i * b_rowstep);
+    };
+    auto store_tile = [&](int stage) {
+        h16* sa = lds + stage * STAGE;
+        h16* sb = sa + BM * BK;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<h16x8*>(sa + lds_off<BK>(rowl + i * RPP, chunk)) = ra[i];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) *reinterpret_cast<h16x8*>(sb + lds_off<BK>(rowl + i * RPP, chunk)) = rb[i];
+    };
+
+    if (kiters > 0) {
+        load_tile(0);
+        store_tile(0);
+    }
+    __syncthreads();
+    for (int kit = 0; kit < kiters; ++kit) {
+        const int cur = kit & 1;
+        if (kit + 1 < kiters) load_tile(kit + 1);
+        const h16* sa = lds + cur * STAGE;
+        const h16* sb = sa + BM * BK;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            h16x8 fa[TM], fb[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                fa[tm] = *reinterpret_cast<const h16x8*>(sa + lds_off<BK>(wm0 + tm * 32 + li, ks * 2 + lg));
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                fb[tn] = *reinterpret_cast<const h16x8*>(sb + lds_off<BK>(wn0 + tn * 32 + li, ks * 2 + lg));
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    // operands swapped: the accumulator holds out^T, i.e. every lane owns one pixel
+                    // (lane%32) and runs of 4 consecutive output channels
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[tn], fa[tm], acc[tm][tn], 0, 0, 0);
+        }
+        if (kit + 1 < kiters) store_tile(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: FP32 -> half, through LDS so that global stores are full 16-byte rows ----
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                h16x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = (h16)acc[tm][tn][q * 4 + e];
+                *reinterpret_cast<h16x4*>(lds + (wm0 + tm * 32 + li) * EP + wn0 + tn * 32 + q * 8 + lg * 4) = v;
+            }
+    __syncthreads();
+    constexpr int OCPR = BN / 8;                 // output chunks per row
+    constexpr int ORPP = kThreads / OCPR;
+    const int oc = tid % OCPR, orl = tid / OCPR;
+#pragma unroll
+    for (int i = 0; i < BM / ORPP; ++i) {
+        const int row = orl + i * ORPP;
+        const int m = mt * BM + row;
+        if (m < M) {
+            const int wq = m % OWs, t = m / OWs;
+            const int hq = t % OHs, n = t / OHs;
+            const size_t opix = ((size_t)n * a.OH + hq * a.o_mul + a.oph[cls]) * a.OW + wq * a.o_mul + a.opw[cls];
+            *reinterpret_cast<h16x8*>(a.out + opix * a.NO + nt * BN + oc * 8) =
+                *reinterpret_cast<const h16x8*>(lds + row * EP + oc * 8);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// filter gradient
+// ------------------------------------------------------------------------------------------------
+// acc[k][g][c] += sum_{pix in this split} dy[pix][k] * X[pix, g][c], g = granule of G columns.
+// Regular mode (G = 64): granule = (tap, 64-channel slab of x).  Stem mode (G = 32): granule = filter
+// row r; the 32 columns are the 8 consecutive padded-image pixels x 4 channels starting at column 2q.
+template <int BM, int BN, int BKP, int G, bool kStem>
+__global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a)
+{
+    constexpr int CPR = BKP / 8;
+    constexpr int STAGE = (BM + BN) * BKP;
+    constexpr int WR = 2, WC = 2;
+    constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
+    constexpr int KS = BKP / 16;
+    static_assert((BM + BN) * (BKP / 8) / 8 == kThreads, "one 8x8 micro-block per thread");
+    __shared__ __attribute__((aligned(16))) h16 lds[2 * STAGE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lg = lane >> 5;
+    const int wm0 = (wave / WC) * WM, wn0 = (wave % WC) * WN;
+
+    const int m_tiles = a.K / BM, n_tiles = a.NG * G / BN;
+    int bid = blockIdx.x;
+    const int nt = bid % n_tiles; bid /= n_tiles;
+    const int mt = bid % m_tiles;
+    const int split = bid / m_tiles;
+    const long long pix_begin = (long long)split * a.pix_per_split;
+    long long pix_end = pix_begin + a.pix_per_split;
+    if (pix_end > a.npix) pix_end = a.npix;
+
+    // ---- loader role: micro-blocks [0, BM/8 * CPR) belong to dy, the rest to x ----
+    constexpr int DY_MB = (BM / 8) * CPR;
+    const bool is_dy = tid < DY_MB;
+    const int mb = is_dy ? tid : tid - DY_MB;
+    const int groups = is_dy ? BM / 8 : BN / 8;
+    const int cg = mb % groups;          // 8-column group inside the tile (fast index: coalesced)
+    const int pg = mb / groups;          // 8-pixel group inside the K-slab
+    // x side: granule and column offset
+    const int gran = nt * (BN / G) + (cg * 8) / G;
+    const int gcol = (cg * 8) % G;
+    int tap_r = 0, tap_s = 0, c0 = 0;
+    bool gran_ok = true;
+    if (!is_dy) {
+        if (kStem) { tap_r = gran; gran_ok = gran < a.R; }
+        else {
+            const int gpt = a.C / G;     // granules per tap
+            const int tap = gran / gpt;
+            tap_r = tap / a.S; tap_s = tap % a.S;
+            c0 = (gran % gpt) * G + gcol;
+        }
+    }
+    const h16* dy_ptr = a.dy + (size_t)(mt * BM + cg * 8);
+    const bool direct = a.direct != 0;   // 1x1 stride 1: x pixel index == dy pixel index
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+    h16x8 r[8];
+    auto load_mb = [&](long long pix0) {
+        const long long p0 = pix0 + pg * 8;
+        if (is_dy) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                h16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (p0 + j < pix_end) v = *reinterpret_cast<const h16x8*>(dy_ptr + (size_t)(p0 + j) * a.K);
+                r[j] = v;
+            }
+        } else if (direct) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                h16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (p0 + j < pix_end) v = *reinterpret_cast<const h16x8*>(a.x + (size_t)(p0 + j) * a.C + c0);
+                r[j] = v;
+            }
+        } else {
+            int q = (int)(p0 % a.Q);
+            long long t = p0 / a.Q;
+            int p = (int)(t % a.P);
+            int n = (int)(t / a.P);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                h16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (p0 + j < pix_end && gran_ok) {
+                    if (kStem) {
+                        // padded image: always in bounds
+                        v = *reinterpret_cast<const h16x8*>(
+                            a.x + (((size_t)n * a.H + 2 * p + tap_r) * a.W + 2 * q) * 4 + gcol);
+                    } else {
+                        const int ih = p * a.stride - a.pad + tap_r, iw = q * a.stride - a.pad + tap_s;
+                        if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
+                            v = *reinterpret_cast<const h16x8*>(a.x + (((size_t)n * a.H + ih) * a.W + iw) * a.C + c0);
+                    }
+                }
+                r[j] = v;
+                if (++q == a.Q) { q = 0; if (++p == a.P) { p = 0; ++n; } }
+            }
+        }
+    };
+    auto store_mb = [&](int stage) {
+        h16* base = lds + stage * STAGE + (is_dy ? 0 : BM * BKP);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            h16x8 o;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = r[j][e];     // 8x8 transpose in registers
+            *reinterpret_cast<h16x8*>(base + lds_off<BKP>(cg * 8 + e, pg)) = o;
+        }
+    };
+
+    const int kiters = (int)((pix_end - pix_begin + BKP - 1) / BKP);
+    if (kiters > 0) { load_mb(pix_begin); store_mb(0); }
+    __syncthreads();
+    for (int kit = 0; kit < kiters; ++kit) {
+        const int cur = kit & 1;
+        if (kit + 1 < kiters) load_mb(pix_begin + (long long)(kit + 1) * BKP);
+        const h16* sa = lds + cur * STAGE;
+        const h16* sb = sa + BM * BKP;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            h16x8 fa[TM], fb[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                fa[tm] = *reinterpret_cast<const h16x8*>(sa + lds_off<BKP>(wm0 + tm * 32 + li, ks * 2 + lg));
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                fb[tn] = *reinterpret_cast<const h16x8*>(sb + lds_off<BKP>(wn0 + tn * 32 + li, ks * 2 + lg));
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[tm], fb[tn], acc[tm][tn], 0, 0, 0);
+        }
+        if (kit + 1 < kiters) store_mb(cur ^ 1);
+        __syncthreads();
+    }
+    if (kiters == 0) return;
+
+    // ---- accumulate into the FP32 buffer: lane owns column li, rows 8*(v/4) + 4*lg + v%4 ----
+    const int row_len = a.NG * G;      // columns per output row
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int col = nt * BN + wn0 + tn * 32 + li;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = mt * BM + wm0 + tm * 32 + (v / 4) * 8 + lg * 4 + (v % 4);
+                atomicAdd(a.acc + (size_t)row * row_len + col, acc[tm][tn][v]);
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------------
+// small helpers: fills, casts, weight re-layouts, stem image staging
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(f32x4* p, size_t n4)
+{
+    const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kThreads) p[i] = z;
+}
+
+__global__ __launch_bounds__(kThreads) void cast_f32_to_h16_kernel(const float* __restrict__ src, h16* __restrict__ dst, size_t n)
+{
+    const size_t n8 = n / 8;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n8; i += (size_t)gridDim.x * kThreads) {
+        const f32x4 u = reinterpret_cast<const f32x4*>(src)[2 * i], w = reinterpret_cast<const f32x4*>(src)[2 * i + 1];
+        h16x8 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { o[j] = (h16)u[j]; o[4 + j] = (h16)w[j]; }
+        reinterpret_cast<h16x8*>(dst)[i] = o;
+    }
+    const size_t t = n8 * 8 + (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t < n) dst[t] = (h16)src[t];
+}
+
+// KRSC -> CRSK for one filter: dst[c][t][k] = src[k][t][c].  32x32 tiles through LDS.
+__global__ __launch_bounds__(kThreads) void transpose_filter_kernel(const h16* __restrict__ src, h16* __restrict__ dst,
+                                                                    int K, int T, int C)
+{
+    __shared__ h16 tile[32][33];
+    const int tiles_c = C / 32, tiles_k = K / 32;
+    int b = blockIdx.x;
+    const int tc = b % tiles_c; b /= tiles_c;
+    const int tk = b % tiles_k;
+    const int t = b / tiles_k;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int k = tk * 32 + ty + i * 8, c = tc * 32 + tx;
+        tile[ty + i * 8][tx] = src[((size_t)k * T + t) * C + c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = tc * 32 + ty + i * 8, k = tk * 32 + tx;
+        dst[((size_t)c * T + t) * K + k] = tile[tx][ty + i * 8];
+    }
+}
+
+// stem: images [N,H,W,3] -> zero-padded [N,H+6,W+6,4] (3 pixels of padding on every side, 4th channel 0)
+__global__ __launch_bounds__(kThreads) void stem_pad_image_kernel(const h16* __restrict__ img, h16* __restrict__ dst,
+                                                                  int N, int H, int W)
+{
+    const int HP = H + 6, WP = W + 6;
+    const size_t total = (size_t)N * HP * WP;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+        const int wp = (int)(i % WP);
+        const size_t t = i / WP;
+        const int hp = (int)(t % HP), n = (int)(t / HP);
+        const int h = hp - 3, w = wp - 3;
+        h16x4 v = {0, 0, 0, 0};
+        if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) {
+            const h16* s = img + (((size_t)n * H + h) * W + w) * 3;
+            v[0] = s[0]; v[1] = s[1]; v[2] = s[2];
+        }
+        reinterpret_cast<h16x4*>(dst)[i] = v;
+    }
+}
+
+// stem filter [K][7][7][3] -> [K][7][32]: column s*4+c, zero for s = 7 or c = 3
+__global__ __launch_bounds__(kThreads) void stem_pack_filter_kernel(const h16* __restrict__ w, h16* __restrict__ dst, int K)
+{
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= K * 7 * 32) return;
+    const int col = i % 32, r = (i / 32) % 7, k = i / (32 * 7);
+    const int s = col / 4, c = col % 4;
+    dst[i] = (s < 7 && c < 3) ? w[(((size_t)k * 7 + r) * 7 + s) * 3 + c] : (h16)0.f;
+}
+
+// stem filter gradient: acc [K][8][32] (row r, column s*4+c) -> out [K][7][7][3] (FP32)
+__global__ __launch_bounds__(kThreads) void stem_unpack_wgrad_kernel(const float* __restrict__ acc, float* __restrict__ out, int K)
+{
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= K * 147) return;
+    const int c = i % 3, s = (i / 3) % 7, r = (i / 21) % 7, k = i / 147;
+    out[i] = acc[((size_t)k * 8 + r) * 32 + s * 4 + c];
+}
+
+int grid_for(size_t work_items)
+{
+    size_t b = (work_items + kThreads - 1) / kThreads;
+    if (b > 256 * 8) b = 256 * 8;
+    return b < 1 ? 1 : (int)b;
+}
+
+inline int floordiv(int a, int b) { return (a >= 0) ? a / b : -((-a + b - 1) / b); }
+
+template <int BM, int BN, int BK, int WR, int WC>
+int launch_gather(GatherArgs& a, hipStream_t s)
+{
+    int total = 0;
+    for (int c = 0; c < a.ncls; ++c) {
+        const long long M = (long long)a.NB * a.cOHs[c] * a.cOWs[c];
+        total += (int)((M + BM - 1) / BM);
+        a.mt_end[c] = total;
+    }
+    if (total == 0) return RN50_OK;
+    const int grid = total * (a.NO / BN);
+    gather_gemm_kernel<BM, BN, BK, WR, WC><<<grid, kThreads, 0, s>>>(a);
+    return rn50_check_launch();
+}
+
+int dispatch_gather(GatherArgs& a, hipStream_t s)
+{
+    if (a.CR == 32) {               // stem forward
+        return launch_gather<128, 64, 32, 2, 2>(a, s);
+    }
+    if (a.NO % 128 == 0) return launch_gather<128, 128, 64, 2, 2>(a, s);
+    return launch_gather<128, 64, 64, 2, 2>(a, s);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// internal entry points (also used by the whole-step driver)
+// ------------------------------------------------------------------------------------------------
+bool rn50_conv_is_stem(const conv_desc& d) { return d.c == 3 && d.r == 7 && d.s == 7 && d.stride == 2 && d.pad == 3; }
+
+int rn50_conv_validate(const conv_desc* d)
+{
+    if (!d) return RN50_ERR_NULL;
+    if (d->dt != RN50_F16) return RN50_ERR_DTYPE;
+    if (d->n < 1 || d->h < 1 || d->w < 1 || d->k < 64 || d->k % 64 != 0) return RN50_ERR_SHAPE;
+    if ((long long)d->n * d->h * d->w * (d->c > d->k ? d->c : d->k) >= (1ll << 31)) return RN50_ERR_SHAPE;
+    if (rn50_conv_is_stem(*d)) return (d->h % 2 == 0 && d->w % 2 == 0) ? RN50_OK : RN50_ERR_SHAPE;
+    if (d->c < 64 || d->c % 64 != 0) return RN50_ERR_SHAPE;
+    if (d->r != d->s || (d->r != 1 && d->r != 3)) return RN50_ERR_SHAPE;
+    if (d->stride != 1 && d->stride != 2) return RN50_ERR_SHAPE;
+    if (d->pad != (d->r - 1) / 2) return RN50_ERR_SHAPE;
+    if (d->h + 2 * d->pad < d->r || d->w + 2 * d->pad < d->s) return RN50_ERR_SHAPE;
+    return RN50_OK;
+}
+
+static inline int out_dim(int h, int pad, int r, int stride) { return (h + 2 * pad - r) / stride + 1; }
+
+size_t rn50_stem_padded_bytes(const conv_desc& d) { return rn50_round_up((size_t)d.n * (d.h + 6) * (d.w + 6) * 4 * sizeof(h16), 256); }
+size_t rn50_stem_packed_filter_bytes(const conv_desc& d) { return rn50_round_up((size_t)d.k * 7 * 32 * sizeof(h16), 256); }
+
+int rn50_stem_pad_image(const conv_desc& d, const h16* img, h16* padded, hipStream_t s)
+{
+    stem_pad_image_kernel<<<grid_for((size_t)d.n * (d.h + 6) * (d.w + 6)), kThreads, 0, s>>>(img, padded, d.n, d.h, d.w);
+    return rn50_check_launch();
+}
+
+int rn50_stem_pack_filter(const conv_desc& d, const h16* w, h16* packed, hipStream_t s)
+{
+    stem_pack_filter_kernel<<<rn50_cdiv(d.k * 7 * 32, kThreads), kThreads, 0, s>>>(w, packed, d.k);
+    return rn50_check_launch();
+}
+
+int rn50_transpose_filter(const conv_desc& d, const h16* w, h16* wt, hipStream_t s)
+{
+    const int T = d.r * d.s;
+    transpose_filter_kernel<<<(d.c / 32) * (d.k / 32) * T, kThreads, 0, s>>>(w, wt, d.k, T, d.c);
+    return rn50_check_launch();
+}
+
+int rn50_fill_zero(float* p, size_t n, hipStream_t s)
+{
+    // n must be a multiple of 4 floats
+    fill_zero_kernel<<<grid_for(n / 4), kThreads, 0, s>>>(reinterpret_cast<f32x4*>(p), n / 4);
+    return rn50_check_launch();
+}
+
+int rn50_cast_f32_to_h16(const float* src, h16* dst, size_t n, hipStream_t s)
+{
+    cast_f32_to_h16_kernel<<<grid_for(n / 8 + 1), kThreads, 0, s>>>(src, dst, n);
+    return rn50_check_launch();
+}
+
+// Forward.  For the stem, x is the padded 4-channel image and w the packed filter.
+int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y, hipStream_t s)
+{
+    GatherArgs a = {};
+    const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
+    a.A = x; a.B = w; a.out = y; a.addend = nullptr;
+    a.NB = d.n; a.NO = d.k; a.OH = P; a.OW = Q; a.o_mul = 1;
+    a.ncls = 1; a.cOHs[0] = P; a.cOWs[0] = Q; a.oph[0] = 0; a.opw[0] = 0;
+    a.a_mul = d.stride;
+    if (rn50_conv_is_stem(d)) {
+        a.IH = d.h + 6; a.IW = d.w + 6; a.lda = 4; a.CR = 32; a.T = 7; a.a_off = 0;
+        a.ntaps[0] = 7;
+        for (int r = 0; r < 7; ++r) { a.dh[0][r] = (signed char)r; a.dw[0][r] = 0; a.bt[0][r] = (signed char)r; }
+    } else {
+        a.IH = d.h; a.IW = d.w; a.lda = d.c; a.CR = d.c; a.T = d.r * d.s; a.a_off = 0;
+        a.ntaps[0] = d.r * d.s;
+        for (int r = 0; r < d.r; ++r)
+            for (int q = 0; q < d.s; ++q) {
+                const int t = r * d.s + q;
+                a.dh[0][t] = (signed char)(r - d.pad); a.dw[0][t] = (signed char)(q - d.pad); a.bt[0][t] = (signed char)t;
+            }
+    }
+    return dispatch_gather(a, s);
+}
+
+// Data gradient.  wt is the filter transposed to [C][R][S][K].  addend (nullable) has dx's layout.
+int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s)
+{
+    GatherArgs a = {};
+    const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
+    a.A = dy; a.B = wt; a.out = dx; a.addend = addend;
+    a.NB = d.n; a.IH = P; a.IW = Q; a.lda = d.k; a.CR = d.k; a.T = d.r * d.s; a.NO = d.c;
+    a.OH = d.h; a.OW = d.w; a.a_mul = 1; a.a_off = 0; a.o_mul = d.stride;
+    a.ncls = d.stride * d.stride;
+    for (int ph = 0; ph < d.stride; ++ph)
+        for (int pw = 0; pw < d.stride; ++pw) {
+            const int c = ph * d.stride + pw;
+            a.oph[c] = ph; a.opw[c] = pw;
+            a.cOHs[c] = (d.h - ph + d.stride - 1) / d.stride;
+            a.cOWs[c] = (d.w - pw + d.stride - 1) / d.stride;
+            int nt = 0;
+            for (int r = 0; r < d.r; ++r) {
+                const int eh = ph + d.pad - r;
+                if (((eh % d.stride) + d.stride) % d.stride != 0) continue;
+                for (int q = 0; q < d.s; ++q) {
+                    const int ew = pw + d.pad - q;
+                    if (((ew % d.stride) + d.stride) % d.stride != 0) continue;
+                    a.dh[c][nt] = (signed char)floordiv(eh, d.stride);
+                    a.dw[c][nt] = (signed char)floordiv(ew, d.stride);
+                    a.bt[c][nt] = (signed char)(r * d.s + q);
+                    ++nt;
+                }
+            }
+            a.ntaps[c] = nt;
+        }
+    return dispatch_gather(a, s);
+}
+
+size_t rn50_wgrad_acc_floats(const conv_desc& d)
+{
+    if (rn50_conv_is_stem(d)) return (size_t)d.k * 8 * 32;
+    return (size_t)d.k * d.r * d.s * d.c;
+}
+
+// Filter gradient into a zero-initialised FP32 accumulator (layout [K][R][S][C]; stem: [K][8][32]).
+// For the stem, x is the padded 4-channel image.
+int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* acc, hipStream_t s)
+{
+    WgradArgs a = {};
+    const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
+    a.x = x; a.dy = dy; a.acc = acc;
+    a.K = d.k; a.P = P; a.Q = Q; a.npix = (long long)d.n * P * Q;
+    a.stride = d.stride; a.pad = d.pad; a.R = d.r; a.S = d.s;
+    const bool stem = rn50_conv_is_stem(d);
+    int BM, BN, BKP, G;
+    if (stem) { a.H = d.h + 6; a.W = d.w + 6; a.C = 4; a.NG = 8; a.direct = 0; BM = 64; BN = 64; BKP = 128; G = 32; }
+    else {
+        a.H = d.h; a.W = d.w; a.C = d.c; a.direct = (d.r == 1 && d.stride == 1) ? 1 : 0;
+        a.NG = d.r * d.s * d.c / 64; G = 64;
+        if (d.k % 128 == 0 && a.NG % 2 == 0) { BM = 128; BN = 128; BKP = 64; }
+        else { BM = 64; BN = 64; BKP = 128; }
+    }
+    const int tiles = (d.k / BM) * (a.NG * G / BN);
+    // enough pixel splits to fill the machine (~4 workgroups per compute unit), each a multiple of the K-slab
+    long long slabs = (a.npix + BKP - 1) / BKP;
+    long long want = (1024 + tiles - 1) / tiles;
+    if (want > slabs) want = slabs;
+    if (want < 1) want = 1;
+    const long long slabs_per = (slabs + want - 1) / want;
+    a.pix_per_split = slabs_per * BKP;
+    const int nsplit = (int)((slabs + slabs_per - 1) / slabs_per);
+    const int grid = tiles * nsplit;
+    if (stem) wgrad_kernel<64, 64, 128, 32, true><<<grid, kThreads, 0, s>>>(a);
+    else if (BM == 128) wgrad_kernel<128, 128, 64, 64, false><<<grid, kThreads, 0, s>>>(a);
+    else wgrad_kernel<64, 64, 128, 64, false><<<grid, kThreads, 0, s>>>(a);
+    return rn50_check_launch();
+}
+
+int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, float* out, hipStream_t s)
+{
+    stem_unpack_wgrad_kernel<<<rn50_cdiv(d.k * 147, kThreads), kThreads, 0, s>>>(acc, out, d.k);
+    return rn50_check_launch();
+}
+
+// ------------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------------
+extern "C" size_t conv_workspace_bytes(const conv_desc* d, int which)
+{
+    if (rn50_conv_validate(d) != RN50_OK) return 0;
+    const bool stem = rn50_conv_is_stem(*d);
+    switch (which) {
+        case RN50_CONV_FWD:
+            return stem ? rn50_stem_padded_bytes(*d) + rn50_stem_packed_filter_bytes(*d) : 0;
+        case RN50_CONV_DGRAD:
+            return stem ? 0 : rn50_round_up((size_t)d->k * d->r * d->s * d->c * sizeof(h16), 256);
+        case RN50_CONV_WGRAD: {
+            size_t b = rn50_round_up(rn50_wgrad_acc_floats(*d) * sizeof(float), 256);
+            if (stem) b += rn50_stem_padded_bytes(*d) + rn50_round_up((size_t)d->k * 147 * sizeof(float), 256);
+            return b;
+        }
+        default: return 0;
+    }
+}
+
+static int check_common(const conv_desc* d, const void* p0, const void* p1, const void* p2, void* ws, size_t ws_bytes, int which)
+{
+    RN50_TRY(rn50_conv_validate(d));
+    RN50_REQUIRE_PTR(p0); RN50_REQUIRE_PTR(p1); RN50_REQUIRE_PTR(p2);
+    const size_t need = conv_workspace_bytes(d, which);
+    if (need > 0 && (!ws || ws_bytes < need)) return RN50_ERR_WORKSPACE;
+    RN50_REQUIRE_ALIGNED(p0); RN50_REQUIRE_ALIGNED(p1); RN50_REQUIRE_ALIGNED(p2); RN50_REQUIRE_ALIGNED(ws);
+    return RN50_OK;
+}
+
+extern "C" int conv_fwd(const conv_desc* d, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, void* stream)
+{
+    RN50_TRY(check_common(d, x, w, y, ws, ws_bytes, RN50_CONV_FWD));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (rn50_conv_is_stem(*d)) {
+        h16* padded = static_cast<h16*>(ws);
+        h16* packed = reinterpret_cast<h16*>(static_cast<char*>(ws) + rn50_stem_padded_bytes(*d));
+        RN50_TRY(rn50_stem_pad_image(*d, static_cast<const h16*>(x), padded, s));
+        RN50_TRY(rn50_stem_pack_filter(*d, static_cast<const h16*>(w), packed, s));
+        return rn50_conv_fwd_launch(*d, padded, packed, static_cast<h16*>(y), s);
+    }
+    return rn50_conv_fwd_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(w), static_cast<h16*>(y), s);
+}
+
+extern "C" int conv_dgrad(const conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, void* stream)
+{
+    RN50_TRY(rn50_conv_validate(d));
+    if (rn50_conv_is_stem(*d)) return RN50_ERR_SHAPE;   // the images need no gradient
+    RN50_TRY(check_common(d, dy, w, dx, ws, ws_bytes, RN50_CONV_DGRAD));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    h16* wt = static_cast<h16*>(ws);
+    RN50_TRY(rn50_transpose_filter(*d, static_cast<const h16*>(w), wt, s));
+    return rn50_conv_dgrad_launch(*d, static_cast<const h16*>(dy), wt, nullptr, static_cast<h16*>(dx), s);
+}
+
+extern "C" int conv_wgrad(const conv_desc* d, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes, void* stream)
+{
+    RN50_TRY(check_common(d, x, dy, dw, ws, ws_bytes, RN50_CONV_WGRAD));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* acc = static_cast<float*>(ws);
+    const size_t acc_floats = rn50_wgrad_acc_floats(*d);
+    RN50_TRY(rn50_fill_zero(acc, acc_floats, s));
+    if (rn50_conv_is_stem(*d)) {
+        char* p = static_cast<char*>(ws) + rn50_round_up(acc_floats * sizeof(float), 256);
+        h16* padded = reinterpret_cast<h16*>(p);
+        float* unpacked = reinterpret_cast<float*>(p + rn50_stem_padded_bytes(*d));
+        RN50_TRY(rn50_stem_pad_image(*d, static_cast<const h16*>(x), padded, s));
+        RN50_TRY(rn50_conv_wgrad_launch(*d, padded, static_cast<const h16*>(dy), acc, s));
+        RN50_TRY(rn50_stem_unpack_wgrad(*d, acc, unpacked, s));
+        return rn50_cast_f32_to_h16(unpacked, static_cast<h16*>(dw), (size_t)d->k * 147, s);
+    }
+    RN50_TRY(rn50_conv_wgrad_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(dy), acc, s));
+    return rn50_cast_f32_to_h16(acc, static_cast<h16*>(dw), acc_floats, s);
+}

@@ -1,0 +1,55 @@
+// Kernel argument blocks and internal launchers of the convolution kernels.
+#pragma once
+#include "common.h"
+
+struct GatherArgs {
+    const h16* A;        // gathered NHWC tensor
+    const h16* B;        // [NO][T][CR]
+    h16* out;            // NHWC output, NO channels
+    const h16* addend;   // nullable, same layout as out
+    int NB;              // images
+    int IH, IW;          // spatial size of A
+    int lda;             // halfs between adjacent pixels of A
+    int CR;              // reduction length per tap
+    int T;               // taps in B's layout
+    int NO;              // output channels
+    int OH, OW;          // spatial size of out
+    int a_mul, a_off;    // A coordinate = sub-grid coordinate * a_mul + a_off + tap offset
+    int o_mul;           // out coordinate = sub-grid coordinate * o_mul + class offset
+    int ncls;            // 1, or stride^2 parity classes for the strided data gradient
+    int cOHs[4], cOWs[4];
+    int oph[4], opw[4];
+    int mt_end[4];       // running end of each class's row tiles (filled by the launcher)
+    int ntaps[4];
+    signed char dh[4][9], dw[4][9], bt[4][9];
+};
+
+struct WgradArgs {
+    const h16* x;
+    const h16* dy;
+    float* acc;          // [K][NG*G] FP32, accumulated with atomics
+    int K;               // output channels (row length of dy)
+    int C;               // input channels (row length of x; 4 for the padded stem image)
+    int H, W;            // spatial size of x (padded size for the stem)
+    int P, Q;            // spatial size of dy
+    int R, S, stride, pad;
+    int NG;              // granules per output row
+    int direct;          // 1x1 stride 1: x pixel index == dy pixel index
+    long long npix;      // N*P*Q
+    long long pix_per_split;
+};
+
+bool rn50_conv_is_stem(const conv_desc& d);
+int rn50_conv_validate(const conv_desc* d);
+size_t rn50_stem_padded_bytes(const conv_desc& d);
+size_t rn50_stem_packed_filter_bytes(const conv_desc& d);
+int rn50_stem_pad_image(const conv_desc& d, const h16* img, h16* padded, hipStream_t s);
+int rn50_stem_pack_filter(const conv_desc& d, const h16* w, h16* packed, hipStream_t s);
+int rn50_transpose_filter(const conv_desc& d, const h16* w, h16* wt, hipStream_t s);
+int rn50_fill_zero(float* p, size_t n, hipStream_t s);
+int rn50_cast_f32_to_h16(const float* src, h16* dst, size_t n, hipStream_t s);
+int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y, hipStream_t s);
+int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s);
+size_t rn50_wgrad_acc_floats(const conv_desc& d);
+int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* acc, hipStream_t s);
+int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, float* out, hipStream_t s);
