@@ -162,6 +162,8 @@ typedef struct {
     float bn_eps;
     float ls_eps;
     float loss_scale; /* dlogits = loss_scale*(p-q)/batch; the update multiplies by grad_scale */
+    int keep_grads;   /* 0: activation gradients live in a few rotating buffers.  1: every one keeps its
+                         own buffer (larger workspace) and rn50_tensor can return it; for checking. */
 } rn50_config;
 
 typedef struct { float lr, momentum, wd, grad_scale; } rn50_hparams;
@@ -195,8 +197,11 @@ int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* labels,
 
 /* Device address of a tensor the last rn50_step left in the workspace, for parity checks.
  * name: "<conv>.conv" (conv output), "<conv>.out" (BN output), "<conv>.mean",
- * "<conv>.invstd", "pool.out", "feat", "logits", "dlogits"; <conv> = "stem" or
- * "s<stage>b<block>{c1,c2,c3,p}" (stage from 1).  *elems = element count,
+ * "<conv>.invstd", "pool.out", "feat", "logits", "dlogits"; with keep_grads also
+ * "<conv>.dconv" (gradient w.r.t. the conv output), "<conv>.din" (w.r.t. its input; for conv1
+ * it includes the shortcut's share), "<conv3>.dres" (masked gradient given to the shortcut),
+ * "head.din" (w.r.t. the last block's output), "pool.din" (w.r.t. the stem's BN output);
+ * <conv> = "stem" or "s<stage>b<block>{c1,c2,c3,p}" (stage from 1).  *elems = element count,
  * *elem_bytes = 2 or 4.  Unknown name: RN50_ERR_SHAPE. */
 int rn50_tensor(rn50_ctx* ctx, const char* name, void** ptr, size_t* elems, int* elem_bytes);
 

@@ -86,27 +86,22 @@ class Net:
         return flat[s.offset:s.offset + s.count].reshape(s.shape)
 
 
-def step_ref(net, images, labels, master_w, momentum, lr, mu, wd, ls_eps=0.1, bn_eps=1e-5,
-             loss_scale=1.0, lowp=True, dtype=np.float64, update=True):
-    """One training iteration.  images NHWC, labels int, master_w/momentum flat arrays.
-
-    Returns a dict with every stored tensor ('t'), the loss, the flat gradient
-    (scaled by loss_scale, rounded to binary16 in lowp mode) and the updated
-    w / v / w_lowp.  Inputs are not modified.
-    """
-    dt = dtype
+def _make_ctx(net, master_w, lowp, dtype):
     st = (lambda a: O.round_binary16(a)) if lowp else (lambda a: a)
-    w_master = np.asarray(master_w, dt)
+    w_master = np.asarray(master_w, dtype)
     w_fwd = st(w_master)                     # FP16 copy used by conv / FC weights
-    t = {}
-    grad = np.zeros(net.param_count, dt)
 
     def P(name, low=True):
         return net.view(w_fwd if low else w_master, name)
+    return st, w_master, P
 
-    def G(name, val):
-        s = net.seg[name]
-        grad[s.offset:s.offset + s.count] = st(np.asarray(val, dt)).reshape(-1)
+
+def forward_ref(net, images, master_w, bn_eps=1e-5, lowp=True, dtype=np.float64):
+    """Forward pass.  Returns the dict t of every stored tensor:
+    '<conv>.in', '<conv>.conv', '<conv>.out', '<conv>.mean', '<conv>.invstd', 'pool.out',
+    '<block>.in', 'feat', 'logits'."""
+    st, _, P = _make_ctx(net, master_w, lowp, dtype)
+    t = {}
 
     def conv_bn_fwd(name, x, relu, residual=None):
         cv = net.convs[name]
@@ -118,6 +113,36 @@ def step_ref(net, images, labels, master_w, momentum, lr, mu, wd, ls_eps=0.1, bn
         y = st(y)
         t[name + ".mean"], t[name + ".invstd"], t[name + ".out"] = mean, invstd, y
         return y
+
+    x = st(np.asarray(images, dtype))
+    if net.has_stem:
+        y = conv_bn_fwd("stem", x, True)
+        x = st(O.maxpool_fwd(y, 3, 2, 1))
+        t["pool.out"] = x
+    for b in net.block_list:
+        n = b["name"]
+        t[n + ".in"] = x
+        a = conv_bn_fwd(n + "c1", x, True)
+        a = conv_bn_fwd(n + "c2", a, True)
+        sc = conv_bn_fwd(n + "p", x, False) if b["proj"] else x
+        x = conv_bn_fwd(n + "c3", a, True, residual=sc)
+    feat = st(O.avgpool_fwd(x))
+    t["feat"] = feat
+    t["logits"] = O.fc_fwd(feat, P("fc.w"), P("fc.b", False))
+    return t
+
+
+def backward_ref(net, t, labels, master_w, ls_eps=0.1, loss_scale=1.0, lowp=True, dtype=np.float64):
+    """Loss and backward pass from a dict t of forward tensors (forward_ref's own, or tensors
+    produced elsewhere with the same names: '<conv>.in' may be omitted for convs whose input is a
+    block input, in which case '<block>.in' is used).  Adds '<conv>.dconv', '<block>.dout',
+    'dlogits', 'pool.dout' to t.  Returns loss, loss_per_sample, flat gradient."""
+    st, _, P = _make_ctx(net, master_w, lowp, dtype)
+    grad = np.zeros(net.param_count, dtype)
+
+    def G(name, val):
+        s = net.seg[name]
+        grad[s.offset:s.offset + s.count] = st(np.asarray(val, dtype)).reshape(-1)
 
     def conv_bn_bwd(name, dy, relu, want_dres, need_dx=True):
         cv = net.convs[name]
@@ -134,34 +159,17 @@ def step_ref(net, images, labels, master_w, momentum, lr, mu, wd, ls_eps=0.1, bn
         dx = O.conv_dgrad(dc, P(name + ".w"), x.shape, cv["stride"], cv["pad"]) if need_dx else None
         return dx, dres
 
-    # ---------------- forward ----------------
-    x = st(np.asarray(images, dt))
-    if net.has_stem:
-        y = conv_bn_fwd("stem", x, True)
-        x = st(O.maxpool_fwd(y, 3, 2, 1))
-        t["pool.out"] = x
-    for b in net.block_list:
-        n = b["name"]
-        t[n + ".in"] = x
-        a = conv_bn_fwd(n + "c1", x, True)
-        a = conv_bn_fwd(n + "c2", a, True)
-        sc = conv_bn_fwd(n + "p", x, False) if b["proj"] else x
-        x = conv_bn_fwd(n + "c3", a, True, residual=sc)
-    feat = st(O.avgpool_fwd(x))
-    t["feat"] = feat
-    logits = O.fc_fwd(feat, P("fc.w"), P("fc.b", False))
-    t["logits"] = logits
+    logits, feat = t["logits"], t["feat"]
     bsz = logits.shape[0]
     loss, per, dz = O.ls_xent_fwd_bwd(logits, labels, ls_eps, loss_scale / bsz)
     dz = st(dz)
     t["dlogits"] = dz
-
-    # ---------------- backward ----------------
     dwt, db, da = O.fc_bwd(feat, P("fc.w"), dz)
     G("fc.w", dwt)
     G("fc.b", db)
     da = st(da)
-    dx = st(O.avgpool_bwd(da, x.shape[1:3]))
+    last = net.block_list[-1]["name"] + "c3"
+    dx = st(O.avgpool_bwd(da, t[last + ".out"].shape[1:3]))
     first = net.block_list[0]["name"]
     for b in reversed(net.block_list):
         n = b["name"]
@@ -179,11 +187,23 @@ def step_ref(net, images, labels, master_w, momentum, lr, mu, wd, ls_eps=0.1, bn
         t["pool.dout"] = dx
         dstem = st(O.maxpool_bwd(t["stem.out"], dx, 3, 2, 1))
         conv_bn_bwd("stem", dstem, True, False, need_dx=False)
+    return loss, per, grad
 
+
+def step_ref(net, images, labels, master_w, momentum, lr, mu, wd, ls_eps=0.1, bn_eps=1e-5,
+             loss_scale=1.0, lowp=True, dtype=np.float64, update=True):
+    """One training iteration.  images NHWC, labels int, master_w/momentum flat arrays.
+
+    Returns a dict with every stored tensor ('t'), the loss, the flat gradient
+    (scaled by loss_scale, rounded to binary16 in lowp mode) and the updated
+    w / v / w_lowp.  Inputs are not modified.
+    """
+    t = forward_ref(net, images, master_w, bn_eps, lowp, dtype)
+    loss, per, grad = backward_ref(net, t, labels, master_w, ls_eps, loss_scale, lowp, dtype)
     out = dict(t=t, loss=loss, loss_per_sample=per, grad=grad)
     if update:
-        w_new = w_master.copy()
-        v_new = np.asarray(momentum, dt).copy()
+        w_new = np.asarray(master_w, dtype).copy()
+        v_new = np.asarray(momentum, dtype).copy()
         out["w_lowp"] = O.sgd_momentum_flat(grad, w_new, v_new, lr, mu, wd, 1.0 / loss_scale)
         out["w"], out["v"] = w_new, v_new
     return out

@@ -33,7 +33,8 @@ class rn50_config(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int), ("image_h", ctypes.c_int), ("image_w", ctypes.c_int),
                 ("has_stem", ctypes.c_int), ("num_stages", ctypes.c_int), ("blocks", ctypes.c_int * 4),
                 ("base_width", ctypes.c_int), ("classes", ctypes.c_int), ("dt", ctypes.c_int),
-                ("bn_eps", ctypes.c_float), ("ls_eps", ctypes.c_float), ("loss_scale", ctypes.c_float)]
+                ("bn_eps", ctypes.c_float), ("ls_eps", ctypes.c_float), ("loss_scale", ctypes.c_float),
+                ("keep_grads", ctypes.c_int)]
 
 
 class rn50_hparams(ctypes.Structure):
@@ -183,10 +184,10 @@ def rn50_cast_params(n, master_w, w_lowp, dt=RN50_F16):
 
 # ------------------------------------------------------------------ whole step
 def make_config(batch, image_hw=(224, 224), has_stem=True, blocks=(3, 4, 6, 3), base_width=64, classes=1000,
-                bn_eps=1e-5, ls_eps=0.1, loss_scale=1.0, dt=RN50_F16):
+                bn_eps=1e-5, ls_eps=0.1, loss_scale=1.0, dt=RN50_F16, keep_grads=False):
     b = (ctypes.c_int * 4)(*(list(blocks) + [0] * (4 - len(blocks))))
     return rn50_config(batch, image_hw[0], image_hw[1], int(has_stem), len(blocks), b, base_width, classes, dt,
-                       bn_eps, ls_eps, loss_scale)
+                       bn_eps, ls_eps, loss_scale, int(keep_grads))
 
 
 def rn50_param_count(cfg):

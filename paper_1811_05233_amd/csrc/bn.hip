@@ -8,6 +8,7 @@
 // The forward statistics are accumulated around a per-channel pivot (row 0) so that
 // E[x^2]-E[x]^2 does not cancel when |mean| >> sigma.
 #include "common.h"
+#include "misc_internal.h"
 
 namespace {
 
@@ -204,7 +205,9 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(long long m, in
 // sums[0..c) = dbeta, sums[c..2c) = dgamma (float, kept for the apply pass); also the half copies.
 __global__ __launch_bounds__(kThreads) void bn_bwd_finalize_kernel(int c, int nblk, const float* __restrict__ part,
                                                                    float* __restrict__ sums,
-                                                                   h16* __restrict__ dgamma, h16* __restrict__ dbeta)
+                                                                   h16* __restrict__ dgamma, h16* __restrict__ dbeta,
+                                                                   float* __restrict__ dgamma32,
+                                                                   float* __restrict__ dbeta32)
 {
     __shared__ double s1[kThreads], s2[kThreads];
     const int tid = threadIdx.x;
@@ -222,8 +225,10 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_finalize_kernel(int c, int nb
         for (int k = 1; k < 16; ++k) { a += s1[k * 16 + cl]; b += s2[k * 16 + cl]; }
         sums[ch] = (float)a;
         sums[c + ch] = (float)b;
-        dbeta[ch] = (h16)(float)a;
-        dgamma[ch] = (h16)(float)b;
+        if (dbeta) dbeta[ch] = (h16)(float)a;
+        if (dgamma) dgamma[ch] = (h16)(float)b;
+        if (dbeta32) dbeta32[ch] = (float)a;
+        if (dgamma32) dgamma32[ch] = (float)b;
     }
 }
 
@@ -306,11 +311,13 @@ int validate(const bn_desc* d)
 
 }  // namespace
 
+// partials of up to kMaxBlocks workgroups (2 rows of c floats each) + 2c floats of totals
+size_t rn50_bn_ws_floats(int c) { return (size_t)kMaxBlocks * 2 * c + 2 * (size_t)c; }
+
 extern "C" size_t bn_workspace_bytes(const bn_desc* d)
 {
     if (validate(d) != RN50_OK) return 0;
-    // partials of up to kMaxBlocks workgroups (2 rows of c floats each) + 2c floats of totals
-    return ((size_t)kMaxBlocks * 2 * d->c + 2 * (size_t)d->c) * sizeof(float);
+    return rn50_bn_ws_floats(d->c) * sizeof(float);
 }
 
 // Internal entry points, also used by the whole-step driver.
@@ -329,14 +336,14 @@ int rn50_bn_fwd_launch(long long m, int c, float eps, bool relu, const h16* x, c
 }
 
 int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* x, const h16* y, const float* gamma,
-                       const float* save_mean, const float* save_invstd, h16* dx, h16* dres, h16* dgamma, h16* dbeta,
-                       float* ws, hipStream_t s)
+                       const float* save_mean, const float* save_invstd, h16* dx, h16* dres,
+                       h16* dgamma, h16* dbeta, float* dgamma32, float* dbeta32, float* ws, hipStream_t s)
 {
     const BnPlan p = plan_rows(m, c);
     float* sums = ws + (size_t)kMaxBlocks * 2 * c;
     if (relu) bn_bwd_reduce_kernel<true><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, save_mean, save_invstd, ws, p.rows_per_block);
     else      bn_bwd_reduce_kernel<false><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, save_mean, save_invstd, ws, p.rows_per_block);
-    bn_bwd_finalize_kernel<<<rn50_cdiv(c, 16), kThreads, 0, s>>>(c, p.nblk, ws, sums, dgamma, dbeta);
+    bn_bwd_finalize_kernel<<<rn50_cdiv(c, 16), kThreads, 0, s>>>(c, p.nblk, ws, sums, dgamma, dbeta, dgamma32, dbeta32);
 #define RN50_BN_BWD(R, Z) bn_bwd_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, gamma, save_mean, \
                                                                                 save_invstd, sums, dx, dres, p.rows_per_block)
     if (relu) { if (dres) RN50_BN_BWD(true, true); else RN50_BN_BWD(true, false); }
@@ -375,5 +382,6 @@ extern "C" int bn_relu_bwd(const bn_desc* d, const void* dy, const void* x, cons
     return rn50_bn_bwd_launch(d->m, d->c, d->relu != 0, static_cast<const h16*>(dy), static_cast<const h16*>(x),
                               static_cast<const h16*>(y), gamma, save_mean, save_invstd, static_cast<h16*>(dx),
                               d->has_residual ? static_cast<h16*>(dresidual) : nullptr, static_cast<h16*>(dgamma),
-                              static_cast<h16*>(dbeta), static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+                              static_cast<h16*>(dbeta), nullptr, nullptr, static_cast<float*>(ws),
+                              static_cast<hipStream_t>(stream));
 }

@@ -1,0 +1,18 @@
+// Internal launchers: pooling, FC, batch norm (used by the whole-step driver).
+#pragma once
+#include "common.h"
+
+int rn50_maxpool_fwd(int N, int H, int W, int C, const h16* x, h16* y, uint8_t* arg, hipStream_t s);
+int rn50_maxpool_bwd(int N, int H, int W, int C, const h16* dy, const uint8_t* arg, h16* dx, hipStream_t s);
+int rn50_avgpool_fwd(int N, int HW, int C, const h16* x, h16* y, hipStream_t s);
+int rn50_fc_fwd(int B, int Cin, int Cout, const h16* a, const h16* Wt, const float* bias, float* z, hipStream_t s);
+int rn50_fc_bwd(int B, int Cin, int Cout, int HW, const h16* a, const h16* Wt, const h16* dz, float* dWt, float* db,
+                h16* dx, hipStream_t s);
+
+int rn50_bn_fwd_launch(long long m, int c, float eps, bool relu, const h16* x, const float* gamma, const float* beta,
+                       const h16* res, h16* y, float* save_mean, float* save_invstd, float* ws, hipStream_t s);
+// dgamma/dbeta are written as half to dgamma16/dbeta16 (if non-null) and as float to dgamma32/dbeta32 (if non-null)
+int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* x, const h16* y, const float* gamma,
+                       const float* save_mean, const float* save_invstd, h16* dx, h16* dres,
+                       h16* dgamma16, h16* dbeta16, float* dgamma32, float* dbeta32, float* ws, hipStream_t s);
+size_t rn50_bn_ws_floats(int c);

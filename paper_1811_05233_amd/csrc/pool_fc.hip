@@ -1,0 +1,238 @@
+// Max-pool 3x3/2, global average pool and the fully connected layer (forward and backward).
+// All of them are small next to the convolutions; they are written for coalesced 16-byte
+// accesses on NHWC data (a thread owns 8 consecutive channels).
+#include "common.h"
+#include "misc_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// y = max over the 3x3 window (stride 2, pad 1); padding never wins.  arg = index (r*3+s) of the
+// FIRST maximum in row-major window order, kept for the backward pass.
+__global__ __launch_bounds__(kThreads) void maxpool_fwd_kernel(int N, int H, int W, int C, int P, int Q,
+                                                               const h16* __restrict__ x, h16* __restrict__ y,
+                                                               uint8_t* __restrict__ arg)
+{
+    const int G = C / 8;
+    const size_t total = (size_t)N * P * Q * G;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+        const int g = (int)(i % G);
+        size_t t = i / G;
+        const int q = (int)(t % Q); t /= Q;
+        const int p = (int)(t % P);
+        const int n = (int)(t / P);
+        h16x8 best;
+        uint8_t bi[8];
+        bool have = false;
+        for (int r = 0; r < 3; ++r) {
+            const int ih = 2 * p - 1 + r;
+            if ((unsigned)ih >= (unsigned)H) continue;
+            for (int s = 0; s < 3; ++s) {
+                const int iw = 2 * q - 1 + s;
+                if ((unsigned)iw >= (unsigned)W) continue;
+                const h16x8 v = *reinterpret_cast<const h16x8*>(x + (((size_t)n * H + ih) * W + iw) * C + g * 8);
+                if (!have) {
+                    best = v;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) bi[j] = (uint8_t)(r * 3 + s);
+                    have = true;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (v[j] > best[j]) { best[j] = v[j]; bi[j] = (uint8_t)(r * 3 + s); }
+                }
+            }
+        }
+        *reinterpret_cast<h16x8*>(y + i * 8) = best;
+        uint2 packed;
+        packed.x = bi[0] | (bi[1] << 8) | (bi[2] << 16) | ((uint32_t)bi[3] << 24);
+        packed.y = bi[4] | (bi[5] << 8) | (bi[6] << 16) | ((uint32_t)bi[7] << 24);
+        *reinterpret_cast<uint2*>(arg + i * 8) = packed;
+    }
+}
+
+// dx[n,h,w,c] = sum of dy over the (at most 4) windows whose recorded first maximum is (h,w).
+__global__ __launch_bounds__(kThreads) void maxpool_bwd_kernel(int N, int H, int W, int C, int P, int Q,
+                                                               const h16* __restrict__ dy,
+                                                               const uint8_t* __restrict__ arg, h16* __restrict__ dx)
+{
+    const int G = C / 8;
+    const size_t total = (size_t)N * H * W * G;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
+        const int g = (int)(i % G);
+        size_t t = i / G;
+        const int w = (int)(t % W); t /= W;
+        const int h = (int)(t % H);
+        const int n = (int)(t / H);
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int p = h / 2; p <= (h + 1) / 2; ++p) {        // windows with 2p-1 <= h <= 2p+1
+            if (p >= P) continue;
+            const int r = h - (2 * p - 1);
+            for (int q = w / 2; q <= (w + 1) / 2; ++q) {
+                if (q >= Q) continue;
+                const int s = w - (2 * q - 1);
+                const size_t o = (((size_t)n * P + p) * Q + q) * C + g * 8;
+                const uint2 packed = *reinterpret_cast<const uint2*>(arg + o);
+                const h16x8 d = *reinterpret_cast<const h16x8*>(dy + o);
+                const uint32_t me = (uint32_t)(r * 3 + s);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t a = ((j < 4 ? packed.x : packed.y) >> ((j & 3) * 8)) & 0xffu;
+                    if (a == me) acc[j] += (float)d[j];
+                }
+            }
+        }
+        h16x8 o;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = (h16)acc[j];
+        *reinterpret_cast<h16x8*>(dx + i * 8) = o;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void avgpool_fwd_kernel(int N, int HW, int C, const h16* __restrict__ x,
+                                                               h16* __restrict__ y)
+{
+    const int G = C / 8;
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N * G) return;
+    const int g = i % G, n = i / G;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < HW; ++k) {
+        const h16x8 v = *reinterpret_cast<const h16x8*>(x + ((size_t)n * HW + k) * C + g * 8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += (float)v[j];
+    }
+    h16x8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (h16)(acc[j] / (float)HW);
+    *reinterpret_cast<h16x8*>(y + (size_t)i * 8) = o;
+}
+
+// z[i,j] = sum_c a[i,c]*Wt[j,c] + b[j]; one wavefront per output column j, the row of Wt stays
+// in registers while the wave walks the batch.  Cin must be a multiple of 8.
+__global__ __launch_bounds__(kThreads) void fc_fwd_kernel(int B, int Cin, int Cout, const h16* __restrict__ a,
+                                                          const h16* __restrict__ Wt, const float* __restrict__ bias,
+                                                          float* __restrict__ z)
+{
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (j >= Cout) return;
+    const int chunks = Cin / 8;
+    for (int i = 0; i < B; ++i) {
+        float s = 0.f;
+        for (int c = lane; c < chunks; c += 64) {
+            const h16x8 wv = *reinterpret_cast<const h16x8*>(Wt + (size_t)j * Cin + c * 8);
+            const h16x8 av = *reinterpret_cast<const h16x8*>(a + (size_t)i * Cin + c * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += (float)wv[e] * (float)av[e];
+        }
+        s = wave_sum(s);
+        if (lane == 0) z[(size_t)i * Cout + j] = s + bias[j];
+    }
+}
+
+// dWt[j,c] = sum_i dz[i,j]*a[i,c]  (FP32 out);  db[j] = sum_i dz[i,j]
+__global__ __launch_bounds__(kThreads) void fc_bwd_w_kernel(int B, int Cin, int Cout, const h16* __restrict__ a,
+                                                            const h16* __restrict__ dz, float* __restrict__ dWt,
+                                                            float* __restrict__ db)
+{
+    const int G = Cin / 8;
+    const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= (size_t)Cout * G) return;
+    const int g = (int)(i % G), j = (int)(i / G);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float sb = 0.f;
+    for (int r = 0; r < B; ++r) {
+        const float d = (float)dz[(size_t)r * Cout + j];
+        const h16x8 av = *reinterpret_cast<const h16x8*>(a + (size_t)r * Cin + g * 8);
+        sb += d;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += d * (float)av[e];
+    }
+    float* o = dWt + (size_t)j * Cin + g * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = acc[e];
+    if (g == 0) db[j] = sb;
+}
+
+// da[i,c] = sum_j dz[i,j]*Wt[j,c] rounded to half, then spread over the HW positions of the
+// average pool: dx[i,hw,c] = half(da/HW).  Workgroup = (image i, slab of 32 channel groups);
+// 8 row-lanes split the classes and are combined through LDS in a fixed order.
+__global__ __launch_bounds__(kThreads) void fc_bwd_a_avgpool_bwd_kernel(int Cin, int Cout, int HW,
+                                                                        const h16* __restrict__ Wt,
+                                                                        const h16* __restrict__ dz,
+                                                                        h16* __restrict__ dx)
+{
+    __shared__ float red[8][32][8];
+    const int G = Cin / 8;
+    const int slabs = (G + 31) / 32;
+    const int i = blockIdx.x / slabs, slab = blockIdx.x % slabs;
+    const int gl = threadIdx.x & 31, jl = threadIdx.x >> 5;
+    const int g = slab * 32 + gl;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (g < G)
+        for (int j = jl; j < Cout; j += 8) {
+            const float d = (float)dz[(size_t)i * Cout + j];
+            const h16x8 wv = *reinterpret_cast<const h16x8*>(Wt + (size_t)j * Cin + g * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += d * (float)wv[e];
+        }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[jl][gl][e] = acc[e];
+    __syncthreads();
+    if (jl == 0 && g < G) {
+        h16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float s = 0.f;
+            for (int k = 0; k < 8; ++k) s += red[k][gl][e];
+            const h16 da = (h16)s;
+            o[e] = (h16)((float)da / (float)HW);
+        }
+        for (int k = 0; k < HW; ++k) *reinterpret_cast<h16x8*>(dx + ((size_t)i * HW + k) * Cin + g * 8) = o;
+    }
+}
+
+int grid_for(size_t items) {
+    size_t b = (items + kThreads - 1) / kThreads;
+    if (b > 256 * 16) b = 256 * 16;
+    return b < 1 ? 1 : (int)b;
+}
+
+}  // namespace
+
+int rn50_maxpool_fwd(int N, int H, int W, int C, const h16* x, h16* y, uint8_t* arg, hipStream_t s)
+{
+    const int P = (H + 2 - 3) / 2 + 1, Q = (W + 2 - 3) / 2 + 1;
+    maxpool_fwd_kernel<<<grid_for((size_t)N * P * Q * (C / 8)), kThreads, 0, s>>>(N, H, W, C, P, Q, x, y, arg);
+    return rn50_check_launch();
+}
+
+int rn50_maxpool_bwd(int N, int H, int W, int C, const h16* dy, const uint8_t* arg, h16* dx, hipStream_t s)
+{
+    const int P = (H + 2 - 3) / 2 + 1, Q = (W + 2 - 3) / 2 + 1;
+    maxpool_bwd_kernel<<<grid_for((size_t)N * H * W * (C / 8)), kThreads, 0, s>>>(N, H, W, C, P, Q, dy, arg, dx);
+    return rn50_check_launch();
+}
+
+int rn50_avgpool_fwd(int N, int HW, int C, const h16* x, h16* y, hipStream_t s)
+{
+    avgpool_fwd_kernel<<<rn50_cdiv((long long)N * (C / 8), kThreads), kThreads, 0, s>>>(N, HW, C, x, y);
+    return rn50_check_launch();
+}
+
+int rn50_fc_fwd(int B, int Cin, int Cout, const h16* a, const h16* Wt, const float* bias, float* z, hipStream_t s)
+{
+    fc_fwd_kernel<<<rn50_cdiv(Cout, kThreads / 64), kThreads, 0, s>>>(B, Cin, Cout, a, Wt, bias, z);
+    return rn50_check_launch();
+}
+
+int rn50_fc_bwd(int B, int Cin, int Cout, int HW, const h16* a, const h16* Wt, const h16* dz, float* dWt, float* db,
+                h16* dx, hipStream_t s)
+{
+    fc_bwd_w_kernel<<<rn50_cdiv((long long)Cout * (Cin / 8), kThreads), kThreads, 0, s>>>(B, Cin, Cout, a, dz, dWt, db);
+    const int slabs = (Cin / 8 + 31) / 32;
+    fc_bwd_a_avgpool_bwd_kernel<<<B * slabs, kThreads, 0, s>>>(Cin, Cout, HW, Wt, dz, dx);
+    return rn50_check_launch();
+}

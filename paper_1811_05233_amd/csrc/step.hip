@@ -1,0 +1,475 @@
+// Whole-iteration driver: walks the ResNet-50 v1.5 layer table and enqueues forward, loss,
+// backward and the momentum-SGD update on one stream, with no host synchronisation.
+// The context is a host object; every device byte lives in the caller's workspace.
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "conv_internal.h"
+#include "misc_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+struct Segment { size_t offset, count; int kind, fan_in; };
+
+struct ConvLayer {
+    std::string name;
+    conv_desc d;
+    int P, Q;
+    size_t w_off, gamma_off, beta_off;   // element offsets into the flat parameter layout
+    size_t wt_off;                       // element offset into the transposed-filter buffer
+    // workspace tensors
+    h16* conv_out = nullptr;
+    h16* bn_out = nullptr;
+    float* mean = nullptr;
+    float* invstd = nullptr;
+    h16* dconv = nullptr;                // gradient w.r.t. the conv output (BN backward result)
+    h16* din = nullptr;                  // gradient w.r.t. the conv input (data-gradient result)
+    h16* dres = nullptr;                 // conv3 only: masked gradient handed to the shortcut
+    size_t in_elems() const { return (size_t)d.n * d.h * d.w * d.c; }
+    size_t out_elems() const { return (size_t)d.n * P * Q * d.k; }
+};
+
+struct Block { int c1, c2, c3, proj; };   // indices into layers (proj = -1 if none)
+
+struct Layout {
+    std::vector<Segment> segments;
+    std::vector<ConvLayer> layers;
+    std::vector<Block> blocks;
+    size_t param_count = 0;
+    size_t fcw_off = 0, fcb_off = 0;
+    int feat = 0, final_h = 0, final_w = 0;
+    int pool_in_h = 0, pool_in_w = 0, pool_h = 0, pool_w = 0;
+};
+
+bool config_ok(const rn50_config* c)
+{
+    if (!c) return false;
+    if (c->dt != RN50_F16) return false;
+    if (c->batch < 1 || c->batch > 4096 || c->image_h < 1 || c->image_w < 1) return false;
+    if (c->num_stages < 1 || c->num_stages > 4) return false;
+    for (int s = 0; s < c->num_stages; ++s) if (c->blocks[s] < 1 || c->blocks[s] > 64) return false;
+    if (c->base_width < 64 || c->base_width % 64 != 0 || c->base_width > 1024) return false;
+    if (c->classes < 8 || c->classes % 8 != 0 || c->classes > 65536) return false;
+    if (c->has_stem && (c->image_h % 2 != 0 || c->image_w % 2 != 0)) return false;
+    if (!(c->bn_eps > 0.f) || !(c->loss_scale > 0.f) || c->ls_eps < 0.f || c->ls_eps >= 1.f) return false;
+    return true;
+}
+
+int out_dim(int h, int pad, int r, int stride) { return (h + 2 * pad - r) / stride + 1; }
+
+// Builds segments, layers and blocks; returns false if some layer has an unsupported shape.
+bool build_layout(const rn50_config& c, Layout& L)
+{
+    size_t off = 0, wt_off = 0;
+    auto add_seg = [&](size_t count, int kind, int fan_in) {
+        L.segments.push_back({off, count, kind, fan_in});
+        off += count;
+        return off - count;
+    };
+    auto add_conv = [&](const std::string& name, int h, int w, int cin, int cout, int r, int stride, int pad) -> int {
+        ConvLayer l;
+        l.name = name;
+        l.d = {c.batch, h, w, cin, cout, r, r, stride, pad, RN50_F16};
+        l.P = out_dim(h, pad, r, stride);
+        l.Q = out_dim(w, pad, r, stride);
+        l.w_off = add_seg((size_t)cout * r * r * cin, RN50_KIND_CONV, cin * r * r);
+        l.gamma_off = add_seg(cout, RN50_KIND_GAMMA, 0);
+        l.beta_off = add_seg(cout, RN50_KIND_BETA, 0);
+        l.wt_off = wt_off;
+        if (cin != 3) wt_off += (size_t)cout * r * r * cin;
+        L.layers.push_back(l);
+        return (int)L.layers.size() - 1;
+    };
+    int h = c.image_h, w = c.image_w;
+    if (c.has_stem) {
+        const int i = add_conv("stem", h, w, 3, c.base_width, 7, 2, 3);
+        L.pool_in_h = L.layers[i].P; L.pool_in_w = L.layers[i].Q;
+        h = out_dim(L.pool_in_h, 1, 3, 2); w = out_dim(L.pool_in_w, 1, 3, 2);
+        L.pool_h = h; L.pool_w = w;
+    }
+    int cin = c.base_width;
+    for (int s = 0; s < c.num_stages; ++s) {
+        const int width = c.base_width << s, cout = 4 * width;
+        for (int b = 0; b < c.blocks[s]; ++b) {
+            const int stride = (b == 0 && s > 0) ? 2 : 1;
+            const std::string nm = "s" + std::to_string(s + 1) + "b" + std::to_string(b);
+            Block blk;
+            blk.c1 = add_conv(nm + "c1", h, w, cin, width, 1, 1, 0);
+            blk.c2 = add_conv(nm + "c2", h, w, width, width, 3, stride, 1);
+            const int h2 = L.layers[blk.c2].P, w2 = L.layers[blk.c2].Q;
+            blk.c3 = add_conv(nm + "c3", h2, w2, width, cout, 1, 1, 0);
+            blk.proj = (b == 0) ? add_conv(nm + "p", h, w, cin, cout, 1, stride, 0) : -1;
+            L.blocks.push_back(blk);
+            h = h2; w = w2; cin = cout;
+        }
+    }
+    L.feat = cin; L.final_h = h; L.final_w = w;
+    L.fcw_off = add_seg((size_t)c.classes * cin, RN50_KIND_FCW, cin);
+    L.fcb_off = add_seg((size_t)c.classes, RN50_KIND_FCB, cin);
+    L.param_count = off;
+    for (const ConvLayer& l : L.layers)
+        if (rn50_conv_validate(&l.d) != RN50_OK || l.P < 1 || l.Q < 1) return false;
+    return h >= 1 && w >= 1;
+}
+
+// ---- batched filter transpose: every non-stem filter KRSC -> CRSK in one launch ----
+struct TransposeJob { unsigned long long src_off, dst_off; int K, T, C, block_end; };
+
+__global__ __launch_bounds__(kThreads) void transpose_all_kernel(const h16* __restrict__ w, h16* __restrict__ wt,
+                                                                 const TransposeJob* __restrict__ jobs, int njobs)
+{
+    __shared__ h16 tile[32][33];
+    int lo = 0, hi = njobs - 1;
+    const int b = blockIdx.x;
+    while (lo < hi) {                     // first job whose block_end exceeds b
+        const int mid = (lo + hi) >> 1;
+        if (jobs[mid].block_end > b) hi = mid; else lo = mid + 1;
+    }
+    const TransposeJob j = jobs[lo];
+    int lb = b - (lo ? jobs[lo - 1].block_end : 0);
+    const int tiles_c = j.C / 32, tiles_k = j.K / 32;
+    const int tc = lb % tiles_c; lb /= tiles_c;
+    const int tk = lb % tiles_k;
+    const int t = lb / tiles_k;
+    const h16* src = w + j.src_off;
+    h16* dst = wt + j.dst_off;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        tile[ty + i * 8][tx] = src[((size_t)(tk * 32 + ty + i * 8) * j.T + t) * j.C + tc * 32 + tx];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        dst[((size_t)(tc * 32 + ty + i * 8) * j.T + t) * j.K + tk * 32 + tx] = tile[tx][ty + i * 8];
+}
+
+}  // namespace
+
+struct rn50_ctx {
+    rn50_config cfg;
+    Layout L;
+    // workspace carve-up
+    char* ws = nullptr;
+    size_t ws_bytes = 0;
+    h16* stem_padded = nullptr;
+    h16* stem_packed = nullptr;
+    float* stem_wacc = nullptr;
+    h16* pool_out = nullptr;
+    uint8_t* pool_arg = nullptr;
+    h16* feat = nullptr;
+    float* logits = nullptr;
+    h16* dlogits = nullptr;
+    h16* wt_all = nullptr;        // transposed filters
+    float* grad32 = nullptr;      // flat FP32 gradient accumulators
+    float* bn_ws = nullptr;
+    h16* head_din = nullptr;      // gradient w.r.t. the last block's output (from the FC / avg-pool backward)
+    h16* pool_din = nullptr;      // gradient w.r.t. the stem's BN output (from the max-pool backward)
+    TransposeJob* jobs = nullptr;
+    int njobs = 0, transpose_blocks = 0;
+    size_t max_act = 0, wt_elems = 0;
+};
+
+namespace {
+
+// Lays the workspace out; with base == nullptr only the size is computed.
+size_t carve(rn50_ctx& c, char* base)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) -> char* {
+        char* p = base ? base + off : nullptr;
+        off += rn50_round_up(bytes, 256);
+        return p;
+    };
+    const rn50_config& cfg = c.cfg;
+    Layout& L = c.L;
+    size_t max_act = (size_t)cfg.batch * cfg.image_h * cfg.image_w * (cfg.has_stem ? 4 : cfg.base_width);
+    size_t wt_elems = 0;
+    int max_c = cfg.base_width;
+    for (ConvLayer& l : L.layers) {
+        l.conv_out = reinterpret_cast<h16*>(take(l.out_elems() * sizeof(h16)));
+        l.bn_out = reinterpret_cast<h16*>(take(l.out_elems() * sizeof(h16)));
+        l.mean = reinterpret_cast<float*>(take(l.d.k * sizeof(float)));
+        l.invstd = reinterpret_cast<float*>(take(l.d.k * sizeof(float)));
+        if (l.out_elems() > max_act) max_act = l.out_elems();
+        if (l.in_elems() > max_act && l.d.c != 3) max_act = l.in_elems();
+        if (l.d.c != 3) wt_elems += (size_t)l.d.k * l.d.r * l.d.s * l.d.c;
+        if (l.d.k > max_c) max_c = l.d.k;
+    }
+    c.max_act = max_act; c.wt_elems = wt_elems;
+    if (cfg.has_stem) {
+        const ConvLayer& st = L.layers[0];
+        c.stem_padded = reinterpret_cast<h16*>(take(rn50_stem_padded_bytes(st.d)));
+        c.stem_packed = reinterpret_cast<h16*>(take(rn50_stem_packed_filter_bytes(st.d)));
+        c.stem_wacc = reinterpret_cast<float*>(take(rn50_wgrad_acc_floats(st.d) * sizeof(float)));
+        const size_t pool_elems = (size_t)cfg.batch * L.pool_h * L.pool_w * cfg.base_width;
+        c.pool_out = reinterpret_cast<h16*>(take(pool_elems * sizeof(h16)));
+        c.pool_arg = reinterpret_cast<uint8_t*>(take(pool_elems));
+    }
+    c.feat = reinterpret_cast<h16*>(take((size_t)cfg.batch * L.feat * sizeof(h16)));
+    c.logits = reinterpret_cast<float*>(take((size_t)cfg.batch * cfg.classes * sizeof(float)));
+    c.dlogits = reinterpret_cast<h16*>(take((size_t)cfg.batch * cfg.classes * sizeof(h16)));
+    c.wt_all = reinterpret_cast<h16*>(take(wt_elems * sizeof(h16)));
+    c.grad32 = reinterpret_cast<float*>(take(rn50_round_up(L.param_count, 8) * sizeof(float)));
+    c.bn_ws = reinterpret_cast<float*>(take(rn50_bn_ws_floats(max_c) * sizeof(float)));
+    // Activation gradients.  Normally six rotating buffers (two alternate as block-input gradients,
+    // one holds the shortcut gradient, three are scratch inside a block); with keep_grads every
+    // gradient tensor gets its own buffer so that it can be inspected after the step.
+    const int nb = (int)L.blocks.size();
+    if (cfg.keep_grads) {
+        for (ConvLayer& l : L.layers) {
+            l.dconv = reinterpret_cast<h16*>(take(l.out_elems() * sizeof(h16)));
+            l.din = reinterpret_cast<h16*>(take(l.in_elems() * sizeof(h16)));
+        }
+        for (const Block& b : L.blocks)
+            L.layers[b.c3].dres = reinterpret_cast<h16*>(take(L.layers[b.c3].out_elems() * sizeof(h16)));
+        c.head_din = reinterpret_cast<h16*>(take(L.layers[L.blocks[nb - 1].c3].out_elems() * sizeof(h16)));
+        c.pool_din = cfg.has_stem ? reinterpret_cast<h16*>(take(L.layers[0].out_elems() * sizeof(h16))) : nullptr;
+    } else {
+        h16* g[6];
+        for (int i = 0; i < 6; ++i) g[i] = reinterpret_cast<h16*>(take(max_act * sizeof(h16)));
+        for (int bi = 0; bi < nb; ++bi) {
+            const Block& b = L.blocks[bi];
+            L.layers[b.c3].dres = g[2];
+            L.layers[b.c3].dconv = g[3]; L.layers[b.c3].din = g[4];
+            L.layers[b.c2].dconv = g[3]; L.layers[b.c2].din = g[4];
+            L.layers[b.c1].dconv = g[3]; L.layers[b.c1].din = g[bi % 2];
+            if (b.proj >= 0) { L.layers[b.proj].dconv = g[4]; L.layers[b.proj].din = g[5]; }
+        }
+        c.head_din = g[nb % 2];
+        if (cfg.has_stem) { c.pool_din = g[4]; L.layers[0].dconv = g[3]; }
+    }
+    c.jobs = reinterpret_cast<TransposeJob*>(take(L.layers.size() * sizeof(TransposeJob)));
+    return off;
+}
+
+}  // namespace
+
+extern "C" size_t rn50_param_count(const rn50_config* cfg)
+{
+    Layout L;
+    if (!config_ok(cfg) || !build_layout(*cfg, L)) return 0;
+    return L.param_count;
+}
+
+extern "C" int rn50_num_segments(const rn50_config* cfg)
+{
+    Layout L;
+    if (!config_ok(cfg) || !build_layout(*cfg, L)) return 0;
+    return (int)L.segments.size();
+}
+
+extern "C" int rn50_param_layout(const rn50_config* cfg, int idx, size_t* offset, size_t* count, int* kind, int* fan_in)
+{
+    Layout L;
+    if (!cfg) return RN50_ERR_NULL;
+    if (!config_ok(cfg) || !build_layout(*cfg, L)) return RN50_ERR_SHAPE;
+    if (idx < 0 || idx >= (int)L.segments.size()) return RN50_ERR_SHAPE;
+    const Segment& s = L.segments[idx];
+    if (offset) *offset = s.offset;
+    if (count) *count = s.count;
+    if (kind) *kind = s.kind;
+    if (fan_in) *fan_in = s.fan_in;
+    return RN50_OK;
+}
+
+extern "C" size_t rn50_workspace_bytes(const rn50_config* cfg)
+{
+    if (!config_ok(cfg)) return 0;
+    rn50_ctx c;
+    c.cfg = *cfg;
+    if (!build_layout(*cfg, c.L)) return 0;
+    return carve(c, nullptr);
+}
+
+extern "C" int rn50_create(rn50_ctx** out, const rn50_config* cfg, void* workspace, size_t workspace_bytes)
+{
+    if (!out || !cfg) return RN50_ERR_NULL;
+    *out = nullptr;
+    if (cfg->dt != RN50_F16) return RN50_ERR_DTYPE;
+    if (!config_ok(cfg)) return RN50_ERR_SHAPE;
+    rn50_ctx* c = new rn50_ctx();
+    c->cfg = *cfg;
+    if (!build_layout(*cfg, c->L)) { delete c; return RN50_ERR_SHAPE; }
+    const size_t need = carve(*c, nullptr);
+    if (!workspace || workspace_bytes < need) { delete c; return RN50_ERR_WORKSPACE; }
+    if (!rn50_aligned16(workspace)) { delete c; return RN50_ERR_ALIGN; }
+    c->ws = static_cast<char*>(workspace);
+    c->ws_bytes = workspace_bytes;
+    carve(*c, c->ws);
+    // job table of the batched filter transpose (uploaded once, synchronously)
+    std::vector<TransposeJob> jobs;
+    int blocks = 0;
+    for (const ConvLayer& l : c->L.layers) {
+        if (l.d.c == 3) continue;
+        const int T = l.d.r * l.d.s;
+        blocks += (l.d.c / 32) * (l.d.k / 32) * T;
+        jobs.push_back({(unsigned long long)l.w_off, (unsigned long long)l.wt_off, l.d.k, T, l.d.c, blocks});
+    }
+    c->njobs = (int)jobs.size();
+    c->transpose_blocks = blocks;
+    if (!jobs.empty()) {
+        hipError_t e = hipMemcpy(c->jobs, jobs.data(), jobs.size() * sizeof(TransposeJob), hipMemcpyHostToDevice);
+        if (e != hipSuccess) { delete c; return rn50_hip_fail(e); }
+    }
+    *out = c;
+    return RN50_OK;
+}
+
+extern "C" void rn50_destroy(rn50_ctx* ctx) { delete ctx; }
+
+extern "C" int rn50_tensor(rn50_ctx* ctx, const char* name, void** ptr, size_t* elems, int* elem_bytes)
+{
+    if (!ctx || !name || !ptr || !elems || !elem_bytes) return RN50_ERR_NULL;
+    const rn50_config& cfg = ctx->cfg;
+    const std::string nm(name);
+    auto set = [&](void* p, size_t n, int eb) { *ptr = p; *elems = n; *elem_bytes = eb; return RN50_OK; };
+    if (nm == "feat") return set(ctx->feat, (size_t)cfg.batch * ctx->L.feat, 2);
+    if (nm == "logits") return set(ctx->logits, (size_t)cfg.batch * cfg.classes, 4);
+    if (nm == "dlogits") return set(ctx->dlogits, (size_t)cfg.batch * cfg.classes, 2);
+    if (nm == "pool.out" && cfg.has_stem)
+        return set(ctx->pool_out, (size_t)cfg.batch * ctx->L.pool_h * ctx->L.pool_w * cfg.base_width, 2);
+    if (cfg.keep_grads) {
+        if (nm == "head.din") return set(ctx->head_din, ctx->L.layers[ctx->L.blocks.back().c3].out_elems(), 2);
+        if (nm == "pool.din" && cfg.has_stem) return set(ctx->pool_din, ctx->L.layers[0].out_elems(), 2);
+    }
+    const size_t dot = nm.rfind('.');
+    if (dot == std::string::npos) return RN50_ERR_SHAPE;
+    const std::string layer = nm.substr(0, dot), what = nm.substr(dot + 1);
+    for (ConvLayer& l : ctx->L.layers) {
+        if (l.name != layer) continue;
+        if (what == "conv") return set(l.conv_out, l.out_elems(), 2);
+        if (what == "out") return set(l.bn_out, l.out_elems(), 2);
+        if (what == "mean") return set(l.mean, (size_t)l.d.k, 4);
+        if (what == "invstd") return set(l.invstd, (size_t)l.d.k, 4);
+        if (cfg.keep_grads) {
+            if (what == "dconv") return set(l.dconv, l.out_elems(), 2);
+            if (what == "din" && l.d.c != 3) return set(l.din, l.in_elems(), 2);
+            if (what == "dres" && l.dres) return set(l.dres, l.out_elems(), 2);
+        }
+    }
+    return RN50_ERR_SHAPE;
+}
+
+extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* labels, float* master_w, float* momentum,
+                         void* w_lowp, void* grad_lowp, const rn50_hparams* hp, float* loss_out, void* stream)
+{
+    RN50_REQUIRE_PTR(ctx); RN50_REQUIRE_PTR(images); RN50_REQUIRE_PTR(labels); RN50_REQUIRE_PTR(master_w);
+    RN50_REQUIRE_PTR(w_lowp); RN50_REQUIRE_PTR(grad_lowp); RN50_REQUIRE_PTR(loss_out);
+    if (hp) RN50_REQUIRE_PTR(momentum);
+    RN50_REQUIRE_ALIGNED(images); RN50_REQUIRE_ALIGNED(master_w); RN50_REQUIRE_ALIGNED(momentum);
+    RN50_REQUIRE_ALIGNED(w_lowp); RN50_REQUIRE_ALIGNED(grad_lowp);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rn50_ctx& c = *ctx;
+    const rn50_config& cfg = c.cfg;
+    Layout& L = c.L;
+    const h16* w16 = static_cast<const h16*>(w_lowp);
+    const int B = cfg.batch;
+
+    // ---- per-step preparation: zero the FP32 gradient accumulators, re-lay the filters ----
+    RN50_TRY(rn50_fill_zero(c.grad32, rn50_round_up(L.param_count, 8), s));
+    if (c.njobs > 0) {
+        transpose_all_kernel<<<c.transpose_blocks, kThreads, 0, s>>>(w16, c.wt_all, c.jobs, c.njobs);
+        RN50_TRY(rn50_check_launch());
+    }
+
+    auto conv_bn_fwd = [&](ConvLayer& l, const h16* x, bool relu, const h16* residual) -> int {
+        RN50_TRY(rn50_conv_fwd_launch(l.d, x, w16 + l.w_off, l.conv_out, s));
+        return rn50_bn_fwd_launch((long long)l.d.n * l.P * l.Q, l.d.k, cfg.bn_eps, relu, l.conv_out,
+                                  master_w + l.gamma_off, master_w + l.beta_off, residual, l.bn_out, l.mean, l.invstd,
+                                  c.bn_ws, s);
+    };
+
+    // ================= forward =================
+    const h16* x = static_cast<const h16*>(images);
+    if (cfg.has_stem) {
+        ConvLayer& st = L.layers[0];
+        RN50_TRY(rn50_stem_pad_image(st.d, x, c.stem_padded, s));
+        RN50_TRY(rn50_stem_pack_filter(st.d, w16 + st.w_off, c.stem_packed, s));
+        RN50_TRY(rn50_conv_fwd_launch(st.d, c.stem_padded, c.stem_packed, st.conv_out, s));
+        RN50_TRY(rn50_bn_fwd_launch((long long)B * st.P * st.Q, st.d.k, cfg.bn_eps, true, st.conv_out,
+                                    master_w + st.gamma_off, master_w + st.beta_off, nullptr, st.bn_out, st.mean,
+                                    st.invstd, c.bn_ws, s));
+        RN50_TRY(rn50_maxpool_fwd(B, st.P, st.Q, st.d.k, st.bn_out, c.pool_out, c.pool_arg, s));
+        x = c.pool_out;
+    }
+    std::vector<const h16*> block_in(L.blocks.size());
+    for (size_t bi = 0; bi < L.blocks.size(); ++bi) {
+        const Block& b = L.blocks[bi];
+        block_in[bi] = x;
+        RN50_TRY(conv_bn_fwd(L.layers[b.c1], x, true, nullptr));
+        RN50_TRY(conv_bn_fwd(L.layers[b.c2], L.layers[b.c1].bn_out, true, nullptr));
+        const h16* shortcut = x;
+        if (b.proj >= 0) {
+            RN50_TRY(conv_bn_fwd(L.layers[b.proj], x, false, nullptr));
+            shortcut = L.layers[b.proj].bn_out;
+        }
+        RN50_TRY(conv_bn_fwd(L.layers[b.c3], L.layers[b.c2].bn_out, true, shortcut));
+        x = L.layers[b.c3].bn_out;
+    }
+    const int HW = L.final_h * L.final_w;
+    RN50_TRY(rn50_avgpool_fwd(B, HW, L.feat, x, c.feat, s));
+    RN50_TRY(rn50_fc_fwd(B, L.feat, cfg.classes, c.feat, w16 + L.fcw_off, master_w + L.fcb_off, c.logits, s));
+
+    // ================= loss =================
+    RN50_TRY(ls_xent_fwd_bwd(B, cfg.classes, c.logits, labels, cfg.ls_eps, cfg.loss_scale / (float)B, loss_out,
+                             nullptr, c.dlogits, RN50_F16, stream));
+
+    // ================= backward =================
+    RN50_TRY(rn50_fc_bwd(B, L.feat, cfg.classes, HW, c.feat, w16 + L.fcw_off, c.dlogits, c.grad32 + L.fcw_off,
+                         c.grad32 + L.fcb_off, c.head_din, s));
+
+    // BN backward + filter gradient of one conv: dy -> l.dconv (and dres), filter gradient accumulated
+    auto conv_bn_bwd = [&](ConvLayer& l, const h16* in, const h16* dy, bool relu, h16* dres) -> int {
+        RN50_TRY(rn50_bn_bwd_launch((long long)l.d.n * l.P * l.Q, l.d.k, relu, dy, l.conv_out, l.bn_out,
+                                    master_w + l.gamma_off, l.mean, l.invstd, l.dconv, dres, nullptr, nullptr,
+                                    c.grad32 + l.gamma_off, c.grad32 + l.beta_off, c.bn_ws, s));
+        return rn50_conv_wgrad_launch(l.d, in, l.dconv, c.grad32 + l.w_off, s);
+    };
+    auto dgrad = [&](ConvLayer& l, const h16* addend) -> int {
+        return rn50_conv_dgrad_launch(l.d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s);
+    };
+
+    const h16* dY = c.head_din;
+    for (int bi = (int)L.blocks.size() - 1; bi >= 0; --bi) {
+        const Block& b = L.blocks[bi];
+        ConvLayer &l1 = L.layers[b.c1], &l2 = L.layers[b.c2], &l3 = L.layers[b.c3];
+        const bool need_in = cfg.has_stem || bi > 0;
+        RN50_TRY(conv_bn_bwd(l3, l2.bn_out, dY, true, l3.dres));     // also the masked shortcut gradient
+        RN50_TRY(dgrad(l3, nullptr));
+        RN50_TRY(conv_bn_bwd(l2, l1.bn_out, l3.din, true, nullptr));
+        RN50_TRY(dgrad(l2, nullptr));
+        RN50_TRY(conv_bn_bwd(l1, block_in[bi], l2.din, true, nullptr));
+        if (b.proj >= 0) {
+            ConvLayer& lp = L.layers[b.proj];
+            RN50_TRY(conv_bn_bwd(lp, block_in[bi], l3.dres, false, nullptr));
+            if (need_in) {
+                RN50_TRY(dgrad(lp, nullptr));
+                RN50_TRY(dgrad(l1, lp.din));                         // main path + projection shortcut
+            }
+        } else {
+            RN50_TRY(dgrad(l1, l3.dres));                            // main path + identity shortcut
+        }
+        dY = l1.din;
+    }
+    if (cfg.has_stem) {
+        ConvLayer& st = L.layers[0];
+        RN50_TRY(rn50_maxpool_bwd(B, st.P, st.Q, st.d.k, dY, c.pool_arg, c.pool_din, s));
+        RN50_TRY(rn50_bn_bwd_launch((long long)B * st.P * st.Q, st.d.k, true, c.pool_din, st.conv_out, st.bn_out,
+                                    master_w + st.gamma_off, st.mean, st.invstd, st.dconv, nullptr, nullptr, nullptr,
+                                    c.grad32 + st.gamma_off, c.grad32 + st.beta_off, c.bn_ws, s));
+        RN50_TRY(rn50_fill_zero(c.stem_wacc, rn50_wgrad_acc_floats(st.d), s));
+        RN50_TRY(rn50_conv_wgrad_launch(st.d, c.stem_padded, st.dconv, c.stem_wacc, s));
+        RN50_TRY(rn50_stem_unpack_wgrad(st.d, c.stem_wacc, c.grad32 + st.w_off, s));
+    }
+
+    // ================= flat FP16 gradient, update =================
+    RN50_TRY(rn50_cast_f32_to_h16(c.grad32, static_cast<h16*>(grad_lowp), L.param_count, s));
+    if (hp)
+        RN50_TRY(sgd_momentum_flat(L.param_count, grad_lowp, RN50_F16, hp->grad_scale, master_w, momentum, w_lowp,
+                                   hp->lr, hp->momentum, hp->wd, stream));
+    return RN50_OK;
+}

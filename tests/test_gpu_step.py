@@ -1,0 +1,373 @@
+"""GPU parity of the whole iteration (rn50_step) against the oracle's step_ref in
+storage-rounding mode (FP64 arithmetic, binary16 rounding wherever the GPU stores a tensor).
+
+Per-tensor tolerance 2e-2 relative to max(|ref|, 1e-2*max|ref|); loss 1e-5 given the GPU's own
+logits (and reported against the oracle's logits); update 1e-5 given the GPU's own gradient."""
+import ctypes
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+import oracle as O                                   # noqa: E402
+from oracle import resnet50 as R                     # noqa: E402
+import paper_1811_05233_amd as P                     # noqa: E402
+from paper_1811_05233_amd import synth               # noqa: E402
+from gpu_util import DEV, dev_f, dev_h, dev_i, host, rel_err, rel_err_fp32   # noqa: E402
+
+TOL16, TOL32 = 2e-2, 1e-5
+
+
+def make_problem(batch, image_hw, has_stem, blocks, classes=1000, loss_scale=128.0, seed=200, perturb_affine=True):
+    cfg = P.make_config(batch, image_hw, has_stem, blocks, 64, classes, loss_scale=loss_scale)
+    net = R.Net(batch, image_hw, has_stem, blocks, 64, classes)
+    lay = P.rn50_param_layout(cfg)
+    assert lay == [(s.kind, s.offset, s.count, s.fan_in) for s in net.segments]
+    w = synth.flat_params(seed, lay)
+    if perturb_affine:   # exercise gamma/beta/bias gradients away from their initial values
+        r = synth.rng(seed + 7)
+        for kind, off, cnt, _ in lay:
+            if kind in (P.KIND_GAMMA, P.KIND_BETA, P.KIND_FCB):
+                w[off:off + cnt] += 0.1 * r.standard_normal(cnt).astype(np.float32)
+    cin = 3 if has_stem else 64
+    x = synth.normal_f16(seed + 1, (batch, image_hw[0], image_hw[1], cin))
+    lab = synth.labels(seed + 2, batch, classes)
+    return cfg, net, w, x, lab
+
+
+def run_gpu(cfg, w, x, lab, hp):
+    n = w.size
+    ctx = P.Rn50Context(cfg)
+    wd, vd = dev_f(w), torch.zeros(n, dtype=torch.float32, device=DEV)
+    w16 = torch.empty(n, dtype=torch.float16, device=DEV)
+    g16 = torch.zeros(n, dtype=torch.float16, device=DEV)
+    P.rn50_cast_params(n, wd, w16)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    ctx.step(dev_h(x), dev_i(lab), wd, vd, w16, g16, hp, loss)
+    torch.cuda.synchronize()
+    return ctx, dict(w=host(wd), v=host(vd), w16=host(w16), g16=host(g16), loss=float(host(loss)[0]))
+
+
+def linf_err(a, b):
+    a = np.asarray(a, np.float64).reshape(-1)
+    b = np.asarray(b, np.float64).reshape(-1)
+    return float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-300))
+
+
+def gpu_forward_tensors(ctx, net, x, batch):
+    """The GPU's own stored forward tensors under the oracle's names (for a teacher-forced backward)."""
+    t = {}
+    for nm, cv in net.convs.items():
+        for what in ("conv", "out"):
+            a = host(ctx.tensor(nm + "." + what))
+            t[nm + "." + what] = a.reshape(batch, -1, 1, cv["cout"])      # H and W are fixed up below
+        t[nm + ".mean"] = host(ctx.tensor(nm + ".mean"))
+        t[nm + ".invstd"] = host(ctx.tensor(nm + ".invstd"))
+    h, w = x.shape[1:3]
+    cur = x.astype(np.float64)
+    if net.has_stem:
+        h, w = O.out_hw(h, w, 7, 7, 2, 3)
+        for what in ("conv", "out"):
+            t["stem." + what] = t["stem." + what].reshape(batch, h, w, -1)
+        t["stem.in"] = cur
+        h, w = O.out_hw(h, w, 3, 3, 2, 1)
+        cur = host(ctx.tensor("pool.out")).reshape(batch, h, w, -1)
+        t["pool.out"] = cur
+    for b in net.block_list:
+        n = b["name"]
+        t[n + ".in"] = cur
+        h2, w2 = O.out_hw(h, w, 3, 3, b["stride"], 1)
+        shapes = {"c1": (h, w), "c2": (h2, w2), "c3": (h2, w2), "p": (h2, w2)}
+        for sfx in ["c1", "c2", "c3"] + (["p"] if b["proj"] else []):
+            for what in ("conv", "out"):
+                t[n + sfx + "." + what] = t[n + sfx + "." + what].reshape(batch, shapes[sfx][0], shapes[sfx][1], -1)
+        t[n + "c1.in"] = cur
+        t[n + "c2.in"] = t[n + "c1.out"]
+        t[n + "c3.in"] = t[n + "c2.out"]
+        if b["proj"]:
+            t[n + "p.in"] = cur
+        cur = t[n + "c3.out"]
+        h, w = h2, w2
+    t["feat"] = host(ctx.tensor("feat")).reshape(batch, -1)
+    t["logits"] = host(ctx.tensor("logits")).reshape(batch, -1)
+    return t
+
+
+def check_step(batch, image_hw, has_stem, blocks, classes=1000, loss_scale=1024.0, fwd_tol=1e-2):
+    """Forward: every stored tensor against the end-to-end oracle, max error relative to the tensor's
+    largest magnitude <= fwd_tol and at most 1% of elements beyond 2e-2 in the element-wise metric
+    (a binary16 rounding flip upstream is amplified where a sum cancels, so single elements may exceed
+    the kernel-level tolerance; the fraction is only checked where BN averages over >= 1024 rows).  Backward: the oracle's backward pass is run on the GPU's own forward
+    tensors (same ReLU masks and statistics); every gradient segment must then agree to fwd_tol of its
+    largest magnitude (the chain of FP16-stored gradients is as deep as the network, so the element-wise
+    2e-2 bound is asserted only for the segments next to the loss, and for every kernel in isolation
+    elsewhere).
+    Loss: 1e-5 given the GPU's logits.  Update: bit-identical to the FP32 formula on the GPU's gradient."""
+    print("[case] rn50_step batch=%d image=%s stem=%d blocks=%s" % (batch, image_hw, has_stem, blocks), flush=True)
+    cfg, net, w, x, lab = make_problem(batch, image_hw, has_stem, blocks, classes, loss_scale)
+    lr, mu, wd_ = 0.1, 0.9, 1e-4
+    hp = P.rn50_hparams(lr, mu, wd_, 1.0 / loss_scale)
+    ctx, out = run_gpu(cfg, w, x, lab, hp)
+    f64 = np.float64
+    t = R.forward_ref(net, x.astype(f64), w.astype(f64))
+    tg = gpu_forward_tensors(ctx, net, x, batch)
+    worst, frac = {}, {}
+    for nm in net.convs:
+        for what in ("conv", "out"):
+            k = nm + "." + what
+            worst[k] = linf_err(tg[k], t[k])
+            a, b = tg[k].reshape(-1), t[k].reshape(-1)
+            if a.size // tg[k].shape[-1] >= 1024:     # batch statistics over few rows amplify any rounding flip
+                frac[k] = float(np.mean(np.abs(a - b) > 2e-2 * np.maximum(np.abs(b), 1e-2 * np.abs(b).max())))
+        assert linf_err(tg[nm + ".invstd"], t[nm + ".invstd"]) <= fwd_tol, nm
+    for k in (["pool.out"] if has_stem else []) + ["feat", "logits"]:
+        worst[k] = linf_err(tg[k], t[k])
+    print("[info] forward: worst max-normalised error %.3e (%s); worst fraction beyond 2e-2: %.2e (%s)" % (
+        max(worst.values()), max(worst, key=worst.get), max(frac.values()), max(frac, key=frac.get)), flush=True)
+    assert max(worst.values()) <= fwd_tol, {k: v for k, v in worst.items() if v > fwd_tol}
+    assert max(frac.values()) <= 1e-2, frac
+    # loss: 1e-5 given the GPU's own logits; close to the oracle's end-to-end loss
+    loss_given, _, grad_tf = R.backward_ref(net, tg, lab, w.astype(f64), 0.1, loss_scale)
+    loss_e2e = O.ls_xent_fwd_bwd(t["logits"], lab, 0.1)[0]
+    print("[info] loss gpu %.7f oracle on gpu logits %.7f oracle end-to-end %.7f" % (out["loss"], loss_given, loss_e2e),
+          flush=True)
+    assert abs(out["loss"] - loss_given) <= TOL32 * abs(loss_given)
+    assert abs(out["loss"] - loss_e2e) <= 5e-3 * abs(loss_e2e)
+    assert rel_err(host(ctx.tensor("dlogits")), tg["dlogits"]) <= TOL16
+    # flat gradient, segment by segment, against the teacher-forced oracle backward
+    assert np.all(np.isfinite(out["g16"]))
+    gerr = {s.name: linf_err(out["g16"][s.offset:s.offset + s.count], grad_tf[s.offset:s.offset + s.count])
+            for s in net.segments}
+    grel = {s.name: rel_err(out["g16"][s.offset:s.offset + s.count], grad_tf[s.offset:s.offset + s.count])
+            for s in net.segments}
+    print("[info] backward: worst gradient segment error: max-normalised %.3e (%s), element-wise %.3e (%s)" % (
+        max(gerr.values()), max(gerr, key=gerr.get), max(grel.values()), max(grel, key=grel.get)), flush=True)
+    assert max(gerr.values()) <= fwd_tol, {k: v for k, v in gerr.items() if v > fwd_tol}
+    last = net.block_list[-1]["name"]
+    for k in ("fc.w", "fc.b", last + "c3.gamma", last + "c3.beta"):   # one kernel away from the loss: element-wise
+        assert grel[k] <= TOL16, (k, grel[k])
+    # update: exact FP32 formula applied to the GPU's own FP16 gradient
+    w32, v32 = w.astype(np.float32), np.zeros(w.size, np.float32)
+    O.sgd_momentum_flat(out["g16"].astype(np.float32), w32, v32, np.float32(lr), np.float32(mu), np.float32(wd_),
+                        np.float32(1.0 / loss_scale), want_lowp=False)
+    assert np.array_equal(out["w"], w32.astype(f64)) and np.array_equal(out["v"], v32.astype(f64))
+    assert np.array_equal(out["w16"], O.round_binary16(out["w"]))
+    ctx.close()
+    return worst, gerr
+
+
+def test_step_bottleneck_config0():
+    """One stage-1 bottleneck + head on 2x56x56x64 input (no stem), 1000 classes."""
+    check_step(2, (56, 56), False, (1,))
+
+
+def test_step_small_full_topology():
+    check_step(4, (64, 64), True, (1, 1, 1, 1))
+
+
+def test_step_two_blocks_per_stage_ragged_batch():
+    # tiny images: BN averages over as few as 18 rows and the stem's dbeta is a sum that cancels almost
+    # completely, so rounding flips weigh more; this case is about ragged geometry and identity blocks
+    check_step(3, (32, 48), True, (2, 2), fwd_tol=3e-2)
+
+
+def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, loss_scale=1024.0, classes=1000):
+    """Every kernel launch inside one rn50_step call, checked where it ran: the oracle recomputes
+    each layer's result from the GPU's OWN input tensors of that layer (read back from the workspace,
+    keep_grads=1), so rounding differences cannot pile up over the depth of the network and the
+    element-wise 2e-2 bound applies to every stored tensor and every gradient segment.
+    n_img / n_k: number of sampled images (convolution outputs) and output channels (filter
+    gradients) the oracle computes; None = all of them."""
+    print("[case] in-situ rn50_step batch=%d image=%s blocks=%s n_img=%s n_k=%s" % (batch, image_hw, blocks, n_img, n_k),
+          flush=True)
+    f64 = np.float64
+    cfg, net, w, x, lab = make_problem(batch, image_hw, has_stem, blocks, classes, loss_scale)
+    cfg.keep_grads = 1
+    lr, mu, wd_ = 0.1, 0.9, 1e-4
+    hp = P.rn50_hparams(lr, mu, wd_, 1.0 / loss_scale)
+    ctx, out = run_gpu(cfg, w, x, lab, hp)
+    tg = gpu_forward_tensors(ctx, net, x, batch)
+    w64 = w.astype(f64)
+    w16 = O.round_binary16(w64)
+    g16 = out["g16"]
+    sel = np.arange(batch) if n_img is None else np.unique(np.linspace(0, batch - 1, n_img).astype(int))
+    worst = [0.0, ""]
+
+    def check(name, got, want, tol=TOL16):
+        e = rel_err(got, want)
+        if e > worst[0]:
+            worst[0], worst[1] = e, name
+        assert e <= tol, "%s: %.3e" % (name, e)
+
+    def seg(name):
+        sg = net.seg[name]
+        return g16[sg.offset:sg.offset + sg.count].reshape(sg.shape)
+
+    def gt(name, like):
+        return host(ctx.tensor(name)).reshape(like.shape)
+
+    # ---------------- forward ----------------
+    for nm, cv in net.convs.items():
+        xin, conv, outp = tg[nm + ".in"], tg[nm + ".conv"], tg[nm + ".out"]
+        check(nm + ".conv", conv[sel], O.conv_fwd(xin[sel], net.view(w16, nm + ".w"), cv["stride"], cv["pad"]))
+        res = None
+        if nm.endswith("c3"):
+            blk = nm[:-2]
+            res = tg[blk + "p.out"] if (blk + "p") in net.convs else tg[blk + ".in"]
+        ry, rmean, rinv, _ = O.bn_relu_fwd(conv, net.view(w64, nm + ".gamma"), net.view(w64, nm + ".beta"), 1e-5,
+                                           not nm.endswith("p"), res)
+        check(nm + ".out", outp, ry)
+        m = conv.size // conv.shape[-1]
+        assert np.max(np.abs(tg[nm + ".mean"] - rmean)) <= 1e-5 * max(1.0, np.max(np.abs(rmean))), nm
+        if m >= 64:
+            assert rel_err_fp32(tg[nm + ".invstd"], rinv) <= 1e-4, nm
+    if has_stem:
+        check("pool.out", tg["pool.out"], O.maxpool_fwd(tg["stem.out"], 3, 2, 1), 0.0)     # pure selection: exact
+    last = net.block_list[-1]["name"]
+    check("feat", tg["feat"], O.avgpool_fwd(tg[last + "c3.out"]))
+    check("logits", tg["logits"], O.fc_fwd(tg["feat"], net.view(w16, "fc.w"), net.view(w64, "fc.b")), 1e-4)
+    loss_ref, _, dz = O.ls_xent_fwd_bwd(tg["logits"], lab, 0.1, loss_scale / batch)
+    assert abs(out["loss"] - loss_ref) <= TOL32 * abs(loss_ref)
+    gdz = host(ctx.tensor("dlogits")).reshape(batch, classes)
+    check("dlogits", gdz, dz)
+
+    # ---------------- backward ----------------
+    dwt, db, da = O.fc_bwd(tg["feat"], net.view(w16, "fc.w"), gdz)
+    check("g:fc.w", seg("fc.w"), dwt)
+    check("g:fc.b", seg("fc.b"), db)
+    hw_last = tg[last + "c3.out"].shape[1:3]
+    head = gt("head.din", tg[last + "c3.out"])
+    check("head.din", head, O.round_binary16(O.avgpool_bwd(O.round_binary16(da), hw_last)))
+
+    def layer_bwd(nm, dy, relu, want_dres, addend, need_dx):
+        cv = net.convs[nm]
+        xin, conv, outp = tg[nm + ".in"], tg[nm + ".conv"], tg[nm + ".out"]
+        dconv = gt(nm + ".dconv", conv)
+        rdc, rdres, rdg, rdb = O.bn_relu_bwd(dy, conv, outp, net.view(w64, nm + ".gamma"), tg[nm + ".mean"],
+                                             tg[nm + ".invstd"], relu, want_dres)
+        check(nm + ".dconv", dconv, rdc)
+        check("g:" + nm + ".gamma", seg(nm + ".gamma"), rdg)
+        check("g:" + nm + ".beta", seg(nm + ".beta"), rdb)
+        dres = None
+        if want_dres:
+            dres = gt(nm + ".dres", conv)
+            assert np.array_equal(dres, rdres), nm + ".dres"
+        k = cv["cout"]
+        ks = np.arange(k) if n_k is None else np.unique(np.linspace(0, k - 1, n_k).astype(int))
+        rdw = O.conv_wgrad(xin, np.ascontiguousarray(dconv[..., ks]), (len(ks),) + net.seg[nm + ".w"].shape[1:],
+                           cv["stride"], cv["pad"])
+        check("g:" + nm + ".w", seg(nm + ".w")[ks], rdw)
+        din = None
+        if need_dx:
+            din = gt(nm + ".din", xin)
+            rdx = O.conv_dgrad(dconv[sel], net.view(w16, nm + ".w"), xin[sel].shape, cv["stride"], cv["pad"])
+            if addend is not None:
+                rdx = rdx + addend[sel]
+            check(nm + ".din", din[sel], rdx)
+        return din, dres
+
+    dY = head
+    first = net.block_list[0]["name"]
+    for b in reversed(net.block_list):
+        n = b["name"]
+        need_in = has_stem or n != first
+        d3, dres = layer_bwd(n + "c3", dY, True, True, None, True)
+        d2, _ = layer_bwd(n + "c2", d3, True, False, None, True)
+        if b["proj"]:
+            dp, _ = layer_bwd(n + "p", dres, False, False, None, need_in)
+            dY, _ = layer_bwd(n + "c1", d2, True, False, dp, need_in)
+        else:
+            dY, _ = layer_bwd(n + "c1", d2, True, False, dres, True)
+    if has_stem:
+        pdin = gt("pool.din", tg["stem.out"])
+        check("pool.din", pdin, O.maxpool_bwd(tg["stem.out"], dY, 3, 2, 1))
+        layer_bwd("stem", pdin, True, False, None, False)
+    print("[info] in-situ: worst element-wise error %.3e (%s)" % (worst[0], worst[1]), flush=True)
+    # update: exact FP32 formula applied to the GPU's own FP16 gradient
+    w32, v32 = w.astype(np.float32), np.zeros(w.size, np.float32)
+    O.sgd_momentum_flat(g16.astype(np.float32), w32, v32, np.float32(lr), np.float32(mu), np.float32(wd_),
+                        np.float32(1.0 / loss_scale), want_lowp=False)
+    assert np.array_equal(out["w"], w32.astype(f64)) and np.array_equal(out["v"], v32.astype(f64))
+    assert np.array_equal(out["w16"], O.round_binary16(out["w"]))
+    ctx.close()
+
+
+def test_step_resnet50_batch2_in_situ():
+    check_step_in_situ(2, (224, 224), True, (3, 4, 6, 3))
+
+
+def test_step_small_in_situ_ragged():
+    check_step_in_situ(3, (32, 48), True, (2, 2))
+
+
+def test_step_without_update_and_determinism_of_forward():
+    cfg, net, w, x, lab = make_problem(2, (32, 32), True, (1, 1))
+    ctx1, o1 = run_gpu(cfg, w, x, lab, None)
+    assert np.array_equal(o1["w"], w.astype(np.float64)) and np.all(o1["v"] == 0)
+    ctx2, o2 = run_gpu(cfg, w, x, lab, None)
+    assert o1["loss"] == o2["loss"]
+    assert np.array_equal(host(ctx1.tensor("logits")), host(ctx2.tensor("logits")))
+    # filter gradients use FP32 atomics: equal up to the last FP16 bit or so
+    assert rel_err(o1["g16"], o2["g16"]) <= 2e-3
+    with pytest.raises(P.Rn50Error):
+        ctx1.tensor("nonexistent.conv")
+    ctx1.close(); ctx2.close()
+
+
+def test_kernels_on_network_tensors():
+    """Every kernel of the path, one at a time, on the tensors of a real (oracle-computed) training
+    step of a small full-topology network: element-wise 2e-2 for each."""
+    batch, hw, blocks, ls = 4, (64, 64), (1, 1, 1, 1), 1024.0
+    cfg, net, w, x, lab = make_problem(batch, hw, True, blocks, 1000, ls)
+    f64 = np.float64
+    ref = R.step_ref(net, x.astype(f64), lab, w.astype(f64), np.zeros(w.size), 0.1, 0.9, 1e-4, loss_scale=ls)
+    t = ref["t"]
+    w16 = O.round_binary16(w.astype(f64))
+    douts = {b["name"] + "c3": t[b["name"] + ".dout"] for b in net.block_list}
+    for nm, cv in net.convs.items():
+        print("[case] kernels on tensors of %s" % nm, flush=True)
+        xin, conv, outp, dconv = t[nm + ".in"], t[nm + ".conv"], t[nm + ".out"], t[nm + ".dconv"]
+        n, h, wd, cin = xin.shape
+        k, r = cv["cout"], cv["r"]
+        d = P.make_conv_desc(n, h, wd, cin, k, r, r, cv["stride"], cv["pad"])
+        filt = net.view(w16, nm + ".w")
+        y = torch.zeros(conv.shape, dtype=torch.float16, device=DEV)
+        P.conv_fwd(d, dev_h(xin), dev_h(filt), y)
+        assert rel_err(host(y), conv) <= TOL16
+        m, c = conv.size // k, k
+        relu = not nm.endswith("p")
+        res = nm.endswith("c3")
+        gamma, beta = net.view(w.astype(f64), nm + ".gamma"), net.view(w.astype(f64), nm + ".beta")
+        bd = P.make_bn_desc(m, c, 1e-5, relu, res)
+        blk = nm[:-2] if not nm.endswith("p") else nm[:-1]
+        if res:
+            proj = blk + "p"
+            shortcut = t[proj + ".out"] if proj in net.convs else t[blk + ".in"]
+        yb = torch.zeros(m, c, dtype=torch.float16, device=DEV)
+        mean = torch.zeros(c, dtype=torch.float32, device=DEV)
+        invstd = torch.zeros(c, dtype=torch.float32, device=DEV)
+        P.bn_relu_fwd(bd, dev_h(conv), dev_f(gamma), dev_f(beta), dev_h(shortcut) if res else None, yb, mean, invstd)
+        assert rel_err(host(yb), outp) <= TOL16
+        if m >= 64:
+            assert rel_err_fp32(host(invstd), t[nm + ".invstd"]) <= 1e-4
+        dw = torch.zeros(k, r, r, cin, dtype=torch.float16, device=DEV)
+        P.conv_wgrad(d, dev_h(xin), dev_h(dconv), dw)
+        s = net.seg[nm + ".w"]
+        assert rel_err(host(dw), ref["grad"][s.offset:s.offset + s.count]) <= TOL16
+        if nm != "stem":
+            dx = torch.zeros(xin.shape, dtype=torch.float16, device=DEV)
+            P.conv_dgrad(d, dev_h(dconv), dev_h(filt), dx)
+            assert rel_err(host(dx), O.conv_dgrad(dconv, filt, xin.shape, cv["stride"], cv["pad"])) <= TOL16
+        if nm in douts:                                   # BN backward where the incoming gradient was kept
+            dxb = torch.zeros(m, c, dtype=torch.float16, device=DEV)
+            dres = torch.zeros(m, c, dtype=torch.float16, device=DEV)
+            dg = torch.zeros(c, dtype=torch.float16, device=DEV)
+            db = torch.zeros(c, dtype=torch.float16, device=DEV)
+            P.bn_relu_bwd(bd, dev_h(douts[nm]), dev_h(conv), dev_h(outp), dev_f(gamma), dev_f(t[nm + ".mean"]),
+                          dev_f(t[nm + ".invstd"]), dxb, dres, dg, db)
+            assert rel_err(host(dxb), dconv) <= TOL16
+            sg, sb = net.seg[nm + ".gamma"], net.seg[nm + ".beta"]
+            assert rel_err(host(dg), ref["grad"][sg.offset:sg.offset + sg.count]) <= TOL16
+            assert rel_err(host(db), ref["grad"][sb.offset:sb.offset + sb.count]) <= TOL16

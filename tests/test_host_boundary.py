@@ -1,0 +1,84 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, validates arguments before touching the GPU, and its flat parameter layout agrees
+with the oracle's independently written one."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1811_05233_amd as P
+from oracle import resnet50 as R
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    src = open(os.path.join(ROOT, "include", "rn50.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b([a-z][a-z0-9_]*)\s*\(", src)
+    return sorted(set(n for n in names if n not in ("defined",)))
+
+
+def test_library_exports_every_declared_symbol():
+    l = ctypes.CDLL(P.LIB_PATH)
+    declared = header_functions()
+    assert "rn50_step" in declared and "conv_wgrad" in declared and len(declared) >= 20
+    for name in declared:
+        assert hasattr(l, name), name
+    assert set(P.EXPORTS) == set(declared)
+    P.lib()
+
+
+def test_status_strings():
+    l = P.lib()
+    assert l.rn50_status_string(0) == b"ok"
+    for rc in range(-6, 0):
+        assert len(l.rn50_status_string(rc)) > 0
+
+
+@pytest.mark.parametrize("kw", [
+    dict(batch=32), dict(batch=2, image_hw=(56, 56), has_stem=False, blocks=(1,)),
+    dict(batch=4, image_hw=(64, 64), blocks=(1, 1, 1, 1)), dict(batch=1, image_hw=(32, 32), blocks=(2, 1), base_width=128, classes=16)])
+def test_flat_layout_matches_oracle(kw):
+    cfg = P.make_config(**kw)
+    net = R.Net(kw["batch"], kw.get("image_hw", (224, 224)), kw.get("has_stem", True), kw.get("blocks", (3, 4, 6, 3)),
+                kw.get("base_width", 64), kw.get("classes", 1000))
+    lay = P.rn50_param_layout(cfg)
+    assert P.rn50_param_count(cfg) == net.param_count
+    assert lay == [(s.kind, s.offset, s.count, s.fan_in) for s in net.segments]
+    assert P.rn50_workspace_bytes(cfg) > 0
+
+
+def test_resnet50_param_count():
+    assert P.rn50_param_count(P.make_config(32)) == 25557032
+
+
+def test_bad_configs_and_null_arguments():
+    l = P.lib()
+    for kw in [dict(batch=0), dict(batch=2, base_width=48), dict(batch=2, classes=1001), dict(batch=2, image_hw=(223, 224)),
+               dict(batch=2, blocks=(0,)), dict(batch=2, dt=P.RN50_BF16)]:
+        cfg = P.make_config(**kw)
+        assert P.rn50_param_count(cfg) == 0 and P.rn50_workspace_bytes(cfg) == 0
+        h = ctypes.c_void_p()
+        assert l.rn50_create(ctypes.byref(h), ctypes.byref(cfg), None, 0) < 0
+    cfg = P.make_config(2, (56, 56), False, (1,))
+    h = ctypes.c_void_p()
+    assert l.rn50_create(ctypes.byref(h), ctypes.byref(cfg), None, 0) == -4          # workspace
+    assert l.rn50_create(None, ctypes.byref(cfg), None, 0) == -1
+    assert l.rn50_step(None, None, None, None, None, None, None, None, None, None) == -1
+    # kernels: validation happens before any launch, so these run without a GPU
+    d = P.make_conv_desc(1, 8, 8, 60, 64, 1, 1, 1, 0)
+    assert l.conv_fwd(ctypes.byref(d), None, None, None, None, 0, None) == -2
+    d = P.make_conv_desc(1, 8, 8, 64, 64, 1, 1, 1, 0)
+    assert l.conv_fwd(ctypes.byref(d), None, None, None, None, 0, None) == -1
+    assert l.conv_fwd(ctypes.byref(d), 16, 32, 8, None, 0, None) == -5              # misaligned y
+    assert P.conv_workspace_bytes(d, P.CONV_DGRAD) == 64 * 64 * 2
+    assert l.conv_dgrad(ctypes.byref(d), 16, 32, 48, None, 0, None) == -4
+    b = P.make_bn_desc(10, 12)
+    assert l.bn_relu_fwd(ctypes.byref(b), None, None, None, None, None, None, None, None, 0, None) == -2
+    assert l.ls_xent_fwd_bwd(0, 10, None, None, 0.1, 1.0, None, None, None, 0, None) == -2
+    assert l.ls_xent_fwd_bwd(4, 10, None, None, 0.1, 1.0, None, None, None, 1, None) == -3
+    assert l.sgd_momentum_flat(8, None, 0, 1.0, None, None, None, 0.1, 0.9, 0.0, None) == -1
+    assert l.sgd_momentum_flat(0, None, 0, 1.0, None, None, None, 0.1, 0.9, 0.0, None) == 0
