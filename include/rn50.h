@@ -205,6 +205,24 @@ int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* labels,
  * *elem_bytes = 2 or 4.  Unknown name: RN50_ERR_SHAPE. */
 int rn50_tensor(rn50_ctx* ctx, const char* name, void** ptr, size_t* elems, int* elem_bytes);
 
+/* ------------------------------------------------------------------------------------------
+ * Measurement aid (not part of the training path).  Between rn50_profile_begin and
+ * rn50_profile_end every kernel launch of this library is bracketed by a pair of HIP events on
+ * its stream.  rn50_profile_end synchronises the device and returns, per kernel, the number of
+ * launches, the summed event-to-event time, and the summed ALGORITHMIC work of those launches:
+ * flops = 2*M*N*K of the convolution as defined (live taps only), bytes = compulsory HBM
+ * traffic (each operand read once, each result written once).  Process-wide, not thread-safe.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct {
+    const char* name;   /* kernel name as it appears in a rocprofv3 kernel trace (abbreviated) */
+    long long launches;
+    double total_ms;
+    double flops;
+    double bytes;
+} rn50_profile_entry;
+int rn50_profile_begin(void);
+int rn50_profile_end(rn50_profile_entry* out, int max_entries, int* n_out);
+
 #ifdef __cplusplus
 }
 #endif

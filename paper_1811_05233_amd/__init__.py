@@ -37,6 +37,11 @@ class rn50_config(ctypes.Structure):
                 ("keep_grads", ctypes.c_int)]
 
 
+class rn50_profile_entry(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_longlong), ("total_ms", ctypes.c_double),
+                ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
+
+
 class rn50_hparams(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float), ("wd", ctypes.c_float),
                 ("grad_scale", ctypes.c_float)]
@@ -66,6 +71,8 @@ _SIGNATURES = {
     "rn50_destroy": (None, [_vp]),
     "rn50_cast_params": (_i, [_sz, _vp, _vp, _i, _vp]),
     "rn50_step": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(rn50_hparams), _vp, _vp]),
+    "rn50_profile_begin": (_i, []),
+    "rn50_profile_end": (_i, [ctypes.POINTER(rn50_profile_entry), _i, ctypes.POINTER(_i)]),
     "rn50_tensor": (_i, [_vp, ctypes.c_char_p, ctypes.POINTER(_vp), ctypes.POINTER(_sz), ctypes.POINTER(_i)]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -180,6 +187,19 @@ def sgd_momentum_flat(n, grad, grad_scale, master_w, momentum, w_lowp_out, lr, m
 
 def rn50_cast_params(n, master_w, w_lowp, dt=RN50_F16):
     _check(lib().rn50_cast_params(n, _ptr(master_w), _ptr(w_lowp), dt, _stream()), "rn50_cast_params")
+
+
+def rn50_profile_begin():
+    _check(lib().rn50_profile_begin(), "rn50_profile_begin")
+
+
+def rn50_profile_end():
+    """List of dicts (name, launches, total_ms, flops, bytes), one per kernel that ran."""
+    buf = (rn50_profile_entry * 64)()
+    n = _i()
+    _check(lib().rn50_profile_end(buf, 64, ctypes.byref(n)), "rn50_profile_end")
+    return [dict(name=buf[i].name.decode(), launches=int(buf[i].launches), total_ms=float(buf[i].total_ms),
+                 flops=float(buf[i].flops), bytes=float(buf[i].bytes)) for i in range(n.value)]
 
 
 # ------------------------------------------------------------------ whole step

@@ -9,6 +9,7 @@
 // E[x^2]-E[x]^2 does not cancel when |mean| >> sigma.
 #include "common.h"
 #include "misc_internal.h"
+#include "prof.h"
 
 namespace {
 
@@ -325,8 +326,16 @@ int rn50_bn_fwd_launch(long long m, int c, float eps, bool relu, const h16* x, c
                        const h16* res, h16* y, float* save_mean, float* save_invstd, float* ws, hipStream_t s)
 {
     const BnPlan p = plan_rows(m, c);
-    bn_stats_kernel<<<p.nblk, kThreads, 0, s>>>(m, c, x, ws, p.rows_per_block);
-    bn_stats_finalize_kernel<<<rn50_cdiv(c, 16), kThreads, 0, s>>>(m, c, eps, p.nblk, x, ws, save_mean, save_invstd);
+    const double elems = (double)m * c;
+    {
+        ProfScope ps(RN50_K_BN_STATS, 0.0, 2.0 * elems, s);
+        bn_stats_kernel<<<p.nblk, kThreads, 0, s>>>(m, c, x, ws, p.rows_per_block);
+    }
+    {
+        ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * p.nblk * c, s);
+        bn_stats_finalize_kernel<<<rn50_cdiv(c, 16), kThreads, 0, s>>>(m, c, eps, p.nblk, x, ws, save_mean, save_invstd);
+    }
+    ProfScope ps(RN50_K_BN_APPLY, 0.0, (res ? 6.0 : 4.0) * elems, s);
 #define RN50_BN_APPLY(R, Z) bn_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, x, gamma, beta, save_mean, \
                                                                               save_invstd, res, y, p.rows_per_block)
     if (relu) { if (res) RN50_BN_APPLY(true, true); else RN50_BN_APPLY(true, false); }
@@ -341,9 +350,17 @@ int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* 
 {
     const BnPlan p = plan_rows(m, c);
     float* sums = ws + (size_t)kMaxBlocks * 2 * c;
-    if (relu) bn_bwd_reduce_kernel<true><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, save_mean, save_invstd, ws, p.rows_per_block);
-    else      bn_bwd_reduce_kernel<false><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, save_mean, save_invstd, ws, p.rows_per_block);
-    bn_bwd_finalize_kernel<<<rn50_cdiv(c, 16), kThreads, 0, s>>>(c, p.nblk, ws, sums, dgamma, dbeta, dgamma32, dbeta32);
+    const double elems = (double)m * c;
+    {
+        ProfScope ps(RN50_K_BN_BWD_REDUCE, 0.0, (relu ? 6.0 : 4.0) * elems, s);
+        if (relu) bn_bwd_reduce_kernel<true><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, save_mean, save_invstd, ws, p.rows_per_block);
+        else      bn_bwd_reduce_kernel<false><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, save_mean, save_invstd, ws, p.rows_per_block);
+    }
+    {
+        ProfScope ps(RN50_K_BN_BWD_FINALIZE, 0.0, 8.0 * p.nblk * c, s);
+        bn_bwd_finalize_kernel<<<rn50_cdiv(c, 16), kThreads, 0, s>>>(c, p.nblk, ws, sums, dgamma, dbeta, dgamma32, dbeta32);
+    }
+    ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, ((relu ? 6.0 : 4.0) + 2.0 + (dres ? 2.0 : 0.0)) * elems, s);
 #define RN50_BN_BWD(R, Z) bn_bwd_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, gamma, save_mean, \
                                                                                 save_invstd, sums, dx, dres, p.rows_per_block)
     if (relu) { if (dres) RN50_BN_BWD(true, true); else RN50_BN_BWD(true, false); }

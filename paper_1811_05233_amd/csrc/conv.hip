@@ -15,6 +15,7 @@
 // loop applies.  The pixel range is split over workgroups and combined with FP32 atomic adds.
 #include "common.h"
 #include "conv_internal.h"
+#include "prof.h"
 
 namespace {
 
@@ -469,7 +470,7 @@ int grid_for(size_t work_items)
 inline int floordiv(int a, int b) { return (a >= 0) ? a / b : -((-a + b - 1) / b); }
 
 template <int BM, int BN, int BK, int WR, int WC>
-int launch_gather(GatherArgs& a, hipStream_t s)
+int launch_gather(GatherArgs& a, hipStream_t s, int kid, double flops, double bytes)
 {
     int total = 0;
     for (int c = 0; c < a.ncls; ++c) {
@@ -479,17 +480,29 @@ int launch_gather(GatherArgs& a, hipStream_t s)
     }
     if (total == 0) return RN50_OK;
     const int grid = total * (a.NO / BN);
+    ProfScope ps(kid, flops, bytes, s);
     gather_gemm_kernel<BM, BN, BK, WR, WC><<<grid, kThreads, 0, s>>>(a);
     return rn50_check_launch();
 }
 
-int dispatch_gather(GatherArgs& a, hipStream_t s)
+int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes)
 {
     if (a.CR == 32) {               // stem forward
-        return launch_gather<128, 64, 32, 2, 2>(a, s);
+        return launch_gather<128, 64, 32, 2, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
     }
-    if (a.NO % 128 == 0) return launch_gather<128, 128, 64, 2, 2>(a, s);
-    return launch_gather<128, 64, 64, 2, 2>(a, s);
+    if (a.NO % 128 == 0) return launch_gather<128, 128, 64, 2, 2>(a, s, RN50_K_GATHER_128x128x64, flops, bytes);
+    return launch_gather<128, 64, 64, 2, 2>(a, s, RN50_K_GATHER_128x64x64, flops, bytes);
+}
+
+// algorithmic work of one convolution (either direction): 2*M*N*K flops; bytes = input pixels actually
+// needed + filter + output, 2 bytes each
+double conv_flops(const conv_desc& d, int P, int Q) { return 2.0 * d.n * P * Q * (double)d.k * d.r * d.s * d.c; }
+double conv_bytes(const conv_desc& d, int P, int Q, bool with_addend)
+{
+    const double in = (d.r == 1 && d.stride > 1) ? (double)d.n * P * Q * d.c : (double)d.n * d.h * d.w * d.c;
+    double b = 2.0 * (in + (double)d.k * d.r * d.s * d.c + (double)d.n * P * Q * d.k);
+    if (with_addend) b += 2.0 * d.n * d.h * d.w * d.c;
+    return b;
 }
 
 }  // namespace
@@ -521,12 +534,14 @@ size_t rn50_stem_packed_filter_bytes(const conv_desc& d) { return rn50_round_up(
 
 int rn50_stem_pad_image(const conv_desc& d, const h16* img, h16* padded, hipStream_t s)
 {
+    ProfScope ps(RN50_K_STEM_MISC, 0.0, (double)d.n * d.h * d.w * 6 + (double)d.n * (d.h + 6) * (d.w + 6) * 8, s);
     stem_pad_image_kernel<<<grid_for((size_t)d.n * (d.h + 6) * (d.w + 6)), kThreads, 0, s>>>(img, padded, d.n, d.h, d.w);
     return rn50_check_launch();
 }
 
 int rn50_stem_pack_filter(const conv_desc& d, const h16* w, h16* packed, hipStream_t s)
 {
+    ProfScope ps(RN50_K_STEM_MISC, 0.0, (double)d.k * (147 + 224) * 2, s);
     stem_pack_filter_kernel<<<rn50_cdiv(d.k * 7 * 32, kThreads), kThreads, 0, s>>>(w, packed, d.k);
     return rn50_check_launch();
 }
@@ -534,6 +549,7 @@ int rn50_stem_pack_filter(const conv_desc& d, const h16* w, h16* packed, hipStre
 int rn50_transpose_filter(const conv_desc& d, const h16* w, h16* wt, hipStream_t s)
 {
     const int T = d.r * d.s;
+    ProfScope ps(RN50_K_TRANSPOSE, 0.0, 4.0 * d.k * T * d.c, s);
     transpose_filter_kernel<<<(d.c / 32) * (d.k / 32) * T, kThreads, 0, s>>>(w, wt, d.k, T, d.c);
     return rn50_check_launch();
 }
@@ -541,12 +557,14 @@ int rn50_transpose_filter(const conv_desc& d, const h16* w, h16* wt, hipStream_t
 int rn50_fill_zero(float* p, size_t n, hipStream_t s)
 {
     // n must be a multiple of 4 floats
+    ProfScope ps(RN50_K_FILL, 0.0, 4.0 * n, s);
     fill_zero_kernel<<<grid_for(n / 4), kThreads, 0, s>>>(reinterpret_cast<f32x4*>(p), n / 4);
     return rn50_check_launch();
 }
 
 int rn50_cast_f32_to_h16(const float* src, h16* dst, size_t n, hipStream_t s)
 {
+    ProfScope ps(RN50_K_CAST, 0.0, 6.0 * n, s);
     cast_f32_to_h16_kernel<<<grid_for(n / 8 + 1), kThreads, 0, s>>>(src, dst, n);
     return rn50_check_launch();
 }
@@ -573,7 +591,7 @@ int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y,
                 a.dh[0][t] = (signed char)(r - d.pad); a.dw[0][t] = (signed char)(q - d.pad); a.bt[0][t] = (signed char)t;
             }
     }
-    return dispatch_gather(a, s);
+    return dispatch_gather(a, s, conv_flops(d, P, Q), conv_bytes(d, P, Q, false));
 }
 
 // Data gradient.  wt is the filter transposed to [C][R][S][K].  addend (nullable) has dx's layout.
@@ -606,7 +624,10 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
             }
             a.ntaps[c] = nt;
         }
-    return dispatch_gather(a, s);
+    // a strided 1x1 data gradient still writes every pixel of dx
+    const double bytes = conv_bytes(d, P, Q, addend != nullptr) +
+                         ((d.r == 1 && d.stride > 1) ? 2.0 * d.n * ((double)d.h * d.w - (double)P * Q) * d.c : 0.0);
+    return dispatch_gather(a, s, conv_flops(d, P, Q), bytes);
 }
 
 size_t rn50_wgrad_acc_floats(const conv_desc& d)
@@ -643,6 +664,9 @@ int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, floa
     a.pix_per_split = slabs_per * BKP;
     const int nsplit = (int)((slabs + slabs_per - 1) / slabs_per);
     const int grid = tiles * nsplit;
+    const double bytes = 2.0 * ((double)d.n * d.h * d.w * d.c + (double)d.n * P * Q * d.k) + 4.0 * d.k * d.r * d.s * d.c;
+    ProfScope ps(stem ? RN50_K_WGRAD_STEM : (BM == 128 ? RN50_K_WGRAD_128x128x64 : RN50_K_WGRAD_64x64x128),
+                 conv_flops(d, P, Q), bytes, s);
     if (stem) wgrad_kernel<64, 64, 128, 32, true><<<grid, kThreads, 0, s>>>(a);
     else if (BM == 128) wgrad_kernel<128, 128, 64, 64, false><<<grid, kThreads, 0, s>>>(a);
     else wgrad_kernel<64, 64, 128, 64, false><<<grid, kThreads, 0, s>>>(a);
@@ -651,6 +675,7 @@ int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, floa
 
 int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, float* out, hipStream_t s)
 {
+    ProfScope ps(RN50_K_STEM_MISC, 0.0, (double)d.k * (147 + 256) * 4, s);
     stem_unpack_wgrad_kernel<<<rn50_cdiv(d.k * 147, kThreads), kThreads, 0, s>>>(acc, out, d.k);
     return rn50_check_launch();
 }

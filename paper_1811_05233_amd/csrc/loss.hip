@@ -2,6 +2,7 @@
 // launch.  One workgroup of 16 wavefronts; each wavefront owns rows i = wave, wave+16, ...
 // and keeps its partial loss in a fixed order, so the result is deterministic.
 #include "common.h"
+#include "prof.h"
 
 namespace {
 
@@ -56,6 +57,7 @@ extern "C" int ls_xent_fwd_bwd(int batch, int classes, const float* logits, cons
     if (batch < 1 || batch > 65536 || classes < 2 || classes > 65536) return RN50_ERR_SHAPE;
     RN50_REQUIRE_PTR(logits); RN50_REQUIRE_PTR(labels); RN50_REQUIRE_PTR(loss_mean); RN50_REQUIRE_PTR(dlogits);
     RN50_REQUIRE_ALIGNED(logits); RN50_REQUIRE_ALIGNED(dlogits);
+    ProfScope ps(RN50_K_LOSS, 0.0, 6.0 * batch * classes, static_cast<hipStream_t>(stream));
     ls_xent_kernel<<<1, kWaves * 64, 0, static_cast<hipStream_t>(stream)>>>(
         batch, classes, logits, labels, eps, grad_scale, loss_mean, loss_per_sample, static_cast<h16*>(dlogits));
     return rn50_check_launch();

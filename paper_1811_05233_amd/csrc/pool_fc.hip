@@ -3,6 +3,7 @@
 // accesses on NHWC data (a thread owns 8 consecutive channels).
 #include "common.h"
 #include "misc_internal.h"
+#include "prof.h"
 
 namespace {
 
@@ -205,6 +206,7 @@ int grid_for(size_t items) {
 int rn50_maxpool_fwd(int N, int H, int W, int C, const h16* x, h16* y, uint8_t* arg, hipStream_t s)
 {
     const int P = (H + 2 - 3) / 2 + 1, Q = (W + 2 - 3) / 2 + 1;
+    ProfScope ps(RN50_K_POOL, 0.0, 2.0 * N * C * ((double)H * W + 1.5 * P * Q), s);
     maxpool_fwd_kernel<<<grid_for((size_t)N * P * Q * (C / 8)), kThreads, 0, s>>>(N, H, W, C, P, Q, x, y, arg);
     return rn50_check_launch();
 }
@@ -212,18 +214,21 @@ int rn50_maxpool_fwd(int N, int H, int W, int C, const h16* x, h16* y, uint8_t* 
 int rn50_maxpool_bwd(int N, int H, int W, int C, const h16* dy, const uint8_t* arg, h16* dx, hipStream_t s)
 {
     const int P = (H + 2 - 3) / 2 + 1, Q = (W + 2 - 3) / 2 + 1;
+    ProfScope ps(RN50_K_POOL, 0.0, 2.0 * N * C * ((double)H * W + 1.5 * P * Q), s);
     maxpool_bwd_kernel<<<grid_for((size_t)N * H * W * (C / 8)), kThreads, 0, s>>>(N, H, W, C, P, Q, dy, arg, dx);
     return rn50_check_launch();
 }
 
 int rn50_avgpool_fwd(int N, int HW, int C, const h16* x, h16* y, hipStream_t s)
 {
+    ProfScope ps(RN50_K_POOL, 0.0, 2.0 * N * C * (HW + 1.0), s);
     avgpool_fwd_kernel<<<rn50_cdiv((long long)N * (C / 8), kThreads), kThreads, 0, s>>>(N, HW, C, x, y);
     return rn50_check_launch();
 }
 
 int rn50_fc_fwd(int B, int Cin, int Cout, const h16* a, const h16* Wt, const float* bias, float* z, hipStream_t s)
 {
+    ProfScope ps(RN50_K_FC, 2.0 * B * Cin * Cout, 2.0 * Cin * (B + Cout) + 4.0 * B * Cout, s);
     fc_fwd_kernel<<<rn50_cdiv(Cout, kThreads / 64), kThreads, 0, s>>>(B, Cin, Cout, a, Wt, bias, z);
     return rn50_check_launch();
 }
@@ -231,6 +236,7 @@ int rn50_fc_fwd(int B, int Cin, int Cout, const h16* a, const h16* Wt, const flo
 int rn50_fc_bwd(int B, int Cin, int Cout, int HW, const h16* a, const h16* Wt, const h16* dz, float* dWt, float* db,
                 h16* dx, hipStream_t s)
 {
+    ProfScope ps(RN50_K_FC, 4.0 * B * Cin * Cout, 2.0 * Cin * (B + Cout) + 4.0 * Cin * Cout + 2.0 * B * Cin * HW, s);
     fc_bwd_w_kernel<<<rn50_cdiv((long long)Cout * (Cin / 8), kThreads), kThreads, 0, s>>>(B, Cin, Cout, a, dz, dWt, db);
     const int slabs = (Cin / 8 + 31) / 32;
     fc_bwd_a_avgpool_bwd_kernel<<<B * slabs, kThreads, 0, s>>>(Cin, Cout, HW, Wt, dz, dx);

@@ -1,0 +1,41 @@
+// Optional per-kernel timing with HIP events (off unless rn50_profile_begin was called).
+// Every launcher wraps its launch in a ProfScope naming the kernel and its algorithmic work.
+#pragma once
+#include "common.h"
+
+enum Rn50Kernel {
+    RN50_K_GATHER_128x128x64 = 0,   // conv forward / data gradient, 128x128 tile
+    RN50_K_GATHER_128x64x64,        // conv forward / data gradient, 128x64 tile
+    RN50_K_GATHER_STEM,             // stem forward (128x64 tile, 32-wide K slabs)
+    RN50_K_WGRAD_128x128x64,
+    RN50_K_WGRAD_64x64x128,
+    RN50_K_WGRAD_STEM,
+    RN50_K_BN_STATS,
+    RN50_K_BN_STATS_FINALIZE,
+    RN50_K_BN_APPLY,
+    RN50_K_BN_BWD_REDUCE,
+    RN50_K_BN_BWD_FINALIZE,
+    RN50_K_BN_BWD_APPLY,
+    RN50_K_SGD,
+    RN50_K_CAST,
+    RN50_K_FILL,
+    RN50_K_TRANSPOSE,
+    RN50_K_POOL,
+    RN50_K_FC,
+    RN50_K_LOSS,
+    RN50_K_STEM_MISC,
+    RN50_K_COUNT
+};
+
+bool rn50_prof_active();
+void rn50_prof_record_begin(int kernel, double flops, double bytes, hipStream_t s);
+void rn50_prof_record_end(hipStream_t s);
+
+struct ProfScope {
+    hipStream_t s;
+    bool on;
+    ProfScope(int kernel, double flops, double bytes, hipStream_t stream) : s(stream), on(rn50_prof_active()) {
+        if (on) rn50_prof_record_begin(kernel, flops, bytes, s);
+    }
+    ~ProfScope() { if (on) rn50_prof_record_end(s); }
+};

@@ -8,6 +8,7 @@
 #include "common.h"
 #include "conv_internal.h"
 #include "misc_internal.h"
+#include "prof.h"
 
 namespace {
 
@@ -372,6 +373,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     // ---- per-step preparation: zero the FP32 gradient accumulators, re-lay the filters ----
     RN50_TRY(rn50_fill_zero(c.grad32, rn50_round_up(L.param_count, 8), s));
     if (c.njobs > 0) {
+        ProfScope ps(RN50_K_TRANSPOSE, 0.0, 4.0 * c.wt_elems, s);
         transpose_all_kernel<<<c.transpose_blocks, kThreads, 0, s>>>(w16, c.wt_all, c.jobs, c.njobs);
         RN50_TRY(rn50_check_launch());
     }

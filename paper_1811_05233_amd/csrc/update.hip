@@ -4,6 +4,7 @@
 // Floating-point contraction is off in this file: the update is evaluated exactly as written
 // (separately rounded FP32 multiplies and adds), so it matches an FP32 host evaluation bit for bit.
 #include "common.h"
+#include "prof.h"
 #pragma clang fp contract(off)
 
 thread_local int rn50_tls_hip_error = 0;
@@ -111,6 +112,7 @@ extern "C" int sgd_momentum_flat(size_t n, const void* grad, int grad_dt, float 
     RN50_REQUIRE_ALIGNED(w_lowp_out);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = stream_grid(n);
+    ProfScope ps(RN50_K_SGD, 0.0, (w_lowp_out ? 20.0 : 18.0) * (double)n, s);
     if (w_lowp_out)
         sgd_momentum_kernel<true><<<grid, kThreads, 0, s>>>(n, static_cast<const h16*>(grad), grad_scale, master_w,
                                                             momentum, static_cast<h16*>(w_lowp_out), lr, mu, wd);
@@ -126,6 +128,7 @@ extern "C" int rn50_cast_params(size_t n, const float* master_w, void* w_lowp, i
     if (n == 0) return RN50_OK;
     RN50_REQUIRE_PTR(master_w); RN50_REQUIRE_PTR(w_lowp);
     RN50_REQUIRE_ALIGNED(master_w); RN50_REQUIRE_ALIGNED(w_lowp);
+    ProfScope ps(RN50_K_CAST, 0.0, 6.0 * (double)n, static_cast<hipStream_t>(stream));
     cast_params_kernel<<<stream_grid(n), kThreads, 0, static_cast<hipStream_t>(stream)>>>(
         n, master_w, static_cast<h16*>(w_lowp));
     return rn50_check_launch();
