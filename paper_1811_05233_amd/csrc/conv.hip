@@ -13,6 +13,8 @@
 // The filter gradient reduces over pixels, which is the strided dimension of both operands; its
 // loader transposes 8x8 half blocks in registers on the way into LDS, after which the same MFMA
 // loop applies.  The pixel range is split over workgroups and combined with FP32 atomic adds.
+#include <cstdlib>
+
 #include "common.h"
 #include "conv_internal.h"
 #include "prof.h"
@@ -46,17 +48,38 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {
 // ------------------------------------------------------------------------------------------------
 // gather GEMM (forward, data-gradient)
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WR, int WC>
-__global__ __launch_bounds__(kThreads) void gather_gemm_kernel(const GatherArgs a)
+// s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14])
+#define RN50_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xf) | 0x0f70 | (((n) >> 4) << 14))
+#define RN50_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xc07f)
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// m = q*d + r with 0 <= r < d, for 0 <= m < 2^24, using the precomputed float reciprocal of d.
+__device__ __forceinline__ void fast_divmod(int m, int d, float inv_d, int& q, int& r) {
+    q = (int)((float)m * inv_d);
+    r = m - q * d;
+    if (r < 0) { r += d; --q; }
+    else if (r >= d) { r -= d; ++q; }
+}
+
+// K-slabs travel global memory -> LDS directly (buffer_load ... lds, 16 bytes per lane, no staging
+// registers) into a ring of NST stages, so that NST-1 slabs are in flight while one is consumed.
+// Rows outside the image (zero padding, ragged last tile) use an out-of-range buffer offset, which
+// the hardware turns into zeros.  One workgroup barrier per K-slab.
+template <int BM, int BN, int BK, int NST, int OCC>
+__global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const GatherArgs a)
 {
+    constexpr int WR = 2, WC = 2;
     constexpr int CPR = BK / 8;            // 16-byte chunks per tile row
-    constexpr int RPP = kThreads / CPR;    // tile rows covered by one pass of the workgroup
-    constexpr int NA = BM / RPP, NB = BN / RPP;
+    constexpr int RPI = 64 / CPR;          // tile rows written by one wave-wide load (1 KB of LDS)
+    constexpr int NA = BM / RPI / 4, NB = BN / RPI / 4;   // loads per thread and K-slab
+    constexpr int NL = NA + NB;
     constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
     constexpr int KS = BK / 16;
     constexpr int STAGE = (BM + BN) * BK;
     constexpr int EP = BN + 8;             // epilogue row pitch in halfs
-    constexpr int LDS_HALFS = (2 * STAGE > BM * EP) ? 2 * STAGE : BM * EP;
+    constexpr int LDS_HALFS = (NST * STAGE > BM * EP) ? NST * STAGE : BM * EP;
+    constexpr unsigned kOutOfRange = 0x80000000u;
     __shared__ __attribute__((aligned(16))) h16 lds[LDS_HALFS];
 
     const int tid = threadIdx.x;
@@ -73,27 +96,75 @@ __global__ __launch_bounds__(kThreads) void gather_gemm_kernel(const GatherArgs 
     while (cls < a.ncls - 1 && mt >= a.mt_end[cls]) ++cls;
     if (cls > 0) mt -= a.mt_end[cls - 1];
     const int OHs = a.cOHs[cls], OWs = a.cOWs[cls];
+    const float inv_oh = a.inv_oh[cls], inv_ow = a.inv_ow[cls];
     const int M = a.NB * OHs * OWs;
     const int ntaps = a.ntaps[cls];
+    const int IH = a.IH, IW = a.IW, lda = a.lda, CR = a.CR;
 
-    // ---- per-thread load coordinates ----
-    const int chunk = tid % CPR, rowl = tid / CPR;
-    int a_h0[NA], a_w0[NA], a_nb[NA];
+    // ---- this lane's place in a wave-wide load: row inside the group of RPI rows, logical chunk ----
+    int row_in_grp, phys;
+    if (BK == 64) { row_in_grp = lane >> 3; phys = lane & 7; }
+    else { row_in_grp = 2 * (lane >> 3) + ((lane & 7) >> 2); phys = lane & 3; }
+    auto logical_chunk = [&](int row) {
+        if (BK == 64) return phys ^ ((row ^ (row >> 3)) & 7);
+        return phys ^ ((row >> 1) & 3);
+    };
+
+    int a_h0[NA], a_w0[NA];
+    unsigned a_voff[NA], b_voff[NB];
 #pragma unroll
-    for (int i = 0; i < NA; ++i) {
-        const int m = mt * BM + rowl + i * RPP;
+    for (int j = 0; j < NA; ++j) {
+        const int row = (wave + 4 * j) * RPI + row_in_grp;
+        const int m = mt * BM + row;
         if (m < M) {
-            const int wq = m % OWs, t = m / OWs;
-            const int hq = t % OHs, n = t / OHs;
-            a_h0[i] = hq * a.a_mul + a.a_off;
-            a_w0[i] = wq * a.a_mul + a.a_off;
-            a_nb[i] = n * a.IH * a.IW;
+            int t, wq, n, hq;
+            fast_divmod(m, OWs, inv_ow, t, wq);
+            fast_divmod(t, OHs, inv_oh, n, hq);
+            a_h0[j] = hq * a.a_mul + a.a_off;
+            a_w0[j] = wq * a.a_mul + a.a_off;
+            a_voff[j] = (unsigned)(((n * IH + a_h0[j]) * IW + a_w0[j]) * lda) * 2u + logical_chunk(row) * 16;
         } else {
-            a_h0[i] = -(1 << 20); a_w0[i] = 0; a_nb[i] = 0;
+            a_h0[j] = -(1 << 20); a_w0[j] = 0; a_voff[j] = 0;
         }
     }
-    const h16* b_base = a.B + ((size_t)(nt * BN + rowl) * a.T) * a.CR + chunk * 8;
-    const size_t b_rowstep = (size_t)RPP * a.T * a.CR;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int row = (wave + 4 * j) * RPI + row_in_grp;
+        b_voff[j] = (unsigned)((nt * BN + row) * a.T * CR) * 2u + logical_chunk(row) * 16;
+    }
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<h16*>(a.A), 0, a.a_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(const_cast<h16*>(a.B), 0, a.b_bytes, 0x00020000);
+
+    const int KC = CR / BK;
+    const int kiters = ntaps * KC;
+    int ld_ti = 0, ld_cc = 0, ld_stage = 0;      // next slab to load: tap, channel slab, ring stage (wave-uniform)
+
+    auto issue_slab = [&]() {
+        const int tap = a.tap[cls][ld_ti];                 // packed: dh | dw << 8 | filter tap << 16
+        const int dh = (int)(signed char)(tap & 0xff), dw = (int)(signed char)((tap >> 8) & 0xff), bt = tap >> 16;
+        const int a_delta = ((dh * IW + dw) * lda + ld_cc * BK) * 2;          // bytes, wave-uniform
+        const unsigned b_delta = (unsigned)(bt * CR + ld_cc * BK) * 2u;
+        h16* sa = lds + ld_stage * STAGE;
+        h16* sb = sa + BM * BK;
+#pragma unroll
+        for (int j = 0; j < NA; ++j) {
+            const int ih = a_h0[j] + dh, iw = a_w0[j] + dw;
+            const bool ok = (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW;
+            const unsigned voff = ok ? a_voff[j] + (unsigned)a_delta : kOutOfRange;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(sa + (wave + 4 * j) * 512), 16, (int)voff, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(sb + (wave + 4 * j) * 512), 16,
+                                                     (int)(b_voff[j] + b_delta), 0, 0, 0);
+        if (++ld_cc == KC) { ld_cc = 0; ++ld_ti; }
+        if (++ld_stage == NST) ld_stage = 0;
+    };
+
+    // start the ring before touching anything else
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p)
+        if (p < kiters) issue_slab();
 
     f32x16 acc[TM][TN];
     if (a.addend) {
@@ -104,8 +175,9 @@ __global__ __launch_bounds__(kThreads) void gather_gemm_kernel(const GatherArgs 
             size_t opix = 0;
             const bool ok = m < M;
             if (ok) {
-                const int wq = m % OWs, t = m / OWs;
-                const int hq = t % OHs, n = t / OHs;
+                int t, wq, n, hq;
+                fast_divmod(m, OWs, inv_ow, t, wq);
+                fast_divmod(t, OHs, inv_oh, n, hq);
                 opix = ((size_t)n * a.OH + hq * a.o_mul + a.oph[cls]) * a.OW + wq * a.o_mul + a.opw[cls];
             }
 #pragma unroll
@@ -127,42 +199,14 @@ __global__ __launch_bounds__(kThreads) void gather_gemm_kernel(const GatherArgs 
                 for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
     }
 
-    const int KC = a.CR / BK;
-    const int kiters = ntaps * KC;
-    h16x8 ra[NA], rb[NB];
-
-    auto load_tile = [&](int kit) {
-        const int ti = kit / KC, cc = kit - ti * KC;
-        const int dh = a.dh[cls][ti], dw = a.dw[cls][ti], bt = a.bt[cls][ti];
-#pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const int ih = a_h0[i] + dh, iw = a_w0[i] + dw;
-            h16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if ((unsigned)ih < (unsigned)a.IH && (unsigned)iw < (unsigned)a.IW)
-                v = *reinterpret_cast<const h16x8*>(a.A + (size_t)(a_nb[i] + ih * a.IW + iw) * a.lda + cc * BK + chunk * 8);
-            ra[i] = v;
-        }
-        const h16* bp = b_base + (size_t)bt * a.CR + cc * BK;
-#pragma unroll
-        for (int i = 0; i < NB; ++i) rb[i] = *reinterpret_cast<const h16x8*>(bp + i * b_rowstep);
-    };
-    auto store_tile = [&](int stage) {
-        h16* sa = lds + stage * STAGE;
-        h16* sb = sa + BM * BK;
-#pragma unroll
-        for (int i = 0; i < NA; ++i) *reinterpret_cast<h16x8*>(sa + lds_off<BK>(rowl + i * RPP, chunk)) = ra[i];
-#pragma unroll
-        for (int i = 0; i < NB; ++i) *reinterpret_cast<h16x8*>(sb + lds_off<BK>(rowl + i * RPP, chunk)) = rb[i];
-    };
-
-    if (kiters > 0) {
-        load_tile(0);
-        store_tile(0);
-    }
-    __syncthreads();
+    int cur = 0;
     for (int kit = 0; kit < kiters; ++kit) {
-        const int cur = kit & 1;
-        if (kit + 1 < kiters) load_tile(kit + 1);
+        // slab `kit` has landed once at most the NST-2 younger slabs are outstanding
+        if (kit + NST - 2 < kiters) RN50_WAIT_VMCNT(NL * (NST - 2));
+        else RN50_WAIT_VMCNT(0);
+        RN50_WAIT_LGKMCNT0();                 // this wave's LDS reads of the previous slab are done
+        __builtin_amdgcn_s_barrier();         // everyone's part of slab kit is in LDS; stage (kit-1)%NST is free
+        if (kit + NST - 1 < kiters) issue_slab();
         const h16* sa = lds + cur * STAGE;
         const h16* sb = sa + BM * BK;
 #pragma unroll
@@ -182,9 +226,10 @@ __global__ __launch_bounds__(kThreads) void gather_gemm_kernel(const GatherArgs 
                     // (lane%32) and runs of 4 consecutive output channels
                     acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[tn], fa[tm], acc[tm][tn], 0, 0, 0);
         }
-        if (kit + 1 < kiters) store_tile(cur ^ 1);
-        __syncthreads();
+        if (++cur == NST) cur = 0;
     }
+    RN50_WAIT_LGKMCNT0();
+    __builtin_amdgcn_s_barrier();             // all waves are done reading the ring before it is reused
 
     // ---- epilogue: FP32 -> half, through LDS so that global stores are full 16-byte rows ----
 #pragma unroll
@@ -207,8 +252,9 @@ __global__ __launch_bounds__(kThreads) void gather_gemm_kernel(const GatherArgs 
         const int row = orl + i * ORPP;
         const int m = mt * BM + row;
         if (m < M) {
-            const int wq = m % OWs, t = m / OWs;
-            const int hq = t % OHs, n = t / OHs;
+            int t, wq, n, hq;
+            fast_divmod(m, OWs, inv_ow, t, wq);
+            fast_divmod(t, OHs, inv_oh, n, hq);
             const size_t opix = ((size_t)n * a.OH + hq * a.o_mul + a.oph[cls]) * a.OW + wq * a.o_mul + a.opw[cls];
             *reinterpret_cast<h16x8*>(a.out + opix * a.NO + nt * BN + oc * 8) =
                 *reinterpret_cast<const h16x8*>(lds + row * EP + oc * 8);
@@ -280,21 +326,22 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a)
             for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
 
     h16x8 r[8];
+    const h16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     auto load_mb = [&](long long pix0) {
         const long long p0 = pix0 + pg * 8;
         if (is_dy) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                h16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (p0 + j < pix_end) v = *reinterpret_cast<const h16x8*>(dy_ptr + (size_t)(p0 + j) * a.K);
-                r[j] = v;
+                const bool ok = p0 + j < pix_end;
+                const h16x8 v = *reinterpret_cast<const h16x8*>(dy_ptr + (ok ? (size_t)(p0 + j) * a.K : 0));
+                r[j] = ok ? v : zero8;
             }
         } else if (direct) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                h16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (p0 + j < pix_end) v = *reinterpret_cast<const h16x8*>(a.x + (size_t)(p0 + j) * a.C + c0);
-                r[j] = v;
+                const bool ok = p0 + j < pix_end;
+                const h16x8 v = *reinterpret_cast<const h16x8*>(a.x + c0 + (ok ? (size_t)(p0 + j) * a.C : 0));
+                r[j] = ok ? v : zero8;
             }
         } else {
             int q = (int)(p0 % a.Q);
@@ -303,19 +350,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a)
             int n = (int)(t / a.P);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                h16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-                if (p0 + j < pix_end && gran_ok) {
-                    if (kStem) {
-                        // padded image: always in bounds
-                        v = *reinterpret_cast<const h16x8*>(
-                            a.x + (((size_t)n * a.H + 2 * p + tap_r) * a.W + 2 * q) * 4 + gcol);
-                    } else {
-                        const int ih = p * a.stride - a.pad + tap_r, iw = q * a.stride - a.pad + tap_s;
-                        if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-                            v = *reinterpret_cast<const h16x8*>(a.x + (((size_t)n * a.H + ih) * a.W + iw) * a.C + c0);
-                    }
+                bool ok = p0 + j < pix_end && gran_ok;
+                size_t off;
+                if (kStem) {
+                    // padded image: always in bounds
+                    off = (((size_t)n * a.H + 2 * p + tap_r) * a.W + 2 * q) * 4 + gcol;
+                } else {
+                    const int ih = p * a.stride - a.pad + tap_r, iw = q * a.stride - a.pad + tap_s;
+                    ok = ok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+                    off = (((size_t)n * a.H + ih) * a.W + iw) * a.C + c0;
                 }
-                r[j] = v;
+                const h16x8 v = *reinterpret_cast<const h16x8*>(a.x + (ok ? off : 0));
+                r[j] = ok ? v : zero8;
                 if (++q == a.Q) { q = 0; if (++p == a.P) { p = 0; ++n; } }
             }
         }
@@ -468,8 +514,9 @@ int grid_for(size_t work_items)
 }
 
 inline int floordiv(int a, int b) { return (a >= 0) ? a / b : -((-a + b - 1) / b); }
+inline int pack_tap(int dh, int dw, int bt) { return (dh & 0xff) | ((dw & 0xff) << 8) | (bt << 16); }
 
-template <int BM, int BN, int BK, int WR, int WC>
+template <int BM, int BN, int BK, int NST, int OCC>
 int launch_gather(GatherArgs& a, hipStream_t s, int kid, double flops, double bytes)
 {
     int total = 0;
@@ -477,21 +524,35 @@ int launch_gather(GatherArgs& a, hipStream_t s, int kid, double flops, double by
         const long long M = (long long)a.NB * a.cOHs[c] * a.cOWs[c];
         total += (int)((M + BM - 1) / BM);
         a.mt_end[c] = total;
+        a.inv_oh[c] = 1.0f / (float)(a.cOHs[c] > 0 ? a.cOHs[c] : 1);
+        a.inv_ow[c] = 1.0f / (float)(a.cOWs[c] > 0 ? a.cOWs[c] : 1);
     }
     if (total == 0) return RN50_OK;
     const int grid = total * (a.NO / BN);
     ProfScope ps(kid, flops, bytes, s);
-    gather_gemm_kernel<BM, BN, BK, WR, WC><<<grid, kThreads, 0, s>>>(a);
+    gather_gemm_kernel<BM, BN, BK, NST, OCC><<<grid, kThreads, 0, s>>>(a);
     return rn50_check_launch();
 }
 
 int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes)
 {
-    if (a.CR == 32) {               // stem forward
-        return launch_gather<128, 64, 32, 2, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
-    }
-    if (a.NO % 128 == 0) return launch_gather<128, 128, 64, 2, 2>(a, s, RN50_K_GATHER_128x128x64, flops, bytes);
-    return launch_gather<128, 64, 64, 2, 2>(a, s, RN50_K_GATHER_128x64x64, flops, bytes);
+    if (a.CR == 32)                 // stem forward
+        return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
+    long long rows = 0;
+    for (int c = 0; c < a.ncls; ++c) rows += (long long)a.NB * a.cOHs[c] * a.cOWs[c];
+    static int dev_tile = -1;
+    if (dev_tile < 0) { const char* e = getenv("RN50_TILE"); dev_tile = e ? atoi(e) : 0; }
+    if (dev_tile == 1 && a.NO % 128 == 0) return launch_gather<128, 128, 32, 4, 2>(a, s, RN50_K_GATHER_128x128x64, flops, bytes);
+    if (dev_tile == 2 && a.NO % 128 == 0) return launch_gather<128, 128, 64, 3, 1>(a, s, RN50_K_GATHER_128x128x64, flops, bytes);
+    if (dev_tile == 3) return launch_gather<64, 64, 64, 4, 2>(a, s, RN50_K_GATHER_64x64x64, flops, bytes);
+    if (dev_tile == 4) return launch_gather<128, 64, 64, 3, 2>(a, s, RN50_K_GATHER_128x64x64, flops, bytes);
+    if (dev_tile == 5) return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_64x64x64, flops, bytes);
+    // prefer the large tile while it still yields about two workgroups per compute unit
+    if (a.NO % 128 == 0 && (rows / 128) * (a.NO / 128) >= 400)
+        return launch_gather<128, 128, 32, 4, 2>(a, s, RN50_K_GATHER_128x128x64, flops, bytes);
+    if ((rows / 128) * (a.NO / 64) >= 400)
+        return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_128x64x64, flops, bytes);
+    return launch_gather<64, 64, 64, 4, 2>(a, s, RN50_K_GATHER_64x64x64, flops, bytes);
 }
 
 // algorithmic work of one convolution (either direction): 2*M*N*K flops; bytes = input pixels actually
@@ -517,7 +578,9 @@ int rn50_conv_validate(const conv_desc* d)
     if (!d) return RN50_ERR_NULL;
     if (d->dt != RN50_F16) return RN50_ERR_DTYPE;
     if (d->n < 1 || d->h < 1 || d->w < 1 || d->k < 64 || d->k % 64 != 0) return RN50_ERR_SHAPE;
-    if ((long long)d->n * d->h * d->w * (d->c > d->k ? d->c : d->k) >= (1ll << 31)) return RN50_ERR_SHAPE;
+    // tensors stay below 2 GiB (32-bit buffer offsets) and pixel counts below 2^24 (float reciprocal division)
+    if ((long long)d->n * (d->h + 6) * (d->w + 6) * (d->c > d->k ? d->c : d->k) >= (1ll << 30)) return RN50_ERR_SHAPE;
+    if ((long long)d->n * d->h * d->w >= (1ll << 24)) return RN50_ERR_SHAPE;
     if (rn50_conv_is_stem(*d)) return (d->h % 2 == 0 && d->w % 2 == 0) ? RN50_OK : RN50_ERR_SHAPE;
     if (d->c < 64 || d->c % 64 != 0) return RN50_ERR_SHAPE;
     if (d->r != d->s || (d->r != 1 && d->r != 3)) return RN50_ERR_SHAPE;
@@ -579,16 +642,20 @@ int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y,
     a.ncls = 1; a.cOHs[0] = P; a.cOWs[0] = Q; a.oph[0] = 0; a.opw[0] = 0;
     a.a_mul = d.stride;
     if (rn50_conv_is_stem(d)) {
+        a.a_bytes = (unsigned)((size_t)d.n * (d.h + 6) * (d.w + 6) * 4 * sizeof(h16));
+        a.b_bytes = (unsigned)((size_t)d.k * 7 * 32 * sizeof(h16));
         a.IH = d.h + 6; a.IW = d.w + 6; a.lda = 4; a.CR = 32; a.T = 7; a.a_off = 0;
         a.ntaps[0] = 7;
-        for (int r = 0; r < 7; ++r) { a.dh[0][r] = (signed char)r; a.dw[0][r] = 0; a.bt[0][r] = (signed char)r; }
+        for (int r = 0; r < 7; ++r) a.tap[0][r] = pack_tap(r, 0, r);
     } else {
+        a.a_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.c * sizeof(h16));
+        a.b_bytes = (unsigned)((size_t)d.k * d.r * d.s * d.c * sizeof(h16));
         a.IH = d.h; a.IW = d.w; a.lda = d.c; a.CR = d.c; a.T = d.r * d.s; a.a_off = 0;
         a.ntaps[0] = d.r * d.s;
         for (int r = 0; r < d.r; ++r)
             for (int q = 0; q < d.s; ++q) {
                 const int t = r * d.s + q;
-                a.dh[0][t] = (signed char)(r - d.pad); a.dw[0][t] = (signed char)(q - d.pad); a.bt[0][t] = (signed char)t;
+                a.tap[0][t] = pack_tap(r - d.pad, q - d.pad, t);
             }
     }
     return dispatch_gather(a, s, conv_flops(d, P, Q), conv_bytes(d, P, Q, false));
@@ -600,6 +667,8 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
     GatherArgs a = {};
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     a.A = dy; a.B = wt; a.out = dx; a.addend = addend;
+    a.a_bytes = (unsigned)((size_t)d.n * P * Q * d.k * sizeof(h16));
+    a.b_bytes = (unsigned)((size_t)d.k * d.r * d.s * d.c * sizeof(h16));
     a.NB = d.n; a.IH = P; a.IW = Q; a.lda = d.k; a.CR = d.k; a.T = d.r * d.s; a.NO = d.c;
     a.OH = d.h; a.OW = d.w; a.a_mul = 1; a.a_off = 0; a.o_mul = d.stride;
     a.ncls = d.stride * d.stride;
@@ -616,9 +685,7 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
                 for (int q = 0; q < d.s; ++q) {
                     const int ew = pw + d.pad - q;
                     if (((ew % d.stride) + d.stride) % d.stride != 0) continue;
-                    a.dh[c][nt] = (signed char)floordiv(eh, d.stride);
-                    a.dw[c][nt] = (signed char)floordiv(ew, d.stride);
-                    a.bt[c][nt] = (signed char)(r * d.s + q);
+                    a.tap[c][nt] = pack_tap(floordiv(eh, d.stride), floordiv(ew, d.stride), r * d.s + q);
                     ++nt;
                 }
             }

@@ -21,7 +21,9 @@ struct GatherArgs {
     int oph[4], opw[4];
     int mt_end[4];       // running end of each class's row tiles (filled by the launcher)
     int ntaps[4];
-    signed char dh[4][9], dw[4][9], bt[4][9];
+    float inv_oh[4], inv_ow[4];   // reciprocals of cOHs / cOWs (filled by the launcher)
+    unsigned a_bytes, b_bytes;    // sizes of A and B in bytes (buffer range checks)
+    int tap[4][9];       // per class and live tap: dh | dw << 8 (signed bytes, A-pixel offset) | filter tap << 16
 };
 
 struct WgradArgs {
