@@ -49,6 +49,9 @@ __device__ __forceinline__ void reduce_row_lanes(float (&vals)[NV], float* smem,
     }
 }
 
+// Row loops are unrolled by kUnroll so that several 16-byte loads per tensor are in flight per thread.
+constexpr int kUnroll = 4;
+
 // ------------------------------------------------------------------ forward statistics
 // part[(blk*2+0)*c + ch] = sum (x - pivot), part[(blk*2+1)*c + ch] = sum (x - pivot)^2
 __global__ __launch_bounds__(kThreads) void bn_stats_kernel(long long m, int c, const h16* __restrict__ x,
@@ -61,13 +64,29 @@ __global__ __launch_bounds__(kThreads) void bn_stats_kernel(long long m, int c, 
     const long long row0 = (long long)blockIdx.x * rows_per_block;
     long long row1 = row0 + rows_per_block;
     if (row1 > m) row1 = m;
+    const int rp = rm.rows_par;
     for (int cg = cgl; cg < rm.gp; cg += rm.gpb) {
         const h16x8 pv = *reinterpret_cast<const h16x8*>(x + (size_t)cg * 8);
+        const h16* xc = x + (size_t)cg * 8;
         float acc[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = 0.f;
-        for (long long r = row0 + rl; r < row1; r += rm.rows_par) {
-            const h16x8 v = *reinterpret_cast<const h16x8*>(x + (size_t)r * c + (size_t)cg * 8);
+        long long r = row0 + rl;
+        for (; r + (kUnroll - 1) * rp < row1; r += kUnroll * rp) {
+            h16x8 v[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) v[u] = *reinterpret_cast<const h16x8*>(xc + (size_t)(r + u * rp) * c);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float d = (float)v[u][j] - (float)pv[j];
+                    acc[j] += d;
+                    acc[8 + j] += d * d;
+                }
+        }
+        for (; r < row1; r += rp) {
+            const h16x8 v = *reinterpret_cast<const h16x8*>(xc + (size_t)r * c);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float d = (float)v[j] - (float)pv[j];
@@ -85,30 +104,33 @@ __global__ __launch_bounds__(kThreads) void bn_stats_kernel(long long m, int c, 
     }
 }
 
-// One workgroup per 16 channels; 16 lanes per channel walk the partials, then combine in double.
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// One wavefront per channel: lanes stride over the partials, the 64 lane sums are combined in double.
+// pivot_row: first row of x (the pivot the partials were accumulated around) or nullptr for pivot 0.
 __global__ __launch_bounds__(kThreads) void bn_stats_finalize_kernel(long long m, int c, float eps, int nblk,
-                                                                     const h16* __restrict__ x,
+                                                                     const h16* __restrict__ pivot_row,
                                                                      const float* __restrict__ part,
                                                                      float* __restrict__ save_mean,
                                                                      float* __restrict__ save_invstd)
 {
-    __shared__ double s1[kThreads], s2[kThreads];
-    const int tid = threadIdx.x;
-    const int cl = tid & 15, bl = tid >> 4;
-    const int ch = blockIdx.x * 16 + cl;
-    double a = 0.0, b = 0.0;
-    if (ch < c)
-        for (int k = bl; k < nblk; k += 16) {
-            a += (double)part[((size_t)k * 2) * c + ch];
-            b += (double)part[((size_t)k * 2 + 1) * c + ch];
-        }
-    s1[tid] = a; s2[tid] = b;
-    __syncthreads();
-    if (bl == 0 && ch < c) {
-        for (int k = 1; k < 16; ++k) { a += s1[k * 16 + cl]; b += s2[k * 16 + cl]; }
-        const double pivot = (double)(float)x[ch];
-        const double md = a / (double)m;
-        double var = b / (double)m - md * md;
+    const int lane = threadIdx.x & 63;
+    const int ch = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (ch >= c) return;
+    float a = 0.f, b = 0.f;
+    for (int k = lane; k < nblk; k += 64) {
+        a += part[((size_t)k * 2) * c + ch];
+        b += part[((size_t)k * 2 + 1) * c + ch];
+    }
+    const double sa = wave_sum_f64((double)a), sb = wave_sum_f64((double)b);
+    if (lane == 0) {
+        const double pivot = pivot_row ? (double)(float)pivot_row[ch] : 0.0;
+        const double md = sa / (double)m;
+        double var = sb / (double)m - md * md;
         if (var < 0.0) var = 0.0;
         save_mean[ch] = (float)(pivot + md);
         save_invstd[ch] = (float)(1.0 / sqrt(var + (double)eps));
@@ -131,6 +153,7 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(long long m, int c, 
     const long long row0 = (long long)blockIdx.x * rows_per_block;
     long long row1 = row0 + rows_per_block;
     if (row1 > m) row1 = m;
+    const int rp = rm.rows_par;
     for (int cg = cgl; cg < rm.gp; cg += rm.gpb) {
         float g[8], b[8], mu[8], is[8];
 #pragma unroll
@@ -138,11 +161,7 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(long long m, int c, 
             g[j] = gamma[cg * 8 + j]; b[j] = beta[cg * 8 + j];
             mu[j] = mean[cg * 8 + j]; is[j] = invstd[cg * 8 + j];
         }
-        for (long long r = row0 + rl; r < row1; r += rm.rows_par) {
-            const size_t off = (size_t)r * c + (size_t)cg * 8;
-            const h16x8 v = *reinterpret_cast<const h16x8*>(x + off);
-            h16x8 rv;
-            if (kRes) rv = *reinterpret_cast<const h16x8*>(res + off);
+        auto one = [&](const h16x8& v, const h16x8& rv) {
             h16x8 o;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -151,7 +170,27 @@ __global__ __launch_bounds__(kThreads) void bn_apply_kernel(long long m, int c, 
                 if (kRelu) t = t > 0.f ? t : 0.f;
                 o[j] = (h16)t;
             }
-            *reinterpret_cast<h16x8*>(y + off) = o;
+            return o;
+        };
+        long long r = row0 + rl;
+        for (; r + (kUnroll - 1) * rp < row1; r += kUnroll * rp) {
+            h16x8 v[kUnroll], rv[kUnroll] = {};
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const size_t off = (size_t)(r + u * rp) * c + (size_t)cg * 8;
+                v[u] = *reinterpret_cast<const h16x8*>(x + off);
+                if (kRes) rv[u] = *reinterpret_cast<const h16x8*>(res + off);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                *reinterpret_cast<h16x8*>(y + (size_t)(r + u * rp) * c + (size_t)cg * 8) = one(v[u], rv[u]);
+        }
+        for (; r < row1; r += rp) {
+            const size_t off = (size_t)r * c + (size_t)cg * 8;
+            const h16x8 v = *reinterpret_cast<const h16x8*>(x + off);
+            h16x8 rv = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (kRes) rv = *reinterpret_cast<const h16x8*>(res + off);
+            *reinterpret_cast<h16x8*>(y + off) = one(v, rv);
         }
     }
 }
@@ -173,18 +212,14 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(long long m, in
     const long long row0 = (long long)blockIdx.x * rows_per_block;
     long long row1 = row0 + rows_per_block;
     if (row1 > m) row1 = m;
+    const int rp = rm.rows_par;
     for (int cg = cgl; cg < rm.gp; cg += rm.gpb) {
         float mu[8], is[8], acc[16];
 #pragma unroll
         for (int j = 0; j < 8; ++j) { mu[j] = mean[cg * 8 + j]; is[j] = invstd[cg * 8 + j]; }
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = 0.f;
-        for (long long r = row0 + rl; r < row1; r += rm.rows_par) {
-            const size_t off = (size_t)r * c + (size_t)cg * 8;
-            const h16x8 d = *reinterpret_cast<const h16x8*>(dy + off);
-            const h16x8 xv = *reinterpret_cast<const h16x8*>(x + off);
-            h16x8 yv;
-            if (kRelu) yv = *reinterpret_cast<const h16x8*>(y + off);
+        auto one = [&](const h16x8& d, const h16x8& xv, const h16x8& yv) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 float g = (float)d[j];
@@ -192,6 +227,27 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(long long m, in
                 acc[j] += g;
                 acc[8 + j] += g * (((float)xv[j] - mu[j]) * is[j]);
             }
+        };
+        long long r = row0 + rl;
+        for (; r + (kUnroll - 1) * rp < row1; r += kUnroll * rp) {
+            h16x8 d[kUnroll], xv[kUnroll], yv[kUnroll] = {};
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const size_t off = (size_t)(r + u * rp) * c + (size_t)cg * 8;
+                d[u] = *reinterpret_cast<const h16x8*>(dy + off);
+                xv[u] = *reinterpret_cast<const h16x8*>(x + off);
+                if (kRelu) yv[u] = *reinterpret_cast<const h16x8*>(y + off);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) one(d[u], xv[u], yv[u]);
+        }
+        for (; r < row1; r += rp) {
+            const size_t off = (size_t)r * c + (size_t)cg * 8;
+            const h16x8 d = *reinterpret_cast<const h16x8*>(dy + off);
+            const h16x8 xv = *reinterpret_cast<const h16x8*>(x + off);
+            h16x8 yv = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (kRelu) yv = *reinterpret_cast<const h16x8*>(y + off);
+            one(d, xv, yv);
         }
         reduce_row_lanes<16>(acc, smem, rm);
         if (rl == 0) {
@@ -203,33 +259,29 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(long long m, in
     }
 }
 
-// sums[0..c) = dbeta, sums[c..2c) = dgamma (float, kept for the apply pass); also the half copies.
+// sums[0..c) = dbeta, sums[c..2c) = dgamma (float, kept for the apply pass); also the half / float copies.
 __global__ __launch_bounds__(kThreads) void bn_bwd_finalize_kernel(int c, int nblk, const float* __restrict__ part,
                                                                    float* __restrict__ sums,
                                                                    h16* __restrict__ dgamma, h16* __restrict__ dbeta,
                                                                    float* __restrict__ dgamma32,
                                                                    float* __restrict__ dbeta32)
 {
-    __shared__ double s1[kThreads], s2[kThreads];
-    const int tid = threadIdx.x;
-    const int cl = tid & 15, bl = tid >> 4;
-    const int ch = blockIdx.x * 16 + cl;
-    double a = 0.0, b = 0.0;
-    if (ch < c)
-        for (int k = bl; k < nblk; k += 16) {
-            a += (double)part[((size_t)k * 2) * c + ch];
-            b += (double)part[((size_t)k * 2 + 1) * c + ch];
-        }
-    s1[tid] = a; s2[tid] = b;
-    __syncthreads();
-    if (bl == 0 && ch < c) {
-        for (int k = 1; k < 16; ++k) { a += s1[k * 16 + cl]; b += s2[k * 16 + cl]; }
-        sums[ch] = (float)a;
-        sums[c + ch] = (float)b;
-        if (dbeta) dbeta[ch] = (h16)(float)a;
-        if (dgamma) dgamma[ch] = (h16)(float)b;
-        if (dbeta32) dbeta32[ch] = (float)a;
-        if (dgamma32) dgamma32[ch] = (float)b;
+    const int lane = threadIdx.x & 63;
+    const int ch = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (ch >= c) return;
+    float a = 0.f, b = 0.f;
+    for (int k = lane; k < nblk; k += 64) {
+        a += part[((size_t)k * 2) * c + ch];
+        b += part[((size_t)k * 2 + 1) * c + ch];
+    }
+    const double sa = wave_sum_f64((double)a), sb = wave_sum_f64((double)b);
+    if (lane == 0) {
+        sums[ch] = (float)sa;
+        sums[c + ch] = (float)sb;
+        if (dbeta) dbeta[ch] = (h16)(float)sa;
+        if (dgamma) dgamma[ch] = (h16)(float)sb;
+        if (dbeta32) dbeta32[ch] = (float)sa;
+        if (dgamma32) dgamma32[ch] = (float)sb;
     }
 }
 
@@ -251,6 +303,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(long long m, int
     long long row1 = row0 + rows_per_block;
     if (row1 > m) row1 = m;
     const float inv_m = 1.f / (float)m;
+    const int rp = rm.rows_par;
     for (int cg = cgl; cg < rm.gp; cg += rm.gpb) {
         float mu[8], is[8], sc[8], mb[8], mg[8];
 #pragma unroll
@@ -260,12 +313,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(long long m, int
             mb[j] = sums[cg * 8 + j] * inv_m;
             mg[j] = sums[c + cg * 8 + j] * inv_m;
         }
-        for (long long r = row0 + rl; r < row1; r += rm.rows_par) {
-            const size_t off = (size_t)r * c + (size_t)cg * 8;
-            const h16x8 d = *reinterpret_cast<const h16x8*>(dy + off);
-            const h16x8 xv = *reinterpret_cast<const h16x8*>(x + off);
-            h16x8 yv;
-            if (kRelu) yv = *reinterpret_cast<const h16x8*>(y + off);
+        auto one = [&](const h16x8& d, const h16x8& xv, const h16x8& yv, size_t off) {
             h16x8 o, go;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -277,6 +325,27 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(long long m, int
             }
             *reinterpret_cast<h16x8*>(dx + off) = o;
             if (kRes) *reinterpret_cast<h16x8*>(dres + off) = go;
+        };
+        long long r = row0 + rl;
+        for (; r + (kUnroll - 1) * rp < row1; r += kUnroll * rp) {
+            h16x8 d[kUnroll], xv[kUnroll], yv[kUnroll] = {};
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const size_t off = (size_t)(r + u * rp) * c + (size_t)cg * 8;
+                d[u] = *reinterpret_cast<const h16x8*>(dy + off);
+                xv[u] = *reinterpret_cast<const h16x8*>(x + off);
+                if (kRelu) yv[u] = *reinterpret_cast<const h16x8*>(y + off);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) one(d[u], xv[u], yv[u], (size_t)(r + u * rp) * c + (size_t)cg * 8);
+        }
+        for (; r < row1; r += rp) {
+            const size_t off = (size_t)r * c + (size_t)cg * 8;
+            const h16x8 d = *reinterpret_cast<const h16x8*>(dy + off);
+            const h16x8 xv = *reinterpret_cast<const h16x8*>(x + off);
+            h16x8 yv = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (kRelu) yv = *reinterpret_cast<const h16x8*>(y + off);
+            one(d, xv, yv, off);
         }
     }
 }
@@ -286,8 +355,8 @@ struct BnPlan { int nblk; int rows_per_block; };
 BnPlan plan_rows(long long m, int c)
 {
     const RowMap rm = make_rowmap(c);
-    // at least 8 row iterations per thread, at most kMaxBlocks workgroups
-    long long rows = (long long)rm.rows_par * 8;
+    // about 16 row iterations per thread, at most kMaxBlocks workgroups
+    long long rows = (long long)rm.rows_par * 16;
     long long nblk = (m + rows - 1) / rows;
     if (nblk > kMaxBlocks) {
         rows = (m + kMaxBlocks - 1) / kMaxBlocks;
@@ -333,7 +402,29 @@ int rn50_bn_fwd_launch(long long m, int c, float eps, bool relu, const h16* x, c
     }
     {
         ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * p.nblk * c, s);
-        bn_stats_finalize_kernel<<<rn50_cdiv(c, 16), kThreads, 0, s>>>(m, c, eps, p.nblk, x, ws, save_mean, save_invstd);
+        bn_stats_finalize_kernel<<<rn50_cdiv(c, kThreads / 64), kThreads, 0, s>>>(m, c, eps, p.nblk, x, ws, save_mean, save_invstd);
+    }
+    ProfScope ps(RN50_K_BN_APPLY, 0.0, (res ? 6.0 : 4.0) * elems, s);
+#define RN50_BN_APPLY(R, Z) bn_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, x, gamma, beta, save_mean, \
+                                                                              save_invstd, res, y, p.rows_per_block)
+    if (relu) { if (res) RN50_BN_APPLY(true, true); else RN50_BN_APPLY(true, false); }
+    else      { if (res) RN50_BN_APPLY(false, true); else RN50_BN_APPLY(false, false); }
+#undef RN50_BN_APPLY
+    return rn50_check_launch();
+}
+
+// Forward for a tensor whose per-row-tile partial sums (pivot 0) were already written by the producing
+// convolution: part[(tile*2+0)*c + ch] = sum x, part[(tile*2+1)*c + ch] = sum x^2 over the tile's rows.
+int rn50_bn_fwd_from_partials_launch(long long m, int c, float eps, bool relu, const h16* x, const float* gamma,
+                                     const float* beta, const h16* res, h16* y, float* save_mean, float* save_invstd,
+                                     const float* part, int ntiles, hipStream_t s)
+{
+    const BnPlan p = plan_rows(m, c);
+    const double elems = (double)m * c;
+    {
+        ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * ntiles * c, s);
+        bn_stats_finalize_kernel<<<rn50_cdiv(c, kThreads / 64), kThreads, 0, s>>>(m, c, eps, ntiles, nullptr, part,
+                                                                                 save_mean, save_invstd);
     }
     ProfScope ps(RN50_K_BN_APPLY, 0.0, (res ? 6.0 : 4.0) * elems, s);
 #define RN50_BN_APPLY(R, Z) bn_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, x, gamma, beta, save_mean, \
@@ -358,7 +449,7 @@ int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* 
     }
     {
         ProfScope ps(RN50_K_BN_BWD_FINALIZE, 0.0, 8.0 * p.nblk * c, s);
-        bn_bwd_finalize_kernel<<<rn50_cdiv(c, 16), kThreads, 0, s>>>(c, p.nblk, ws, sums, dgamma, dbeta, dgamma32, dbeta32);
+        bn_bwd_finalize_kernel<<<rn50_cdiv(c, kThreads / 64), kThreads, 0, s>>>(c, p.nblk, ws, sums, dgamma, dbeta, dgamma32, dbeta32);
     }
     ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, ((relu ? 6.0 : 4.0) + 2.0 + (dres ? 2.0 : 0.0)) * elems, s);
 #define RN50_BN_BWD(R, Z) bn_bwd_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, gamma, save_mean, \

@@ -247,6 +247,9 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     constexpr int OCPR = BN / 8;                 // output chunks per row
     constexpr int ORPP = kThreads / OCPR;
     const int oc = tid % OCPR, orl = tid / OCPR;
+    float st[16];                                // per-channel sum and sum of squares of the stored halves
+#pragma unroll
+    for (int j = 0; j < 16; ++j) st[j] = 0.f;
 #pragma unroll
     for (int i = 0; i < BM / ORPP; ++i) {
         const int row = orl + i * ORPP;
@@ -256,8 +259,27 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
             fast_divmod(m, OWs, inv_ow, t, wq);
             fast_divmod(t, OHs, inv_oh, n, hq);
             const size_t opix = ((size_t)n * a.OH + hq * a.o_mul + a.oph[cls]) * a.OW + wq * a.o_mul + a.opw[cls];
-            *reinterpret_cast<h16x8*>(a.out + opix * a.NO + nt * BN + oc * 8) =
-                *reinterpret_cast<const h16x8*>(lds + row * EP + oc * 8);
+            const h16x8 v = *reinterpret_cast<const h16x8*>(lds + row * EP + oc * 8);
+            *reinterpret_cast<h16x8*>(a.out + opix * a.NO + nt * BN + oc * 8) = v;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { const float f = (float)v[j]; st[j] += f; st[8 + j] += f * f; }
+        }
+    }
+    if (a.stats_part) {
+        // BatchNorm statistics of this row tile, summed in a fixed order: [tile][sum | sumsq][channel]
+        float* red = reinterpret_cast<float*>(lds + BM * EP);          // ORPP x 2 x BN floats behind the staged tile
+        static_assert(BM * EP * 2 + ORPP * 2 * BN * 4 <= LDS_HALFS * 2, "statistics scratch must fit in LDS");
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            red[(orl * 2 + 0) * BN + oc * 8 + j] = st[j];
+            red[(orl * 2 + 1) * BN + oc * 8 + j] = st[8 + j];
+        }
+        __syncthreads();
+        if (tid < 2 * BN) {
+            const int which = tid / BN, col = tid % BN;
+            float sum = 0.f;
+            for (int r = 0; r < ORPP; ++r) sum += red[(r * 2 + which) * BN + col];
+            a.stats_part[((size_t)(bid / n_tiles) * 2 + which) * a.NO + nt * BN + col] = sum;
         }
     }
 }
@@ -633,9 +655,11 @@ int rn50_cast_f32_to_h16(const float* src, h16* dst, size_t n, hipStream_t s)
 }
 
 // Forward.  For the stem, x is the padded 4-channel image and w the packed filter.
-int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y, hipStream_t s)
+int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y, hipStream_t s, float* stats_part,
+                         int* stats_tiles)
 {
     GatherArgs a = {};
+    a.stats_part = stats_part;
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     a.A = x; a.B = w; a.out = y; a.addend = nullptr;
     a.NB = d.n; a.NO = d.k; a.OH = P; a.OW = Q; a.o_mul = 1;
@@ -658,7 +682,9 @@ int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y,
                 a.tap[0][t] = pack_tap(r - d.pad, q - d.pad, t);
             }
     }
-    return dispatch_gather(a, s, conv_flops(d, P, Q), conv_bytes(d, P, Q, false));
+    const int rc = dispatch_gather(a, s, conv_flops(d, P, Q), conv_bytes(d, P, Q, false));
+    if (stats_tiles) *stats_tiles = a.mt_end[0];
+    return rc;
 }
 
 // Data gradient.  wt is the filter transposed to [C][R][S][K].  addend (nullable) has dx's layout.
@@ -695,6 +721,13 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
     const double bytes = conv_bytes(d, P, Q, addend != nullptr) +
                          ((d.r == 1 && d.stride > 1) ? 2.0 * d.n * ((double)d.h * d.w - (double)P * Q) * d.c : 0.0);
     return dispatch_gather(a, s, conv_flops(d, P, Q), bytes);
+}
+
+// upper bound of the floats conv_fwd writes to stats_part: (smallest tile = 64 rows) x 2 x k
+size_t rn50_conv_stats_floats(const conv_desc& d)
+{
+    const long long M = (long long)d.n * out_dim(d.h, d.pad, d.r, d.stride) * out_dim(d.w, d.pad, d.s, d.stride);
+    return (size_t)((M + 63) / 64) * 2 * d.k;
 }
 
 size_t rn50_wgrad_acc_floats(const conv_desc& d)
@@ -787,9 +820,10 @@ extern "C" int conv_fwd(const conv_desc* d, const void* x, const void* w, void* 
         h16* packed = reinterpret_cast<h16*>(static_cast<char*>(ws) + rn50_stem_padded_bytes(*d));
         RN50_TRY(rn50_stem_pad_image(*d, static_cast<const h16*>(x), padded, s));
         RN50_TRY(rn50_stem_pack_filter(*d, static_cast<const h16*>(w), packed, s));
-        return rn50_conv_fwd_launch(*d, padded, packed, static_cast<h16*>(y), s);
+        return rn50_conv_fwd_launch(*d, padded, packed, static_cast<h16*>(y), s, nullptr, nullptr);
     }
-    return rn50_conv_fwd_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(w), static_cast<h16*>(y), s);
+    return rn50_conv_fwd_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(w), static_cast<h16*>(y), s, nullptr,
+                                nullptr);
 }
 
 extern "C" int conv_dgrad(const conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, void* stream)

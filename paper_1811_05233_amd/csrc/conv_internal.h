@@ -7,6 +7,7 @@ struct GatherArgs {
     const h16* B;        // [NO][T][CR]
     h16* out;            // NHWC output, NO channels
     const h16* addend;   // nullable, same layout as out
+    float* stats_part;   // nullable: per row tile, [sum | sum of squares][NO] of the stored output (forward only)
     int NB;              // images
     int IH, IW;          // spatial size of A
     int lda;             // halfs between adjacent pixels of A
@@ -50,7 +51,10 @@ int rn50_stem_pack_filter(const conv_desc& d, const h16* w, h16* packed, hipStre
 int rn50_transpose_filter(const conv_desc& d, const h16* w, h16* wt, hipStream_t s);
 int rn50_fill_zero(float* p, size_t n, hipStream_t s);
 int rn50_cast_f32_to_h16(const float* src, h16* dst, size_t n, hipStream_t s);
-int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y, hipStream_t s);
+// stats_part (nullable): receives per-row-tile BatchNorm partial sums; *stats_tiles = number of row tiles
+int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y, hipStream_t s, float* stats_part,
+                         int* stats_tiles);
+size_t rn50_conv_stats_floats(const conv_desc& d);
 int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s);
 size_t rn50_wgrad_acc_floats(const conv_desc& d);
 int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* acc, hipStream_t s);

@@ -215,7 +215,10 @@ size_t carve(rn50_ctx& c, char* base)
     c.dlogits = reinterpret_cast<h16*>(take((size_t)cfg.batch * cfg.classes * sizeof(h16)));
     c.wt_all = reinterpret_cast<h16*>(take(wt_elems * sizeof(h16)));
     c.grad32 = reinterpret_cast<float*>(take(rn50_round_up(L.param_count, 8) * sizeof(float)));
-    c.bn_ws = reinterpret_cast<float*>(take(rn50_bn_ws_floats(max_c) * sizeof(float)));
+    size_t bn_ws_floats = rn50_bn_ws_floats(max_c);
+    for (const ConvLayer& l : L.layers)
+        if (rn50_conv_stats_floats(l.d) > bn_ws_floats) bn_ws_floats = rn50_conv_stats_floats(l.d);
+    c.bn_ws = reinterpret_cast<float*>(take(bn_ws_floats * sizeof(float)));
     // Activation gradients.  Normally six rotating buffers (two alternate as block-input gradients,
     // one holds the shortcut gradient, three are scratch inside a block); with keep_grads every
     // gradient tensor gets its own buffer so that it can be inspected after the step.
@@ -378,11 +381,13 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         RN50_TRY(rn50_check_launch());
     }
 
-    auto conv_bn_fwd = [&](ConvLayer& l, const h16* x, bool relu, const h16* residual) -> int {
-        RN50_TRY(rn50_conv_fwd_launch(l.d, x, w16 + l.w_off, l.conv_out, s));
-        return rn50_bn_fwd_launch((long long)l.d.n * l.P * l.Q, l.d.k, cfg.bn_eps, relu, l.conv_out,
-                                  master_w + l.gamma_off, master_w + l.beta_off, residual, l.bn_out, l.mean, l.invstd,
-                                  c.bn_ws, s);
+    // convolution (its epilogue also leaves the BatchNorm partial sums of every row tile), then BN
+    auto conv_bn_fwd = [&](ConvLayer& l, const h16* x, const h16* wts, bool relu, const h16* residual) -> int {
+        int tiles = 0;
+        RN50_TRY(rn50_conv_fwd_launch(l.d, x, wts, l.conv_out, s, c.bn_ws, &tiles));
+        return rn50_bn_fwd_from_partials_launch((long long)l.d.n * l.P * l.Q, l.d.k, cfg.bn_eps, relu, l.conv_out,
+                                                master_w + l.gamma_off, master_w + l.beta_off, residual, l.bn_out,
+                                                l.mean, l.invstd, c.bn_ws, tiles, s);
     };
 
     // ================= forward =================
@@ -391,10 +396,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         ConvLayer& st = L.layers[0];
         RN50_TRY(rn50_stem_pad_image(st.d, x, c.stem_padded, s));
         RN50_TRY(rn50_stem_pack_filter(st.d, w16 + st.w_off, c.stem_packed, s));
-        RN50_TRY(rn50_conv_fwd_launch(st.d, c.stem_padded, c.stem_packed, st.conv_out, s));
-        RN50_TRY(rn50_bn_fwd_launch((long long)B * st.P * st.Q, st.d.k, cfg.bn_eps, true, st.conv_out,
-                                    master_w + st.gamma_off, master_w + st.beta_off, nullptr, st.bn_out, st.mean,
-                                    st.invstd, c.bn_ws, s));
+        RN50_TRY(conv_bn_fwd(st, c.stem_padded, c.stem_packed, true, nullptr));
         RN50_TRY(rn50_maxpool_fwd(B, st.P, st.Q, st.d.k, st.bn_out, c.pool_out, c.pool_arg, s));
         x = c.pool_out;
     }
@@ -402,14 +404,14 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     for (size_t bi = 0; bi < L.blocks.size(); ++bi) {
         const Block& b = L.blocks[bi];
         block_in[bi] = x;
-        RN50_TRY(conv_bn_fwd(L.layers[b.c1], x, true, nullptr));
-        RN50_TRY(conv_bn_fwd(L.layers[b.c2], L.layers[b.c1].bn_out, true, nullptr));
+        RN50_TRY(conv_bn_fwd(L.layers[b.c1], x, w16 + L.layers[b.c1].w_off, true, nullptr));
+        RN50_TRY(conv_bn_fwd(L.layers[b.c2], L.layers[b.c1].bn_out, w16 + L.layers[b.c2].w_off, true, nullptr));
         const h16* shortcut = x;
         if (b.proj >= 0) {
-            RN50_TRY(conv_bn_fwd(L.layers[b.proj], x, false, nullptr));
+            RN50_TRY(conv_bn_fwd(L.layers[b.proj], x, w16 + L.layers[b.proj].w_off, false, nullptr));
             shortcut = L.layers[b.proj].bn_out;
         }
-        RN50_TRY(conv_bn_fwd(L.layers[b.c3], L.layers[b.c2].bn_out, true, shortcut));
+        RN50_TRY(conv_bn_fwd(L.layers[b.c3], L.layers[b.c2].bn_out, w16 + L.layers[b.c3].w_off, true, shortcut));
         x = L.layers[b.c3].bn_out;
     }
     const int HW = L.final_h * L.final_w;
