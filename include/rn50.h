@@ -75,8 +75,8 @@ int conv_fwd(const conv_desc* d, const void* x, const void* w, void* y,
 int conv_dgrad(const conv_desc* d, const void* dy, const void* w, void* dx,
                void* ws, size_t ws_bytes, void* stream);
 /* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n,p*stride+r-pad,q*stride+s-pad,c], stored as
- * half.  FP32 partial sums of different pixel ranges are combined with atomic adds, so
- * the last bits may differ from run to run. */
+ * half.  FP32 partial sums of different pixel ranges are added in a fixed order, so the
+ * result is deterministic. */
 int conv_wgrad(const conv_desc* d, const void* x, const void* dy, void* dw,
                void* ws, size_t ws_bytes, void* stream);
 

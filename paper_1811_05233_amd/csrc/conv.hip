@@ -287,19 +287,38 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
 // ------------------------------------------------------------------------------------------------
 // filter gradient
 // ------------------------------------------------------------------------------------------------
-// acc[k][g][c] += sum_{pix in this split} dy[pix][k] * X[pix, g][c], g = granule of G columns.
+// out[k][g][c] = sum_{pix in this split} dy[pix][k] * X[pix, g][c], g = granule of G columns.
 // Regular mode (G = 64): granule = (tap, 64-channel slab of x).  Stem mode (G = 32): granule = filter
 // row r; the 32 columns are the 8 consecutive padded-image pixels x 4 channels starting at column 2q.
-template <int BM, int BN, int BKP, int G, bool kStem>
-__global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a)
+//
+// Both operands are pixel-major in memory while the MFMA wants 8 consecutive pixels per lane.  The
+// tiles travel global -> LDS untouched ([pixel][channel], same ring as the gather GEMM) and the
+// operands are read with ds_read_b64_tr_b16, which transposes 4x4 blocks of halves across lanes:
+// within 16 lanes, lane 4*r+e receives element e of the 8-byte words read by lanes r, 4+r, 8+r, 12+r.
+// Lanes 4*j..4*j+3 therefore read 16 consecutive channels of pixel j, and lane L ends up with
+// channel L of pixels 0..3.  Each workgroup reduces its own pixel range and stores an FP32 partial
+// tile; a second kernel adds the partials in a fixed order (deterministic, no atomics).
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+
+// 8 bytes per lane through the transposing LDS read, as four halves
+__device__ __forceinline__ h16x4 lds_read_tr(const h16* p) {
+    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(const_cast<h16*>(p)));
+    return __builtin_bit_cast(h16x4, v);
+}
+
+template <int BM, int BN, int NST, int G, bool kStem>
+__global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradArgs a)
 {
-    constexpr int CPR = BKP / 8;
+    constexpr int BKP = 32;                                   // pixels per K-slab
+    constexpr int A_LPR = BM / 8, A_RPI = 64 / A_LPR, NA = BKP / A_RPI / 4;
+    constexpr int B_LPR = BN / 8, B_RPI = 64 / B_LPR, NB = BKP / B_RPI / 4;
+    constexpr int NL = NA + NB;
     constexpr int STAGE = (BM + BN) * BKP;
     constexpr int WR = 2, WC = 2;
     constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
-    constexpr int KS = BKP / 16;
-    static_assert((BM + BN) * (BKP / 8) / 8 == kThreads, "one 8x8 micro-block per thread");
-    __shared__ __attribute__((aligned(16))) h16 lds[2 * STAGE];
+    constexpr unsigned kOutOfRange = 0x80000000u;
+    __shared__ __attribute__((aligned(16))) h16 lds[NST * STAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -311,33 +330,71 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a)
     const int nt = bid % n_tiles; bid /= n_tiles;
     const int mt = bid % m_tiles;
     const int split = bid / m_tiles;
-    const long long pix_begin = (long long)split * a.pix_per_split;
-    long long pix_end = pix_begin + a.pix_per_split;
+    const int pix_begin = split * a.pix_per_split;
+    int pix_end = pix_begin + a.pix_per_split;
     if (pix_end > a.npix) pix_end = a.npix;
+    const int kiters = (pix_end - pix_begin + BKP - 1) / BKP;
 
-    // ---- loader role: micro-blocks [0, BM/8 * CPR) belong to dy, the rest to x ----
-    constexpr int DY_MB = (BM / 8) * CPR;
-    const bool is_dy = tid < DY_MB;
-    const int mb = is_dy ? tid : tid - DY_MB;
-    const int groups = is_dy ? BM / 8 : BN / 8;
-    const int cg = mb % groups;          // 8-column group inside the tile (fast index: coalesced)
-    const int pg = mb / groups;          // 8-pixel group inside the K-slab
-    // x side: granule and column offset
-    const int gran = nt * (BN / G) + (cg * 8) / G;
-    const int gcol = (cg * 8) % G;
+    // ---- this lane's part of the wave-wide loads ----
+    // dy tile: [pixel][BM channels]; chunk index XOR-ed with 2*(pixel & 3) (conflict-free transposing reads)
+    const int a_pl = lane / A_LPR, a_chunk = (lane % A_LPR) ^ ((a_pl & 3) << 1);
+    const unsigned a_col = (unsigned)(mt * BM + a_chunk * 8) * 2u;
+    const int b_pl = lane / B_LPR, b_chunk = (lane % B_LPR) ^ ((b_pl & 3) << 1);
+    const int gran = nt * (BN / G) + (b_chunk * 8) / G;
+    const int gcol = (b_chunk * 8) % G;
     int tap_r = 0, tap_s = 0, c0 = 0;
     bool gran_ok = true;
-    if (!is_dy) {
-        if (kStem) { tap_r = gran; gran_ok = gran < a.R; }
-        else {
-            const int gpt = a.C / G;     // granules per tap
-            const int tap = gran / gpt;
-            tap_r = tap / a.S; tap_s = tap % a.S;
-            c0 = (gran % gpt) * G + gcol;
-        }
+    if (kStem) { tap_r = gran; gran_ok = gran < a.R; }
+    else {
+        const int gpt = a.C / G;     // granules per tap
+        const int tap = gran / gpt;
+        tap_r = tap / a.S; tap_s = tap % a.S;
+        c0 = (gran % gpt) * G + gcol;
     }
-    const h16* dy_ptr = a.dy + (size_t)(mt * BM + cg * 8);
     const bool direct = a.direct != 0;   // 1x1 stride 1: x pixel index == dy pixel index
+    const int K = a.K, C = a.C, H = a.H, W = a.W, P = a.P, Q = a.Q;
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<h16*>(a.dy), 0, a.dy_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(const_cast<h16*>(a.x), 0, a.x_bytes, 0x00020000);
+
+    int ld_pix = pix_begin, ld_stage = 0;
+    auto issue_slab = [&]() {
+        h16* sa = lds + ld_stage * STAGE;
+        h16* sb = sa + BM * BKP;
+#pragma unroll
+        for (int j = 0; j < NA; ++j) {
+            const int pix = ld_pix + (wave + 4 * j) * A_RPI + a_pl;
+            const unsigned voff = pix < pix_end ? (unsigned)(pix * K) * 2u + a_col : kOutOfRange;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(sa + (wave + 4 * j) * 512), 16, (int)voff, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int pix = ld_pix + (wave + 4 * j) * B_RPI + b_pl;
+            bool ok = pix < pix_end && gran_ok;
+            unsigned voff;
+            if (direct) {
+                voff = (unsigned)(pix * C + c0) * 2u;
+            } else {
+                int t, q, n, p;
+                fast_divmod(pix, Q, a.inv_q, t, q);
+                fast_divmod(t, P, a.inv_p, n, p);
+                if (kStem) {
+                    voff = (unsigned)(((n * H + 2 * p + tap_r) * W + 2 * q) * 4 + gcol) * 2u;   // padded image: in bounds
+                } else {
+                    const int ih = p * a.stride - a.pad + tap_r, iw = q * a.stride - a.pad + tap_s;
+                    ok = ok && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W;
+                    voff = (unsigned)(((n * H + ih) * W + iw) * C + c0) * 2u;
+                }
+            }
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(sb + (wave + 4 * j) * 512), 16,
+                                                     (int)(ok ? voff : kOutOfRange), 0, 0, 0);
+        }
+        ld_pix += BKP;
+        if (++ld_stage == NST) ld_stage = 0;
+    };
+
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p)
+        if (p < kiters) issue_slab();
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -347,88 +404,57 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
 
-    h16x8 r[8];
-    const h16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    auto load_mb = [&](long long pix0) {
-        const long long p0 = pix0 + pg * 8;
-        if (is_dy) {
+    // transposing-read addresses: 16-lane group g4 serves channels 16*(g4&1).. and pixels 8*(g4>>1)..;
+    // inside the group lane 4*jj+r reads channels 4r..4r+3 of pixel jj
+    const int g4 = lane >> 4, jj = (lane >> 2) & 3, rr = lane & 3;
+    int fa_off[TM], fb_off[TN];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bool ok = p0 + j < pix_end;
-                const h16x8 v = *reinterpret_cast<const h16x8*>(dy_ptr + (ok ? (size_t)(p0 + j) * a.K : 0));
-                r[j] = ok ? v : zero8;
-            }
-        } else if (direct) {
+    for (int tm = 0; tm < TM; ++tm) {
+        const int ch = wm0 + tm * 32 + 16 * (g4 & 1) + 4 * rr;
+        fa_off[tm] = (8 * (g4 >> 1) + jj) * BM + ((((ch >> 3) ^ (jj << 1)) << 3) | (ch & 7));
+    }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bool ok = p0 + j < pix_end;
-                const h16x8 v = *reinterpret_cast<const h16x8*>(a.x + c0 + (ok ? (size_t)(p0 + j) * a.C : 0));
-                r[j] = ok ? v : zero8;
-            }
-        } else {
-            int q = (int)(p0 % a.Q);
-            long long t = p0 / a.Q;
-            int p = (int)(t % a.P);
-            int n = (int)(t / a.P);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                bool ok = p0 + j < pix_end && gran_ok;
-                size_t off;
-                if (kStem) {
-                    // padded image: always in bounds
-                    off = (((size_t)n * a.H + 2 * p + tap_r) * a.W + 2 * q) * 4 + gcol;
-                } else {
-                    const int ih = p * a.stride - a.pad + tap_r, iw = q * a.stride - a.pad + tap_s;
-                    ok = ok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-                    off = (((size_t)n * a.H + ih) * a.W + iw) * a.C + c0;
-                }
-                const h16x8 v = *reinterpret_cast<const h16x8*>(a.x + (ok ? off : 0));
-                r[j] = ok ? v : zero8;
-                if (++q == a.Q) { q = 0; if (++p == a.P) { p = 0; ++n; } }
-            }
-        }
-    };
-    auto store_mb = [&](int stage) {
-        h16* base = lds + stage * STAGE + (is_dy ? 0 : BM * BKP);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            h16x8 o;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) o[j] = r[j][e];     // 8x8 transpose in registers
-            *reinterpret_cast<h16x8*>(base + lds_off<BKP>(cg * 8 + e, pg)) = o;
-        }
-    };
+    for (int tn = 0; tn < TN; ++tn) {
+        const int ch = wn0 + tn * 32 + 16 * (g4 & 1) + 4 * rr;
+        fb_off[tn] = (8 * (g4 >> 1) + jj) * BN + ((((ch >> 3) ^ (jj << 1)) << 3) | (ch & 7));
+    }
 
-    const int kiters = (int)((pix_end - pix_begin + BKP - 1) / BKP);
-    if (kiters > 0) { load_mb(pix_begin); store_mb(0); }
-    __syncthreads();
+    int cur = 0;
     for (int kit = 0; kit < kiters; ++kit) {
-        const int cur = kit & 1;
-        if (kit + 1 < kiters) load_mb(pix_begin + (long long)(kit + 1) * BKP);
-        const h16* sa = lds + cur * STAGE;
-        const h16* sb = sa + BM * BKP;
+        if (kit + NST - 2 < kiters) RN50_WAIT_VMCNT(NL * (NST - 2));
+        else RN50_WAIT_VMCNT(0);
+        RN50_WAIT_LGKMCNT0();
+        __builtin_amdgcn_s_barrier();
+        if (kit + NST - 1 < kiters) issue_slab();
+        h16* sa = lds + cur * STAGE;
+        h16* sb = sa + BM * BKP;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+        for (int ks = 0; ks < BKP / 16; ++ks) {
             h16x8 fa[TM], fb[TN];
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                fa[tm] = *reinterpret_cast<const h16x8*>(sa + lds_off<BKP>(wm0 + tm * 32 + li, ks * 2 + lg));
+            for (int tm = 0; tm < TM; ++tm) {
+                const h16x4 lo = lds_read_tr(sa + fa_off[tm] + (ks * 16) * BM);
+                const h16x4 hi = lds_read_tr(sa + fa_off[tm] + (ks * 16 + 4) * BM);
+                fa[tm] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                fb[tn] = *reinterpret_cast<const h16x8*>(sb + lds_off<BKP>(wn0 + tn * 32 + li, ks * 2 + lg));
+            for (int tn = 0; tn < TN; ++tn) {
+                const h16x4 lo = lds_read_tr(sb + fb_off[tn] + (ks * 16) * BN);
+                const h16x4 hi = lds_read_tr(sb + fb_off[tn] + (ks * 16 + 4) * BN);
+                fb[tn] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
                     acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[tm], fb[tn], acc[tm][tn], 0, 0, 0);
         }
-        if (kit + 1 < kiters) store_mb(cur ^ 1);
-        __syncthreads();
+        if (++cur == NST) cur = 0;
     }
-    if (kiters == 0) return;
 
-    // ---- accumulate into the FP32 buffer: lane owns column li, rows 8*(v/4) + 4*lg + v%4 ----
+    // ---- FP32 partial tile: lane owns column li, rows 8*(v/4) + 4*lg + v%4 ----
     const int row_len = a.NG * G;      // columns per output row
+    float* out = a.out + (size_t)split * a.split_stride;
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -437,9 +463,28 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = mt * BM + wm0 + tm * 32 + (v / 4) * 8 + lg * 4 + (v % 4);
-                atomicAdd(a.acc + (size_t)row * row_len + col, acc[tm][tn][v]);
+                out[(size_t)row * row_len + col] = acc[tm][tn][v];
             }
         }
+}
+
+// out[i] = sum over splits of part[s][i].  A workgroup owns 16 consecutive float4 elements; 16 split
+// lanes each add every 16th split in order, and their sums are combined in a fixed order through LDS.
+__global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const f32x4* __restrict__ part, f32x4* __restrict__ out,
+                                                                size_t n4, int nsplit, size_t stride4)
+{
+    __shared__ f32x4 red[16][16];
+    const int il = threadIdx.x & 15, sl = threadIdx.x >> 4;
+    const size_t i = (size_t)blockIdx.x * 16 + il;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (i < n4)
+        for (int k = sl; k < nsplit; k += 16) s += part[(size_t)k * stride4 + i];
+    red[sl][il] = s;
+    __syncthreads();
+    if (sl == 0 && i < n4) {
+        for (int k = 1; k < 16; ++k) s += red[k][il];
+        out[i] = s;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -736,41 +781,80 @@ size_t rn50_wgrad_acc_floats(const conv_desc& d)
     return (size_t)d.k * d.r * d.s * d.c;
 }
 
-// Filter gradient into a zero-initialised FP32 accumulator (layout [K][R][S][C]; stem: [K][8][32]).
-// For the stem, x is the padded 4-channel image.
-int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* acc, hipStream_t s)
+namespace {
+struct WgradPlan { int BM, BN, G, NG, tiles, nsplit, pix_per_split; bool stem; };
+
+WgradPlan wgrad_plan(const conv_desc& d)
+{
+    WgradPlan p;
+    const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
+    const long long npix = (long long)d.n * P * Q;
+    p.stem = rn50_conv_is_stem(d);
+    if (p.stem) { p.BM = 64; p.BN = 64; p.G = 32; p.NG = 8; }
+    else {
+        p.G = 64; p.NG = d.r * d.s * d.c / 64;
+        if (d.k % 128 == 0 && p.NG % 2 == 0) { p.BM = 128; p.BN = 128; }
+        else { p.BM = 64; p.BN = 64; }
+    }
+    p.tiles = (d.k / p.BM) * (p.NG * p.G / p.BN);
+    // pixel splits: about two workgroups per compute unit, but at least 8 K-slabs of 32 pixels each
+    const long long slabs = (npix + 31) / 32;
+    long long want = (512 + p.tiles - 1) / p.tiles;
+    long long slabs_per = (slabs + want - 1) / want;
+    if (slabs_per < 8) slabs_per = slabs < 8 ? slabs : 8;
+    p.pix_per_split = (int)(slabs_per * 32);
+    p.nsplit = (int)((slabs + slabs_per - 1) / slabs_per);
+    return p;
+}
+}  // namespace
+
+// floats of scratch rn50_conv_wgrad_launch needs for its per-split partial tiles (0 if it does not split)
+size_t rn50_wgrad_partial_floats(const conv_desc& d)
+{
+    const WgradPlan p = wgrad_plan(d);
+    return p.nsplit > 1 ? (size_t)p.nsplit * rn50_wgrad_acc_floats(d) : 0;
+}
+
+// Filter gradient in FP32 into out (layout [K][R][S][C]; stem: [K][8][32]); every element is written.
+// partials: scratch of rn50_wgrad_partial_floats(d) floats.  For the stem, x is the padded 4-channel image.
+int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* out, float* partials, hipStream_t s)
 {
     WgradArgs a = {};
+    const WgradPlan p = wgrad_plan(d);
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
-    a.x = x; a.dy = dy; a.acc = acc;
-    a.K = d.k; a.P = P; a.Q = Q; a.npix = (long long)d.n * P * Q;
-    a.stride = d.stride; a.pad = d.pad; a.R = d.r; a.S = d.s;
-    const bool stem = rn50_conv_is_stem(d);
-    int BM, BN, BKP, G;
-    if (stem) { a.H = d.h + 6; a.W = d.w + 6; a.C = 4; a.NG = 8; a.direct = 0; BM = 64; BN = 64; BKP = 128; G = 32; }
-    else {
+    a.x = x; a.dy = dy;
+    a.K = d.k; a.P = P; a.Q = Q; a.npix = d.n * P * Q;
+    a.inv_p = 1.0f / (float)P; a.inv_q = 1.0f / (float)Q;
+    a.stride = d.stride; a.pad = d.pad; a.R = d.r; a.S = d.s; a.NG = p.NG;
+    a.dy_bytes = (unsigned)((size_t)a.npix * d.k * sizeof(h16));
+    if (p.stem) {
+        a.H = d.h + 6; a.W = d.w + 6; a.C = 4; a.direct = 0;
+        a.x_bytes = (unsigned)((size_t)d.n * a.H * a.W * 4 * sizeof(h16));
+    } else {
         a.H = d.h; a.W = d.w; a.C = d.c; a.direct = (d.r == 1 && d.stride == 1) ? 1 : 0;
-        a.NG = d.r * d.s * d.c / 64; G = 64;
-        if (d.k % 128 == 0 && a.NG % 2 == 0) { BM = 128; BN = 128; BKP = 64; }
-        else { BM = 64; BN = 64; BKP = 128; }
+        a.x_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.c * sizeof(h16));
     }
-    const int tiles = (d.k / BM) * (a.NG * G / BN);
-    // enough pixel splits to fill the machine (~4 workgroups per compute unit), each a multiple of the K-slab
-    long long slabs = (a.npix + BKP - 1) / BKP;
-    long long want = (1024 + tiles - 1) / tiles;
-    if (want > slabs) want = slabs;
-    if (want < 1) want = 1;
-    const long long slabs_per = (slabs + want - 1) / want;
-    a.pix_per_split = slabs_per * BKP;
-    const int nsplit = (int)((slabs + slabs_per - 1) / slabs_per);
-    const int grid = tiles * nsplit;
-    const double bytes = 2.0 * ((double)d.n * d.h * d.w * d.c + (double)d.n * P * Q * d.k) + 4.0 * d.k * d.r * d.s * d.c;
-    ProfScope ps(stem ? RN50_K_WGRAD_STEM : (BM == 128 ? RN50_K_WGRAD_128x128x64 : RN50_K_WGRAD_64x64x128),
-                 conv_flops(d, P, Q), bytes, s);
-    if (stem) wgrad_kernel<64, 64, 128, 32, true><<<grid, kThreads, 0, s>>>(a);
-    else if (BM == 128) wgrad_kernel<128, 128, 64, 64, false><<<grid, kThreads, 0, s>>>(a);
-    else wgrad_kernel<64, 64, 128, 64, false><<<grid, kThreads, 0, s>>>(a);
-    return rn50_check_launch();
+    a.pix_per_split = p.pix_per_split;
+    a.split_stride = rn50_wgrad_acc_floats(d);
+    a.out = p.nsplit > 1 ? partials : out;
+    const int grid = p.tiles * p.nsplit;
+    {
+        const double bytes = 2.0 * ((double)d.n * d.h * d.w * d.c + (double)d.n * P * Q * d.k) + 4.0 * d.k * d.r * d.s * d.c;
+        ProfScope ps(p.stem ? RN50_K_WGRAD_STEM : (p.BM == 128 ? RN50_K_WGRAD_128x128x64 : RN50_K_WGRAD_64x64x128),
+                     conv_flops(d, P, Q), bytes, s);
+        if (p.stem) wgrad_kernel<64, 64, 4, 32, true><<<grid, kThreads, 0, s>>>(a);
+        else if (p.BM == 128) wgrad_kernel<128, 128, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
+        else wgrad_kernel<64, 64, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
+        RN50_TRY(rn50_check_launch());
+    }
+    if (p.nsplit > 1) {
+        const size_t n4 = a.split_stride / 4;
+        ProfScope ps(RN50_K_WGRAD_REDUCE, 0.0, 4.0 * a.split_stride * (p.nsplit + 1.0), s);
+        wgrad_reduce_kernel<<<(unsigned)((n4 + 15) / 16), kThreads, 0, s>>>(reinterpret_cast<const f32x4*>(partials),
+                                                              reinterpret_cast<f32x4*>(out), n4, p.nsplit, n4);
+        RN50_TRY(rn50_check_launch());
+    }
+    return RN50_OK;
 }
 
 int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, float* out, hipStream_t s)
@@ -793,7 +877,8 @@ extern "C" size_t conv_workspace_bytes(const conv_desc* d, int which)
         case RN50_CONV_DGRAD:
             return stem ? 0 : rn50_round_up((size_t)d->k * d->r * d->s * d->c * sizeof(h16), 256);
         case RN50_CONV_WGRAD: {
-            size_t b = rn50_round_up(rn50_wgrad_acc_floats(*d) * sizeof(float), 256);
+            size_t b = rn50_round_up(rn50_wgrad_acc_floats(*d) * sizeof(float), 256) +
+                       rn50_round_up(rn50_wgrad_partial_floats(*d) * sizeof(float), 256);
             if (stem) b += rn50_stem_padded_bytes(*d) + rn50_round_up((size_t)d->k * 147 * sizeof(float), 256);
             return b;
         }
@@ -843,16 +928,17 @@ extern "C" int conv_wgrad(const conv_desc* d, const void* x, const void* dy, voi
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* acc = static_cast<float*>(ws);
     const size_t acc_floats = rn50_wgrad_acc_floats(*d);
-    RN50_TRY(rn50_fill_zero(acc, acc_floats, s));
+    char* p = static_cast<char*>(ws) + rn50_round_up(acc_floats * sizeof(float), 256);
+    float* partials = reinterpret_cast<float*>(p);
+    p += rn50_round_up(rn50_wgrad_partial_floats(*d) * sizeof(float), 256);
     if (rn50_conv_is_stem(*d)) {
-        char* p = static_cast<char*>(ws) + rn50_round_up(acc_floats * sizeof(float), 256);
         h16* padded = reinterpret_cast<h16*>(p);
         float* unpacked = reinterpret_cast<float*>(p + rn50_stem_padded_bytes(*d));
         RN50_TRY(rn50_stem_pad_image(*d, static_cast<const h16*>(x), padded, s));
-        RN50_TRY(rn50_conv_wgrad_launch(*d, padded, static_cast<const h16*>(dy), acc, s));
+        RN50_TRY(rn50_conv_wgrad_launch(*d, padded, static_cast<const h16*>(dy), acc, partials, s));
         RN50_TRY(rn50_stem_unpack_wgrad(*d, acc, unpacked, s));
         return rn50_cast_f32_to_h16(unpacked, static_cast<h16*>(dw), (size_t)d->k * 147, s);
     }
-    RN50_TRY(rn50_conv_wgrad_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(dy), acc, s));
+    RN50_TRY(rn50_conv_wgrad_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(dy), acc, partials, s));
     return rn50_cast_f32_to_h16(acc, static_cast<h16*>(dw), acc_floats, s);
 }

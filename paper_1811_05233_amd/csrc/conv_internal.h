@@ -30,7 +30,7 @@ struct GatherArgs {
 struct WgradArgs {
     const h16* x;
     const h16* dy;
-    float* acc;          // [K][NG*G] FP32, accumulated with atomics
+    float* out;          // [nsplit][K][NG*G] FP32 partial tiles (or the final tile when there is one split)
     int K;               // output channels (row length of dy)
     int C;               // input channels (row length of x; 4 for the padded stem image)
     int H, W;            // spatial size of x (padded size for the stem)
@@ -38,8 +38,11 @@ struct WgradArgs {
     int R, S, stride, pad;
     int NG;              // granules per output row
     int direct;          // 1x1 stride 1: x pixel index == dy pixel index
-    long long npix;      // N*P*Q
-    long long pix_per_split;
+    int npix;            // N*P*Q
+    int pix_per_split;
+    float inv_p, inv_q;
+    unsigned x_bytes, dy_bytes;
+    size_t split_stride; // floats between consecutive splits' tiles
 };
 
 bool rn50_conv_is_stem(const conv_desc& d);
@@ -57,5 +60,6 @@ int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y,
 size_t rn50_conv_stats_floats(const conv_desc& d);
 int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s);
 size_t rn50_wgrad_acc_floats(const conv_desc& d);
-int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* acc, hipStream_t s);
+size_t rn50_wgrad_partial_floats(const conv_desc& d);
+int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* out, float* partials, hipStream_t s);
 int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, float* out, hipStream_t s);

@@ -11,6 +11,7 @@ enum Rn50Kernel {
     RN50_K_WGRAD_128x128x64,
     RN50_K_WGRAD_64x64x128,
     RN50_K_WGRAD_STEM,
+    RN50_K_WGRAD_REDUCE,
     RN50_K_BN_STATS,
     RN50_K_BN_STATS_FINALIZE,
     RN50_K_BN_APPLY,

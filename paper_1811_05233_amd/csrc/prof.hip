@@ -8,7 +8,7 @@ namespace {
 const char* const kNames[RN50_K_COUNT] = {
     "gather_gemm_kernel<128,128,64>", "gather_gemm_kernel<128,64,64>", "gather_gemm_kernel<64,64,64>",
     "gather_gemm_kernel<128,64,32>",
-    "wgrad_kernel<128,128,64>", "wgrad_kernel<64,64,128>", "wgrad_kernel<stem>",
+    "wgrad_kernel<128,128>", "wgrad_kernel<64,64>", "wgrad_kernel<stem>", "wgrad_reduce_kernel",
     "bn_stats_kernel", "bn_stats_finalize_kernel", "bn_apply_kernel",
     "bn_bwd_reduce_kernel", "bn_bwd_finalize_kernel", "bn_bwd_apply_kernel",
     "sgd_momentum_kernel", "cast_f32_to_h16_kernel", "fill_zero_kernel", "transpose_all_kernel",

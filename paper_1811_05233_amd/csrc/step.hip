@@ -167,6 +167,7 @@ struct rn50_ctx {
     h16* wt_all = nullptr;        // transposed filters
     float* grad32 = nullptr;      // flat FP32 gradient accumulators
     float* bn_ws = nullptr;
+    float* wgrad_part = nullptr;  // per-split partial tiles of the filter gradient
     h16* head_din = nullptr;      // gradient w.r.t. the last block's output (from the FC / avg-pool backward)
     h16* pool_din = nullptr;      // gradient w.r.t. the stem's BN output (from the max-pool backward)
     TransposeJob* jobs = nullptr;
@@ -219,6 +220,10 @@ size_t carve(rn50_ctx& c, char* base)
     for (const ConvLayer& l : L.layers)
         if (rn50_conv_stats_floats(l.d) > bn_ws_floats) bn_ws_floats = rn50_conv_stats_floats(l.d);
     c.bn_ws = reinterpret_cast<float*>(take(bn_ws_floats * sizeof(float)));
+    size_t part_floats = 4;
+    for (const ConvLayer& l : L.layers)
+        if (rn50_wgrad_partial_floats(l.d) > part_floats) part_floats = rn50_wgrad_partial_floats(l.d);
+    c.wgrad_part = reinterpret_cast<float*>(take(part_floats * sizeof(float)));
     // Activation gradients.  Normally six rotating buffers (two alternate as block-input gradients,
     // one holds the shortcut gradient, three are scratch inside a block); with keep_grads every
     // gradient tensor gets its own buffer so that it can be inspected after the step.
@@ -373,8 +378,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     const h16* w16 = static_cast<const h16*>(w_lowp);
     const int B = cfg.batch;
 
-    // ---- per-step preparation: zero the FP32 gradient accumulators, re-lay the filters ----
-    RN50_TRY(rn50_fill_zero(c.grad32, rn50_round_up(L.param_count, 8), s));
+    // ---- per-step preparation: re-lay the filters for the data gradient ----
     if (c.njobs > 0) {
         ProfScope ps(RN50_K_TRANSPOSE, 0.0, 4.0 * c.wt_elems, s);
         transpose_all_kernel<<<c.transpose_blocks, kThreads, 0, s>>>(w16, c.wt_all, c.jobs, c.njobs);
@@ -431,7 +435,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         RN50_TRY(rn50_bn_bwd_launch((long long)l.d.n * l.P * l.Q, l.d.k, relu, dy, l.conv_out, l.bn_out,
                                     master_w + l.gamma_off, l.mean, l.invstd, l.dconv, dres, nullptr, nullptr,
                                     c.grad32 + l.gamma_off, c.grad32 + l.beta_off, c.bn_ws, s));
-        return rn50_conv_wgrad_launch(l.d, in, l.dconv, c.grad32 + l.w_off, s);
+        return rn50_conv_wgrad_launch(l.d, in, l.dconv, c.grad32 + l.w_off, c.wgrad_part, s);
     };
     auto dgrad = [&](ConvLayer& l, const h16* addend) -> int {
         return rn50_conv_dgrad_launch(l.d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s);
@@ -465,8 +469,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         RN50_TRY(rn50_bn_bwd_launch((long long)B * st.P * st.Q, st.d.k, true, c.pool_din, st.conv_out, st.bn_out,
                                     master_w + st.gamma_off, st.mean, st.invstd, st.dconv, nullptr, nullptr, nullptr,
                                     c.grad32 + st.gamma_off, c.grad32 + st.beta_off, c.bn_ws, s));
-        RN50_TRY(rn50_fill_zero(c.stem_wacc, rn50_wgrad_acc_floats(st.d), s));
-        RN50_TRY(rn50_conv_wgrad_launch(st.d, c.stem_padded, st.dconv, c.stem_wacc, s));
+        RN50_TRY(rn50_conv_wgrad_launch(st.d, c.stem_padded, st.dconv, c.stem_wacc, c.wgrad_part, s));
         RN50_TRY(rn50_stem_unpack_wgrad(st.d, c.stem_wacc, c.grad32 + st.w_off, s));
     }
 
