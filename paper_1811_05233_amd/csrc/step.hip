@@ -172,6 +172,10 @@ struct rn50_ctx {
     h16* pool_din = nullptr;      // gradient w.r.t. the stem's BN output (from the max-pool backward)
     TransposeJob* jobs = nullptr;
     int njobs = 0, transpose_blocks = 0;
+    // filter gradients run on a second stream, next to the data-gradient / BN-backward chain
+    hipStream_t side = nullptr;
+    std::vector<hipEvent_t> fork_events;   // one per conv layer: "d(conv output) is ready"
+    hipEvent_t join_event = nullptr;
     size_t max_act = 0, wt_elems = 0;
 };
 
@@ -224,9 +228,9 @@ size_t carve(rn50_ctx& c, char* base)
     for (const ConvLayer& l : L.layers)
         if (rn50_wgrad_partial_floats(l.d) > part_floats) part_floats = rn50_wgrad_partial_floats(l.d);
     c.wgrad_part = reinterpret_cast<float*>(take(part_floats * sizeof(float)));
-    // Activation gradients.  Normally six rotating buffers (two alternate as block-input gradients,
-    // one holds the shortcut gradient, three are scratch inside a block); with keep_grads every
-    // gradient tensor gets its own buffer so that it can be inspected after the step.
+    // Activation gradients.  Normally five rotating buffers (two alternate as block-input gradients,
+    // one holds the shortcut gradient, two are scratch inside a block) plus d(conv output) per layer;
+    // with keep_grads every gradient tensor gets its own buffer so that it can be inspected afterwards.
     const int nb = (int)L.blocks.size();
     if (cfg.keep_grads) {
         for (ConvLayer& l : L.layers) {
@@ -238,18 +242,21 @@ size_t carve(rn50_ctx& c, char* base)
         c.head_din = reinterpret_cast<h16*>(take(L.layers[L.blocks[nb - 1].c3].out_elems() * sizeof(h16)));
         c.pool_din = cfg.has_stem ? reinterpret_cast<h16*>(take(L.layers[0].out_elems() * sizeof(h16))) : nullptr;
     } else {
-        h16* g[6];
-        for (int i = 0; i < 6; ++i) g[i] = reinterpret_cast<h16*>(take(max_act * sizeof(h16)));
+        // d(conv output) keeps a buffer of its own per layer: the filter gradient reads it on the side
+        // stream while the main stream already produces the next layer's gradients
+        for (ConvLayer& l : L.layers) l.dconv = reinterpret_cast<h16*>(take(l.out_elems() * sizeof(h16)));
+        h16* g[5];
+        for (int i = 0; i < 5; ++i) g[i] = reinterpret_cast<h16*>(take(max_act * sizeof(h16)));
         for (int bi = 0; bi < nb; ++bi) {
             const Block& b = L.blocks[bi];
             L.layers[b.c3].dres = g[2];
-            L.layers[b.c3].dconv = g[3]; L.layers[b.c3].din = g[4];
-            L.layers[b.c2].dconv = g[3]; L.layers[b.c2].din = g[4];
-            L.layers[b.c1].dconv = g[3]; L.layers[b.c1].din = g[bi % 2];
-            if (b.proj >= 0) { L.layers[b.proj].dconv = g[4]; L.layers[b.proj].din = g[5]; }
+            L.layers[b.c3].din = g[3];
+            L.layers[b.c2].din = g[3];
+            L.layers[b.c1].din = g[bi % 2];
+            if (b.proj >= 0) L.layers[b.proj].din = g[4];
         }
         c.head_din = g[nb % 2];
-        if (cfg.has_stem) { c.pool_din = g[4]; L.layers[0].dconv = g[3]; }
+        if (cfg.has_stem) c.pool_din = g[3];
     }
     c.jobs = reinterpret_cast<TransposeJob*>(take(L.layers.size() * sizeof(TransposeJob)));
     return off;
@@ -324,11 +331,24 @@ extern "C" int rn50_create(rn50_ctx** out, const rn50_config* cfg, void* workspa
         hipError_t e = hipMemcpy(c->jobs, jobs.data(), jobs.size() * sizeof(TransposeJob), hipMemcpyHostToDevice);
         if (e != hipSuccess) { delete c; return rn50_hip_fail(e); }
     }
+    hipError_t e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_event, hipEventDisableTiming);
+    c->fork_events.assign(c->L.layers.size(), nullptr);
+    for (size_t i = 0; e == hipSuccess && i < c->fork_events.size(); ++i)
+        e = hipEventCreateWithFlags(&c->fork_events[i], hipEventDisableTiming);
+    if (e != hipSuccess) { rn50_destroy(c); return rn50_hip_fail(e); }
     *out = c;
     return RN50_OK;
 }
 
-extern "C" void rn50_destroy(rn50_ctx* ctx) { delete ctx; }
+extern "C" void rn50_destroy(rn50_ctx* ctx)
+{
+    if (!ctx) return;
+    for (hipEvent_t ev : ctx->fork_events) if (ev) (void)hipEventDestroy(ev);
+    if (ctx->join_event) (void)hipEventDestroy(ctx->join_event);
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    delete ctx;
+}
 
 extern "C" int rn50_tensor(rn50_ctx* ctx, const char* name, void** ptr, size_t* elems, int* elem_bytes)
 {
@@ -430,12 +450,21 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     RN50_TRY(rn50_fc_bwd(B, L.feat, cfg.classes, HW, c.feat, w16 + L.fcw_off, c.dlogits, c.grad32 + L.fcw_off,
                          c.grad32 + L.fcb_off, c.head_din, s));
 
-    // BN backward + filter gradient of one conv: dy -> l.dconv (and dres), filter gradient accumulated
+    // BN backward on the main stream: dy -> l.dconv (and dres); then the filter gradient of the conv is
+    // queued on the side stream (it only needs l.dconv and forward activations), so that it overlaps
+    // with the data gradient and the next layer's BN backward.
+    auto fork_wgrad = [&](ConvLayer& l, const h16* in, float* out) -> int {
+        hipEvent_t ev = c.fork_events[&l - &L.layers[0]];
+        hipError_t e = hipEventRecord(ev, s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(c.side, ev, 0);
+        if (e != hipSuccess) return rn50_hip_fail(e);
+        return rn50_conv_wgrad_launch(l.d, in, l.dconv, out, c.wgrad_part, c.side);
+    };
     auto conv_bn_bwd = [&](ConvLayer& l, const h16* in, const h16* dy, bool relu, h16* dres) -> int {
         RN50_TRY(rn50_bn_bwd_launch((long long)l.d.n * l.P * l.Q, l.d.k, relu, dy, l.conv_out, l.bn_out,
                                     master_w + l.gamma_off, l.mean, l.invstd, l.dconv, dres, nullptr, nullptr,
                                     c.grad32 + l.gamma_off, c.grad32 + l.beta_off, c.bn_ws, s));
-        return rn50_conv_wgrad_launch(l.d, in, l.dconv, c.grad32 + l.w_off, c.wgrad_part, s);
+        return fork_wgrad(l, in, c.grad32 + l.w_off);
     };
     auto dgrad = [&](ConvLayer& l, const h16* addend) -> int {
         return rn50_conv_dgrad_launch(l.d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s);
@@ -469,8 +498,13 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         RN50_TRY(rn50_bn_bwd_launch((long long)B * st.P * st.Q, st.d.k, true, c.pool_din, st.conv_out, st.bn_out,
                                     master_w + st.gamma_off, st.mean, st.invstd, st.dconv, nullptr, nullptr, nullptr,
                                     c.grad32 + st.gamma_off, c.grad32 + st.beta_off, c.bn_ws, s));
-        RN50_TRY(rn50_conv_wgrad_launch(st.d, c.stem_padded, st.dconv, c.stem_wacc, c.wgrad_part, s));
-        RN50_TRY(rn50_stem_unpack_wgrad(st.d, c.stem_wacc, c.grad32 + st.w_off, s));
+        RN50_TRY(fork_wgrad(st, c.stem_padded, c.stem_wacc));
+        RN50_TRY(rn50_stem_unpack_wgrad(st.d, c.stem_wacc, c.grad32 + st.w_off, c.side));
+    }
+    {   // join: everything queued on the side stream precedes the gradient cast and the update
+        hipError_t e = hipEventRecord(c.join_event, c.side);
+        if (e == hipSuccess) e = hipStreamWaitEvent(s, c.join_event, 0);
+        if (e != hipSuccess) return rn50_hip_fail(e);
     }
 
     // ================= flat FP16 gradient, update =================
