@@ -352,11 +352,23 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(long long m, int
 
 struct BnPlan { int nblk; int rows_per_block; };
 
+// Elementwise passes: 4 rows per thread (one unrolled batch), as many workgroups as that takes.
+BnPlan plan_rows_apply(long long m, int c)
+{
+    const RowMap rm = make_rowmap(c);
+    const long long rows = (long long)rm.rows_par * kUnroll;
+    BnPlan p;
+    p.nblk = (int)((m + rows - 1) / rows);
+    p.rows_per_block = (int)rows;
+    return p;
+}
+
+// Reducing passes: partials cost a second kernel, so fewer, fatter workgroups.
 BnPlan plan_rows(long long m, int c)
 {
     const RowMap rm = make_rowmap(c);
-    // about 16 row iterations per thread, at most kMaxBlocks workgroups
-    long long rows = (long long)rm.rows_par * 16;
+    // about 8 row iterations per thread, at most kMaxBlocks workgroups
+    long long rows = (long long)rm.rows_par * 8;
     long long nblk = (m + rows - 1) / rows;
     if (nblk > kMaxBlocks) {
         rows = (m + kMaxBlocks - 1) / kMaxBlocks;
@@ -405,8 +417,9 @@ int rn50_bn_fwd_launch(long long m, int c, float eps, bool relu, const h16* x, c
         bn_stats_finalize_kernel<<<rn50_cdiv(c, kThreads / 64), kThreads, 0, s>>>(m, c, eps, p.nblk, x, ws, save_mean, save_invstd);
     }
     ProfScope ps(RN50_K_BN_APPLY, 0.0, (res ? 6.0 : 4.0) * elems, s);
-#define RN50_BN_APPLY(R, Z) bn_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, x, gamma, beta, save_mean, \
-                                                                              save_invstd, res, y, p.rows_per_block)
+    const BnPlan pa = plan_rows_apply(m, c);
+#define RN50_BN_APPLY(R, Z) bn_apply_kernel<R, Z><<<pa.nblk, kThreads, 0, s>>>(m, c, x, gamma, beta, save_mean, \
+                                                                               save_invstd, res, y, pa.rows_per_block)
     if (relu) { if (res) RN50_BN_APPLY(true, true); else RN50_BN_APPLY(true, false); }
     else      { if (res) RN50_BN_APPLY(false, true); else RN50_BN_APPLY(false, false); }
 #undef RN50_BN_APPLY
@@ -419,7 +432,6 @@ int rn50_bn_fwd_from_partials_launch(long long m, int c, float eps, bool relu, c
                                      const float* beta, const h16* res, h16* y, float* save_mean, float* save_invstd,
                                      const float* part, int ntiles, hipStream_t s)
 {
-    const BnPlan p = plan_rows(m, c);
     const double elems = (double)m * c;
     {
         ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * ntiles * c, s);
@@ -427,8 +439,9 @@ int rn50_bn_fwd_from_partials_launch(long long m, int c, float eps, bool relu, c
                                                                                  save_mean, save_invstd);
     }
     ProfScope ps(RN50_K_BN_APPLY, 0.0, (res ? 6.0 : 4.0) * elems, s);
-#define RN50_BN_APPLY(R, Z) bn_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, x, gamma, beta, save_mean, \
-                                                                              save_invstd, res, y, p.rows_per_block)
+    const BnPlan pa = plan_rows_apply(m, c);
+#define RN50_BN_APPLY(R, Z) bn_apply_kernel<R, Z><<<pa.nblk, kThreads, 0, s>>>(m, c, x, gamma, beta, save_mean, \
+                                                                               save_invstd, res, y, pa.rows_per_block)
     if (relu) { if (res) RN50_BN_APPLY(true, true); else RN50_BN_APPLY(true, false); }
     else      { if (res) RN50_BN_APPLY(false, true); else RN50_BN_APPLY(false, false); }
 #undef RN50_BN_APPLY
@@ -452,8 +465,9 @@ int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* 
         bn_bwd_finalize_kernel<<<rn50_cdiv(c, kThreads / 64), kThreads, 0, s>>>(c, p.nblk, ws, sums, dgamma, dbeta, dgamma32, dbeta32);
     }
     ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, ((relu ? 6.0 : 4.0) + 2.0 + (dres ? 2.0 : 0.0)) * elems, s);
-#define RN50_BN_BWD(R, Z) bn_bwd_apply_kernel<R, Z><<<p.nblk, kThreads, 0, s>>>(m, c, dy, x, y, gamma, save_mean, \
-                                                                                save_invstd, sums, dx, dres, p.rows_per_block)
+    const BnPlan pa = plan_rows_apply(m, c);
+#define RN50_BN_BWD(R, Z) bn_bwd_apply_kernel<R, Z><<<pa.nblk, kThreads, 0, s>>>(m, c, dy, x, y, gamma, save_mean, \
+                                                                                 save_invstd, sums, dx, dres, pa.rows_per_block)
     if (relu) { if (dres) RN50_BN_BWD(true, true); else RN50_BN_BWD(true, false); }
     else      { if (dres) RN50_BN_BWD(false, true); else RN50_BN_BWD(false, false); }
 #undef RN50_BN_BWD

@@ -1,5 +1,6 @@
 // Momentum SGD over the flat parameter buffer and the FP32 -> FP16 parameter cast.
 // Pure HBM streaming: 20 bytes per parameter (read g 2, w 4, v 4; write w 4, v 4, w16 2).
+// Plain (temporal) 16-byte accesses: non-temporal hints measured 15-25 % slower here.
 //
 // Floating-point contraction is off in this file: the update is evaluated exactly as written
 // (separately rounded FP32 multiplies and adds), so it matches an FP32 host evaluation bit for bit.
@@ -36,11 +37,11 @@ __global__ __launch_bounds__(kThreads) void sgd_momentum_kernel(
     const size_t nvec = n / 8;
     const size_t stride = (size_t)gridDim.x * kThreads;
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
-        const h16x8 gv = __builtin_nontemporal_load(reinterpret_cast<const h16x8*>(g) + i);
-        f32x4 w0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(w) + 2 * i);
-        f32x4 w1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(w) + 2 * i + 1);
-        f32x4 v0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(v) + 2 * i);
-        f32x4 v1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(v) + 2 * i + 1);
+        const h16x8 gv = reinterpret_cast<const h16x8*>(g)[i];
+        f32x4 w0 = reinterpret_cast<const f32x4*>(w)[2 * i];
+        f32x4 w1 = reinterpret_cast<const f32x4*>(w)[2 * i + 1];
+        f32x4 v0 = reinterpret_cast<const f32x4*>(v)[2 * i];
+        f32x4 v1 = reinterpret_cast<const f32x4*>(v)[2 * i + 1];
         h16x8 lo;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -53,11 +54,11 @@ __global__ __launch_bounds__(kThreads) void sgd_momentum_kernel(
             w1[j] = w1[j] - lr * v1[j];
             lo[4 + j] = (h16)w1[j];
         }
-        __builtin_nontemporal_store(w0, reinterpret_cast<f32x4*>(w) + 2 * i);
-        __builtin_nontemporal_store(w1, reinterpret_cast<f32x4*>(w) + 2 * i + 1);
-        __builtin_nontemporal_store(v0, reinterpret_cast<f32x4*>(v) + 2 * i);
-        __builtin_nontemporal_store(v1, reinterpret_cast<f32x4*>(v) + 2 * i + 1);
-        if (kWriteLowp) __builtin_nontemporal_store(lo, reinterpret_cast<h16x8*>(w16) + i);
+        reinterpret_cast<f32x4*>(w)[2 * i] = w0;
+        reinterpret_cast<f32x4*>(w)[2 * i + 1] = w1;
+        reinterpret_cast<f32x4*>(v)[2 * i] = v0;
+        reinterpret_cast<f32x4*>(v)[2 * i + 1] = v1;
+        if (kWriteLowp) reinterpret_cast<h16x8*>(w16)[i] = lo;
     }
     // ragged tail (n not a multiple of 8): one thread per element
     const size_t tail0 = nvec * 8;
@@ -93,7 +94,9 @@ int stream_grid(size_t n)
 {
     const size_t nvec = n / 8 + 1;
     size_t blocks = (nvec + kThreads - 1) / kThreads;
-    const size_t cap = 256 * 16;   // 256 compute units, up to 16 resident blocks of 256 threads each
+    // one 8-element group per thread: measured faster than a capped grid with a grid-stride loop
+    // (6.7 vs 5.0 TB/s on the 25.6 M-parameter buffer); the loop only matters beyond 2^31 threads
+    const size_t cap = (size_t)1 << 22;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     return (int)blocks;
