@@ -298,6 +298,13 @@ def test_step_resnet50_batch2_in_situ():
     check_step_in_situ(2, (224, 224), True, (3, 4, 6, 3))
 
 
+def test_step_resnet50_batch32_in_situ_sampled():
+    """The benchmarked configuration (batch 32, 224x224): every BN / pooling / loss / FC result in full,
+    convolution outputs and data gradients for 2 sampled images, filter gradients for 8 sampled output
+    channels per layer (each computed by the oracle from the GPU's own layer inputs)."""
+    check_step_in_situ(32, (224, 224), True, (3, 4, 6, 3), n_img=2, n_k=8)
+
+
 def test_step_small_in_situ_ragged():
     check_step_in_situ(3, (32, 48), True, (2, 2))
 
