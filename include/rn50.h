@@ -199,7 +199,9 @@ int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* labels,
  * name: "<conv>.conv" (conv output), "<conv>.out" (BN output), "<conv>.mean",
  * "<conv>.invstd", "pool.out", "feat", "logits", "dlogits"; with keep_grads also
  * "<conv>.dconv" (gradient w.r.t. the conv output), "<conv>.din" (w.r.t. its input; for conv1
- * it includes the shortcut's share), "<conv3>.dres" (masked gradient given to the shortcut),
+ * it includes the shortcut's share; where the input is a ReLU output inside the network the
+ * stored tensor is already multiplied by the ReLU mask [input > 0]),
+ * "<conv3>.dres" (masked gradient given to the shortcut),
  * "head.din" (w.r.t. the last block's output), "pool.din" (w.r.t. the stem's BN output);
  * <conv> = "stem" or "s<stage>b<block>{c1,c2,c3,p}" (stage from 1).  *elems = element count,
  * *elem_bytes = 2 or 4.  Unknown name: RN50_ERR_SHAPE. */

@@ -474,6 +474,26 @@ int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* 
     return rn50_check_launch();
 }
 
+// Backward for a layer whose masked incoming gradient g and per-row-tile partial sums (sum g, sum g*xhat)
+// were already produced by the data gradient that wrote g: combine the partials, then dx.  sums: 2c floats.
+int rn50_bn_bwd_from_partials_launch(long long m, int c, const h16* g, const h16* x, const float* gamma,
+                                     const float* save_mean, const float* save_invstd, h16* dx,
+                                     float* dgamma32, float* dbeta32, const float* part, int ntiles, float* sums,
+                                     hipStream_t s)
+{
+    const double elems = (double)m * c;
+    {
+        ProfScope ps(RN50_K_BN_BWD_FINALIZE, 0.0, 8.0 * ntiles * c, s);
+        bn_bwd_finalize_kernel<<<rn50_cdiv(c, kThreads / 64), kThreads, 0, s>>>(c, ntiles, part, sums, nullptr, nullptr,
+                                                                               dgamma32, dbeta32);
+    }
+    ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, 6.0 * elems, s);
+    const BnPlan pa = plan_rows_apply(m, c);
+    bn_bwd_apply_kernel<false, false><<<pa.nblk, kThreads, 0, s>>>(m, c, g, x, nullptr, gamma, save_mean, save_invstd,
+                                                                   sums, dx, nullptr, pa.rows_per_block);
+    return rn50_check_launch();
+}
+
 extern "C" int bn_relu_fwd(const bn_desc* d, const void* x, const float* gamma, const float* beta,
                            const void* residual, void* y, float* save_mean, float* save_invstd,
                            void* ws, size_t ws_bytes, void* stream)

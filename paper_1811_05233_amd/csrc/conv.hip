@@ -247,9 +247,18 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     constexpr int OCPR = BN / 8;                 // output chunks per row
     constexpr int ORPP = kThreads / OCPR;
     const int oc = tid % OCPR, orl = tid / OCPR;
-    float st[16];                                // per-channel sum and sum of squares of the stored halves
+    // Per-channel sums over this tile's rows.  Forward: sum and sum of squares of the stored halves (BN
+    // statistics of the layer that follows).  Data gradient with bn_x set: the stored gradient g is first
+    // masked by the ReLU of the tensor it belongs to (mask_y), then sum g and sum g*xhat are formed for the
+    // backward pass of the BN that produced that tensor.
+    float st[16], mu[8], is[8];
 #pragma unroll
     for (int j = 0; j < 16; ++j) st[j] = 0.f;
+    const bool bwd_stats = a.bn_x != nullptr;
+    if (bwd_stats) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { mu[j] = a.bn_mean[nt * BN + oc * 8 + j]; is[j] = a.bn_invstd[nt * BN + oc * 8 + j]; }
+    }
 #pragma unroll
     for (int i = 0; i < BM / ORPP; ++i) {
         const int row = orl + i * ORPP;
@@ -259,14 +268,30 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
             fast_divmod(m, OWs, inv_ow, t, wq);
             fast_divmod(t, OHs, inv_oh, n, hq);
             const size_t opix = ((size_t)n * a.OH + hq * a.o_mul + a.oph[cls]) * a.OW + wq * a.o_mul + a.opw[cls];
-            const h16x8 v = *reinterpret_cast<const h16x8*>(lds + row * EP + oc * 8);
-            *reinterpret_cast<h16x8*>(a.out + opix * a.NO + nt * BN + oc * 8) = v;
+            const size_t gidx = opix * a.NO + nt * BN + oc * 8;
+            h16x8 v = *reinterpret_cast<const h16x8*>(lds + row * EP + oc * 8);
+            if (a.mask_y) {
+                const h16x8 yv = *reinterpret_cast<const h16x8*>(a.mask_y + gidx);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) { const float f = (float)v[j]; st[j] += f; st[8 + j] += f * f; }
+                for (int j = 0; j < 8; ++j) v[j] = (float)yv[j] > 0.f ? v[j] : (h16)0.f;
+            }
+            *reinterpret_cast<h16x8*>(a.out + gidx) = v;
+            if (bwd_stats) {
+                const h16x8 xv = *reinterpret_cast<const h16x8*>(a.bn_x + gidx);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float g = (float)v[j];
+                    st[j] += g;
+                    st[8 + j] += g * (((float)xv[j] - mu[j]) * is[j]);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) { const float f = (float)v[j]; st[j] += f; st[8 + j] += f * f; }
+            }
         }
     }
     if (a.stats_part) {
-        // BatchNorm statistics of this row tile, summed in a fixed order: [tile][sum | sumsq][channel]
+        // per-channel sums of this row tile, added in a fixed order: [tile][first | second sum][channel]
         float* red = reinterpret_cast<float*>(lds + BM * EP);          // ORPP x 2 x BN floats behind the staged tile
         static_assert(BM * EP * 2 + ORPP * 2 * BN * 4 <= LDS_HALFS * 2, "statistics scratch must fit in LDS");
 #pragma unroll
@@ -733,9 +758,14 @@ int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y,
 }
 
 // Data gradient.  wt is the filter transposed to [C][R][S][K].  addend (nullable) has dx's layout.
-int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s)
+int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s,
+                           const DgradBnFuse* fuse, int* tiles_out)
 {
     GatherArgs a = {};
+    if (fuse) {
+        a.mask_y = fuse->mask_y; a.bn_x = fuse->bn_x; a.bn_mean = fuse->mean; a.bn_invstd = fuse->invstd;
+        a.stats_part = fuse->part;
+    }
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     a.A = dy; a.B = wt; a.out = dx; a.addend = addend;
     a.a_bytes = (unsigned)((size_t)d.n * P * Q * d.k * sizeof(h16));
@@ -765,7 +795,17 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
     // a strided 1x1 data gradient still writes every pixel of dx
     const double bytes = conv_bytes(d, P, Q, addend != nullptr) +
                          ((d.r == 1 && d.stride > 1) ? 2.0 * d.n * ((double)d.h * d.w - (double)P * Q) * d.c : 0.0);
-    return dispatch_gather(a, s, conv_flops(d, P, Q), bytes);
+    const int rc = dispatch_gather(a, s, conv_flops(d, P, Q), bytes + (fuse ? 4.0 * d.n * d.h * d.w * d.c : 0.0));
+    if (tiles_out) *tiles_out = a.mt_end[a.ncls - 1];
+    return rc;
+}
+
+// upper bound of the floats a fused data gradient writes to DgradBnFuse::part: one row tile per 64 pixels
+// (plus one ragged tile per parity class), two sums per input channel
+size_t rn50_dgrad_stats_floats(const conv_desc& d)
+{
+    const long long rows = (long long)d.n * d.h * d.w;
+    return (size_t)((rows + 63) / 64 + 4) * 2 * d.c;
 }
 
 // upper bound of the floats conv_fwd writes to stats_part: (smallest tile = 64 rows) x 2 x k
@@ -919,7 +959,7 @@ extern "C" int conv_dgrad(const conv_desc* d, const void* dy, const void* w, voi
     hipStream_t s = static_cast<hipStream_t>(stream);
     h16* wt = static_cast<h16*>(ws);
     RN50_TRY(rn50_transpose_filter(*d, static_cast<const h16*>(w), wt, s));
-    return rn50_conv_dgrad_launch(*d, static_cast<const h16*>(dy), wt, nullptr, static_cast<h16*>(dx), s);
+    return rn50_conv_dgrad_launch(*d, static_cast<const h16*>(dy), wt, nullptr, static_cast<h16*>(dx), s, nullptr, nullptr);
 }
 
 extern "C" int conv_wgrad(const conv_desc* d, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes, void* stream)

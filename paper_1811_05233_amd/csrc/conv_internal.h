@@ -7,7 +7,11 @@ struct GatherArgs {
     const h16* B;        // [NO][T][CR]
     h16* out;            // NHWC output, NO channels
     const h16* addend;   // nullable, same layout as out
-    float* stats_part;   // nullable: per row tile, [sum | sum of squares][NO] of the stored output (forward only)
+    float* stats_part;   // nullable: per row tile, two per-channel sums of the stored output, [tile][2][NO]
+    const h16* mask_y;   // nullable (data gradient): zero the output where this tensor (out's layout) is <= 0
+    const h16* bn_x;     // nullable (data gradient): input of the BN that produced mask_y; switches the sums
+    const float* bn_mean;    //   to sum g and sum g*xhat with xhat = (bn_x - mean) * invstd
+    const float* bn_invstd;
     int NB;              // images
     int IH, IW;          // spatial size of A
     int lda;             // halfs between adjacent pixels of A
@@ -58,7 +62,18 @@ int rn50_cast_f32_to_h16(const float* src, h16* dst, size_t n, hipStream_t s);
 int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y, hipStream_t s, float* stats_part,
                          int* stats_tiles);
 size_t rn50_conv_stats_floats(const conv_desc& d);
-int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s);
+// Optional fusion of the ReLU mask and the BN-backward reductions of the layer that produced this
+// convolution's input into the data gradient's epilogue.
+struct DgradBnFuse {
+    const h16* mask_y;     // the convolution's own input (a ReLU output)
+    const h16* bn_x;       // conv output the BN normalised to produce mask_y
+    const float* mean;
+    const float* invstd;
+    float* part;           // [row tile][sum g | sum g*xhat][channels], rn50_dgrad_stats_floats(d) floats
+};
+int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s,
+                           const DgradBnFuse* fuse, int* tiles_out);
+size_t rn50_dgrad_stats_floats(const conv_desc& d);
 size_t rn50_wgrad_acc_floats(const conv_desc& d);
 size_t rn50_wgrad_partial_floats(const conv_desc& d);
 int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* out, float* partials, hipStream_t s);

@@ -19,3 +19,7 @@ size_t rn50_bn_ws_floats(int c);
 int rn50_bn_fwd_from_partials_launch(long long m, int c, float eps, bool relu, const h16* x, const float* gamma,
                                      const float* beta, const h16* res, h16* y, float* save_mean, float* save_invstd,
                                      const float* part, int ntiles, hipStream_t s);
+int rn50_bn_bwd_from_partials_launch(long long m, int c, const h16* g, const h16* x, const float* gamma,
+                                     const float* save_mean, const float* save_invstd, h16* dx,
+                                     float* dgamma32, float* dbeta32, const float* part, int ntiles, float* sums,
+                                     hipStream_t s);

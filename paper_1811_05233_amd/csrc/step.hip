@@ -221,8 +221,11 @@ size_t carve(rn50_ctx& c, char* base)
     c.wt_all = reinterpret_cast<h16*>(take(wt_elems * sizeof(h16)));
     c.grad32 = reinterpret_cast<float*>(take(rn50_round_up(L.param_count, 8) * sizeof(float)));
     size_t bn_ws_floats = rn50_bn_ws_floats(max_c);
-    for (const ConvLayer& l : L.layers)
+    for (const ConvLayer& l : L.layers) {
         if (rn50_conv_stats_floats(l.d) > bn_ws_floats) bn_ws_floats = rn50_conv_stats_floats(l.d);
+        if (l.d.c != 3 && rn50_dgrad_stats_floats(l.d) + 2 * (size_t)l.d.c > bn_ws_floats)
+            bn_ws_floats = rn50_dgrad_stats_floats(l.d) + 2 * (size_t)l.d.c;
+    }
     c.bn_ws = reinterpret_cast<float*>(take(bn_ws_floats * sizeof(float)));
     size_t part_floats = 4;
     for (const ConvLayer& l : L.layers)
@@ -258,6 +261,9 @@ size_t carve(rn50_ctx& c, char* base)
         c.head_din = g[nb % 2];
         if (cfg.has_stem) c.pool_din = g[3];
     }
+    // conv3's masked shortcut gradient is the (masked) block-output gradient itself whenever that was
+    // produced by the next block's conv1 data gradient; only the last block keeps a buffer of its own
+    for (int bi = 0; bi + 1 < nb; ++bi) L.layers[L.blocks[bi].c3].dres = L.layers[L.blocks[bi + 1].c1].din;
     c.jobs = reinterpret_cast<TransposeJob*>(take(L.layers.size() * sizeof(TransposeJob)));
     return off;
 }
@@ -450,9 +456,8 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     RN50_TRY(rn50_fc_bwd(B, L.feat, cfg.classes, HW, c.feat, w16 + L.fcw_off, c.dlogits, c.grad32 + L.fcw_off,
                          c.grad32 + L.fcb_off, c.head_din, s));
 
-    // BN backward on the main stream: dy -> l.dconv (and dres); then the filter gradient of the conv is
-    // queued on the side stream (it only needs l.dconv and forward activations), so that it overlaps
-    // with the data gradient and the next layer's BN backward.
+    // The filter gradient of a conv is queued on the side stream as soon as d(conv output) exists (it only
+    // needs that and forward activations), so that it overlaps with the data-gradient / BN-backward chain.
     auto fork_wgrad = [&](ConvLayer& l, const h16* in, float* out) -> int {
         hipEvent_t ev = c.fork_events[&l - &L.layers[0]];
         hipError_t e = hipEventRecord(ev, s);
@@ -460,37 +465,61 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         if (e != hipSuccess) return rn50_hip_fail(e);
         return rn50_conv_wgrad_launch(l.d, in, l.dconv, out, c.wgrad_part, c.side);
     };
-    auto conv_bn_bwd = [&](ConvLayer& l, const h16* in, const h16* dy, bool relu, h16* dres) -> int {
-        RN50_TRY(rn50_bn_bwd_launch((long long)l.d.n * l.P * l.Q, l.d.k, relu, dy, l.conv_out, l.bn_out,
-                                    master_w + l.gamma_off, l.mean, l.invstd, l.dconv, dres, nullptr, nullptr,
-                                    c.grad32 + l.gamma_off, c.grad32 + l.beta_off, c.bn_ws, s));
-        return fork_wgrad(l, in, c.grad32 + l.w_off);
+    // BN backward, stand-alone form (reduce, finalize, apply): dy -> l.dconv (and dres)
+    auto bn_bwd_std = [&](ConvLayer& l, const h16* dy, bool relu, h16* dres) -> int {
+        return rn50_bn_bwd_launch((long long)l.d.n * l.P * l.Q, l.d.k, relu, dy, l.conv_out, l.bn_out,
+                                  master_w + l.gamma_off, l.mean, l.invstd, l.dconv, dres, nullptr, nullptr,
+                                  c.grad32 + l.gamma_off, c.grad32 + l.beta_off, c.bn_ws, s);
     };
-    auto dgrad = [&](ConvLayer& l, const h16* addend) -> int {
-        return rn50_conv_dgrad_launch(l.d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s);
+    // BN backward when the data gradient that produced g already applied the ReLU mask and left the
+    // per-tile sums (sum g, sum g*xhat) in c.bn_ws: finalize + apply only
+    int fused_tiles = 0;
+    auto bn_bwd_fused = [&](ConvLayer& l, const h16* g) -> int {
+        float* sums = c.bn_ws + (size_t)fused_tiles * 2 * l.d.k;
+        return rn50_bn_bwd_from_partials_launch((long long)l.d.n * l.P * l.Q, l.d.k, g, l.conv_out,
+                                                master_w + l.gamma_off, l.mean, l.invstd, l.dconv,
+                                                c.grad32 + l.gamma_off, c.grad32 + l.beta_off, c.bn_ws, fused_tiles,
+                                                sums, s);
+    };
+    // data gradient of conv l into l.din.  prev (nullable) = the layer whose BN+ReLU output `in` is l's input:
+    // then the result is masked by in > 0 and the BN-backward sums of prev are formed in the epilogue.
+    auto dgrad = [&](ConvLayer& l, const h16* addend, ConvLayer* prev, const h16* in) -> int {
+        DgradBnFuse f = {in, prev ? prev->conv_out : nullptr, prev ? prev->mean : nullptr,
+                         prev ? prev->invstd : nullptr, c.bn_ws};
+        return rn50_conv_dgrad_launch(l.d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s, prev ? &f : nullptr,
+                                      prev ? &fused_tiles : nullptr);
     };
 
     const h16* dY = c.head_din;
+    bool dY_fused = false;   // dY is already masked and conv3's BN sums are waiting in c.bn_ws
     for (int bi = (int)L.blocks.size() - 1; bi >= 0; --bi) {
         const Block& b = L.blocks[bi];
         ConvLayer &l1 = L.layers[b.c1], &l2 = L.layers[b.c2], &l3 = L.layers[b.c3];
+        ConvLayer* below = bi > 0 ? &L.layers[L.blocks[bi - 1].c3] : nullptr;   // produced this block's input
         const bool need_in = cfg.has_stem || bi > 0;
-        RN50_TRY(conv_bn_bwd(l3, l2.bn_out, dY, true, l3.dres));     // also the masked shortcut gradient
-        RN50_TRY(dgrad(l3, nullptr));
-        RN50_TRY(conv_bn_bwd(l2, l1.bn_out, l3.din, true, nullptr));
-        RN50_TRY(dgrad(l2, nullptr));
-        RN50_TRY(conv_bn_bwd(l1, block_in[bi], l2.din, true, nullptr));
+        const h16* gres;                                              // masked gradient for the shortcut
+        if (dY_fused) { RN50_TRY(bn_bwd_fused(l3, dY)); gres = dY; }
+        else { RN50_TRY(bn_bwd_std(l3, dY, true, l3.dres)); gres = l3.dres; }
+        RN50_TRY(fork_wgrad(l3, l2.bn_out, c.grad32 + l3.w_off));
+        RN50_TRY(dgrad(l3, nullptr, &l2, l2.bn_out));
+        RN50_TRY(bn_bwd_fused(l2, l3.din));
+        RN50_TRY(fork_wgrad(l2, l1.bn_out, c.grad32 + l2.w_off));
+        RN50_TRY(dgrad(l2, nullptr, &l1, l1.bn_out));
+        RN50_TRY(bn_bwd_fused(l1, l2.din));
+        RN50_TRY(fork_wgrad(l1, block_in[bi], c.grad32 + l1.w_off));
         if (b.proj >= 0) {
             ConvLayer& lp = L.layers[b.proj];
-            RN50_TRY(conv_bn_bwd(lp, block_in[bi], l3.dres, false, nullptr));
+            RN50_TRY(bn_bwd_std(lp, gres, false, nullptr));
+            RN50_TRY(fork_wgrad(lp, block_in[bi], c.grad32 + lp.w_off));
             if (need_in) {
-                RN50_TRY(dgrad(lp, nullptr));
-                RN50_TRY(dgrad(l1, lp.din));                         // main path + projection shortcut
+                RN50_TRY(dgrad(lp, nullptr, nullptr, nullptr));
+                RN50_TRY(dgrad(l1, lp.din, below, block_in[bi]));     // main path + projection shortcut
             }
         } else {
-            RN50_TRY(dgrad(l1, l3.dres));                            // main path + identity shortcut
+            RN50_TRY(dgrad(l1, gres, below, block_in[bi]));           // main path + identity shortcut
         }
         dY = l1.din;
+        dY_fused = below != nullptr;
     }
     if (cfg.has_stem) {
         ConvLayer& st = L.layers[0];

@@ -241,6 +241,8 @@ def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, 
     head = gt("head.din", tg[last + "c3.out"])
     check("head.din", head, O.round_binary16(O.avgpool_bwd(O.round_binary16(da), hw_last)))
 
+    first_blk = net.block_list[0]["name"]
+
     def layer_bwd(nm, dy, relu, want_dres, addend, need_dx):
         cv = net.convs[nm]
         xin, conv, outp = tg[nm + ".in"], tg[nm + ".conv"], tg[nm + ".out"]
@@ -265,6 +267,9 @@ def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, 
             rdx = O.conv_dgrad(dconv[sel], net.view(w16, nm + ".w"), xin[sel].shape, cv["stride"], cv["pad"])
             if addend is not None:
                 rdx = rdx + addend[sel]
+            # the library stores the gradient of a ReLU output already multiplied by the ReLU mask
+            if nm.endswith(("c2", "c3")) or (nm.endswith("c1") and not nm.startswith(first_blk)):
+                rdx = rdx * (xin[sel] > 0)
             check(nm + ".din", din[sel], rdx)
         return din, dres
 
