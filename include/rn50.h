@@ -195,6 +195,15 @@ int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* labels,
               float* master_w, float* momentum, void* w_lowp, void* grad_lowp,
               const rn50_hparams* hp, float* loss_out, void* stream);
 
+/* Optional: measures, for every convolution of the network and each of its three kernels, the kernel
+ * variants the library has (tile shapes, pipeline depths, split counts) on the real tensors of one
+ * forward+backward pass, and makes later rn50_step calls on this context use the fastest.  Arguments as
+ * for rn50_step without the update.  Unlike every other call this one SYNCHRONISES (it times kernels
+ * with HIP events) and must not run under stream capture.  Results of later steps stay within the
+ * documented tolerances but may differ in the last bits from an untuned context (summation order). */
+int rn50_autotune(rn50_ctx* ctx, const void* images, const int32_t* labels, float* master_w, void* w_lowp,
+                  void* grad_lowp, float* loss_out, void* stream);
+
 /* Device address of a tensor the last rn50_step left in the workspace, for parity checks.
  * name: "<conv>.conv" (conv output), "<conv>.out" (BN output), "<conv>.mean",
  * "<conv>.invstd", "pool.out", "feat", "logits", "dlogits"; with keep_grads also

@@ -73,6 +73,7 @@ _SIGNATURES = {
     "rn50_step": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(rn50_hparams), _vp, _vp]),
     "rn50_profile_begin": (_i, []),
     "rn50_profile_end": (_i, [ctypes.POINTER(rn50_profile_entry), _i, ctypes.POINTER(_i)]),
+    "rn50_autotune": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "rn50_tensor": (_i, [_vp, ctypes.c_char_p, ctypes.POINTER(_vp), ctypes.POINTER(_sz), ctypes.POINTER(_i)]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -248,6 +249,11 @@ class Rn50Context:
         hpp = None if hp is None else ctypes.byref(hp)
         _check(lib().rn50_step(self.handle, _ptr(images), _ptr(labels), _ptr(master_w), _ptr(momentum),
                                _ptr(w_lowp), _ptr(grad_lowp), hpp, _ptr(loss_out), _stream()), "rn50_step")
+
+    def autotune(self, images, labels, master_w, w_lowp, grad_lowp, loss_out):
+        """Time the kernel variants of every convolution on one forward+backward pass (synchronises)."""
+        _check(lib().rn50_autotune(self.handle, _ptr(images), _ptr(labels), _ptr(master_w), _ptr(w_lowp),
+                                   _ptr(grad_lowp), _ptr(loss_out), _stream()), "rn50_autotune")
 
     def tensor(self, name):
         """Copy of a workspace tensor left by the last step, as a flat torch tensor (half or float)."""

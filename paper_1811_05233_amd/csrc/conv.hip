@@ -13,8 +13,6 @@
 // The filter gradient reduces over pixels, which is the strided dimension of both operands; its
 // loader transposes 8x8 half blocks in registers on the way into LDS, after which the same MFMA
 // loop applies.  The pixel range is split over workgroups and combined with FP32 atomic adds.
-#include <cstdlib>
-
 #include "common.h"
 #include "conv_internal.h"
 #include "prof.h"
@@ -53,6 +51,12 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {
 #define RN50_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xc07f)
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
+#ifndef RN50_AUX_A
+#define RN50_AUX_A 0
+#endif
+#ifndef RN50_AUX_B
+#define RN50_AUX_B 0
+#endif
 
 // m = q*d + r with 0 <= r < d, for 0 <= m < 2^24, using the precomputed float reciprocal of d.
 __device__ __forceinline__ void fast_divmod(int m, int d, float inv_d, int& q, int& r) {
@@ -151,12 +155,12 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
             const int ih = a_h0[j] + dh, iw = a_w0[j] + dw;
             const bool ok = (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW;
             const unsigned voff = ok ? a_voff[j] + (unsigned)a_delta : kOutOfRange;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(sa + (wave + 4 * j) * 512), 16, (int)voff, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(sa + (wave + 4 * j) * 512), 16, (int)voff, 0, 0, RN50_AUX_A);
         }
 #pragma unroll
         for (int j = 0; j < NB; ++j)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(sb + (wave + 4 * j) * 512), 16,
-                                                     (int)(b_voff[j] + b_delta), 0, 0, 0);
+                                                     (int)(b_voff[j] + b_delta), 0, 0, RN50_AUX_B);
         if (++ld_cc == KC) { ld_cc = 0; ++ld_ti; }
         if (++ld_stage == NST) ld_stage = 0;
     };
@@ -626,25 +630,35 @@ int launch_gather(GatherArgs& a, hipStream_t s, int kid, double flops, double by
     return rn50_check_launch();
 }
 
-int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes)
+bool gather_tile_ok(const GatherArgs& a, int tile)
+{
+    if (tile < 0 || tile >= RN50_NUM_GATHER_TILES) return false;
+    return tile != RN50_TILE_128x128 || a.NO % 128 == 0;
+}
+
+// default choice when no tuned tile is given: the large tile while it still yields about two workgroups
+// per compute unit, else smaller ones
+int gather_tile_heuristic(const GatherArgs& a)
+{
+    long long rows = 0;
+    for (int c = 0; c < a.ncls; ++c) rows += (long long)a.NB * a.cOHs[c] * a.cOWs[c];
+    if (a.NO % 128 == 0 && (rows / 128) * (a.NO / 128) >= 400) return RN50_TILE_128x128;
+    if ((rows / 128) * (a.NO / 64) >= 400) return RN50_TILE_128x64;
+    return RN50_TILE_64x64_DEEP;
+}
+
+int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, int tile)
 {
     if (a.CR == 32)                 // stem forward
         return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
-    long long rows = 0;
-    for (int c = 0; c < a.ncls; ++c) rows += (long long)a.NB * a.cOHs[c] * a.cOWs[c];
-    static int dev_tile = -1;
-    if (dev_tile < 0) { const char* e = getenv("RN50_TILE"); dev_tile = e ? atoi(e) : 0; }
-    if (dev_tile == 1 && a.NO % 128 == 0) return launch_gather<128, 128, 32, 4, 2>(a, s, RN50_K_GATHER_128x128x64, flops, bytes);
-    if (dev_tile == 2 && a.NO % 128 == 0) return launch_gather<128, 128, 64, 3, 1>(a, s, RN50_K_GATHER_128x128x64, flops, bytes);
-    if (dev_tile == 3) return launch_gather<64, 64, 64, 4, 2>(a, s, RN50_K_GATHER_64x64x64, flops, bytes);
-    if (dev_tile == 4) return launch_gather<128, 64, 64, 3, 2>(a, s, RN50_K_GATHER_128x64x64, flops, bytes);
-    if (dev_tile == 5) return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_64x64x64, flops, bytes);
-    // prefer the large tile while it still yields about two workgroups per compute unit
-    if (a.NO % 128 == 0 && (rows / 128) * (a.NO / 128) >= 400)
-        return launch_gather<128, 128, 32, 4, 2>(a, s, RN50_K_GATHER_128x128x64, flops, bytes);
-    if ((rows / 128) * (a.NO / 64) >= 400)
-        return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_128x64x64, flops, bytes);
-    return launch_gather<64, 64, 64, 4, 2>(a, s, RN50_K_GATHER_64x64x64, flops, bytes);
+    if (!gather_tile_ok(a, tile)) tile = gather_tile_heuristic(a);
+    switch (tile) {
+        case RN50_TILE_128x128: return launch_gather<128, 128, 32, 4, 2>(a, s, RN50_K_GATHER_128x128, flops, bytes);
+        case RN50_TILE_128x64: return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_128x64, flops, bytes);
+        case RN50_TILE_64x64_DEEP: return launch_gather<64, 64, 64, 4, 2>(a, s, RN50_K_GATHER_64x64, flops, bytes);
+        case RN50_TILE_64x64_WIDE: return launch_gather<64, 64, 64, 2, 4>(a, s, RN50_K_GATHER_64x64, flops, bytes);
+        default: return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_64x64, flops, bytes);
+    }
 }
 
 // algorithmic work of one convolution (either direction): 2*M*N*K flops; bytes = input pixels actually
@@ -726,7 +740,7 @@ int rn50_cast_f32_to_h16(const float* src, h16* dst, size_t n, hipStream_t s)
 
 // Forward.  For the stem, x is the padded 4-channel image and w the packed filter.
 int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y, hipStream_t s, float* stats_part,
-                         int* stats_tiles)
+                         int* stats_tiles, int tile)
 {
     GatherArgs a = {};
     a.stats_part = stats_part;
@@ -752,14 +766,14 @@ int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y,
                 a.tap[0][t] = pack_tap(r - d.pad, q - d.pad, t);
             }
     }
-    const int rc = dispatch_gather(a, s, conv_flops(d, P, Q), conv_bytes(d, P, Q, false));
+    const int rc = dispatch_gather(a, s, conv_flops(d, P, Q), conv_bytes(d, P, Q, false), tile);
     if (stats_tiles) *stats_tiles = a.mt_end[0];
     return rc;
 }
 
 // Data gradient.  wt is the filter transposed to [C][R][S][K].  addend (nullable) has dx's layout.
 int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s,
-                           const DgradBnFuse* fuse, int* tiles_out)
+                           const DgradBnFuse* fuse, int* tiles_out, int tile)
 {
     GatherArgs a = {};
     if (fuse) {
@@ -795,7 +809,7 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
     // a strided 1x1 data gradient still writes every pixel of dx
     const double bytes = conv_bytes(d, P, Q, addend != nullptr) +
                          ((d.r == 1 && d.stride > 1) ? 2.0 * d.n * ((double)d.h * d.w - (double)P * Q) * d.c : 0.0);
-    const int rc = dispatch_gather(a, s, conv_flops(d, P, Q), bytes + (fuse ? 4.0 * d.n * d.h * d.w * d.c : 0.0));
+    const int rc = dispatch_gather(a, s, conv_flops(d, P, Q), bytes + (fuse ? 4.0 * d.n * d.h * d.w * d.c : 0.0), tile);
     if (tiles_out) *tiles_out = a.mt_end[a.ncls - 1];
     return rc;
 }
@@ -824,22 +838,26 @@ size_t rn50_wgrad_acc_floats(const conv_desc& d)
 namespace {
 struct WgradPlan { int BM, BN, G, NG, tiles, nsplit, pix_per_split; bool stem; };
 
-WgradPlan wgrad_plan(const conv_desc& d)
+// variant: RN50_TILE_AUTO, or tile_index * 3 + split_index with tile 0 = 128x128 (if the shape allows),
+// 1 = 64x64 and split targets of 256, 512, 1024 workgroups
+WgradPlan wgrad_plan(const conv_desc& d, int variant)
 {
     WgradPlan p;
+    const int want_blocks = variant < 0 ? 512 : 256 << (variant % 3);
+    const bool small_tile = variant >= 3;
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     const long long npix = (long long)d.n * P * Q;
     p.stem = rn50_conv_is_stem(d);
     if (p.stem) { p.BM = 64; p.BN = 64; p.G = 32; p.NG = 8; }
     else {
         p.G = 64; p.NG = d.r * d.s * d.c / 64;
-        if (d.k % 128 == 0 && p.NG % 2 == 0) { p.BM = 128; p.BN = 128; }
+        if (d.k % 128 == 0 && p.NG % 2 == 0 && !small_tile) { p.BM = 128; p.BN = 128; }
         else { p.BM = 64; p.BN = 64; }
     }
     p.tiles = (d.k / p.BM) * (p.NG * p.G / p.BN);
-    // pixel splits: about two workgroups per compute unit, but at least 8 K-slabs of 32 pixels each
+    // pixel splits: about want_blocks workgroups, but at least 8 K-slabs of 32 pixels each
     const long long slabs = (npix + 31) / 32;
-    long long want = (512 + p.tiles - 1) / p.tiles;
+    long long want = (want_blocks + p.tiles - 1) / p.tiles;
     long long slabs_per = (slabs + want - 1) / want;
     if (slabs_per < 8) slabs_per = slabs < 8 ? slabs : 8;
     p.pix_per_split = (int)(slabs_per * 32);
@@ -851,16 +869,22 @@ WgradPlan wgrad_plan(const conv_desc& d)
 // floats of scratch rn50_conv_wgrad_launch needs for its per-split partial tiles (0 if it does not split)
 size_t rn50_wgrad_partial_floats(const conv_desc& d)
 {
-    const WgradPlan p = wgrad_plan(d);
-    return p.nsplit > 1 ? (size_t)p.nsplit * rn50_wgrad_acc_floats(d) : 0;
+    size_t most = 0;
+    for (int v = RN50_TILE_AUTO; v < RN50_NUM_WGRAD_VARIANTS; ++v) {
+        const WgradPlan p = wgrad_plan(d, v);
+        const size_t f = p.nsplit > 1 ? (size_t)p.nsplit * rn50_wgrad_acc_floats(d) : 0;
+        if (f > most) most = f;
+    }
+    return most;
 }
 
 // Filter gradient in FP32 into out (layout [K][R][S][C]; stem: [K][8][32]); every element is written.
 // partials: scratch of rn50_wgrad_partial_floats(d) floats.  For the stem, x is the padded 4-channel image.
-int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* out, float* partials, hipStream_t s)
+int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* out, float* partials, hipStream_t s,
+                           int variant)
 {
     WgradArgs a = {};
-    const WgradPlan p = wgrad_plan(d);
+    const WgradPlan p = wgrad_plan(d, variant);
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     a.x = x; a.dy = dy;
     a.K = d.k; a.P = P; a.Q = Q; a.npix = d.n * P * Q;
@@ -880,7 +904,7 @@ int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, floa
     const int grid = p.tiles * p.nsplit;
     {
         const double bytes = 2.0 * ((double)d.n * d.h * d.w * d.c + (double)d.n * P * Q * d.k) + 4.0 * d.k * d.r * d.s * d.c;
-        ProfScope ps(p.stem ? RN50_K_WGRAD_STEM : (p.BM == 128 ? RN50_K_WGRAD_128x128x64 : RN50_K_WGRAD_64x64x128),
+        ProfScope ps(p.stem ? RN50_K_WGRAD_STEM : (p.BM == 128 ? RN50_K_WGRAD_128x128 : RN50_K_WGRAD_64x64),
                      conv_flops(d, P, Q), bytes, s);
         if (p.stem) wgrad_kernel<64, 64, 4, 32, true><<<grid, kThreads, 0, s>>>(a);
         else if (p.BM == 128) wgrad_kernel<128, 128, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
@@ -945,10 +969,10 @@ extern "C" int conv_fwd(const conv_desc* d, const void* x, const void* w, void* 
         h16* packed = reinterpret_cast<h16*>(static_cast<char*>(ws) + rn50_stem_padded_bytes(*d));
         RN50_TRY(rn50_stem_pad_image(*d, static_cast<const h16*>(x), padded, s));
         RN50_TRY(rn50_stem_pack_filter(*d, static_cast<const h16*>(w), packed, s));
-        return rn50_conv_fwd_launch(*d, padded, packed, static_cast<h16*>(y), s, nullptr, nullptr);
+        return rn50_conv_fwd_launch(*d, padded, packed, static_cast<h16*>(y), s, nullptr, nullptr, RN50_TILE_AUTO);
     }
     return rn50_conv_fwd_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(w), static_cast<h16*>(y), s, nullptr,
-                                nullptr);
+                                nullptr, RN50_TILE_AUTO);
 }
 
 extern "C" int conv_dgrad(const conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, void* stream)
@@ -959,7 +983,8 @@ extern "C" int conv_dgrad(const conv_desc* d, const void* dy, const void* w, voi
     hipStream_t s = static_cast<hipStream_t>(stream);
     h16* wt = static_cast<h16*>(ws);
     RN50_TRY(rn50_transpose_filter(*d, static_cast<const h16*>(w), wt, s));
-    return rn50_conv_dgrad_launch(*d, static_cast<const h16*>(dy), wt, nullptr, static_cast<h16*>(dx), s, nullptr, nullptr);
+    return rn50_conv_dgrad_launch(*d, static_cast<const h16*>(dy), wt, nullptr, static_cast<h16*>(dx), s, nullptr, nullptr,
+                                  RN50_TILE_AUTO);
 }
 
 extern "C" int conv_wgrad(const conv_desc* d, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes, void* stream)
@@ -975,10 +1000,10 @@ extern "C" int conv_wgrad(const conv_desc* d, const void* x, const void* dy, voi
         h16* padded = reinterpret_cast<h16*>(p);
         float* unpacked = reinterpret_cast<float*>(p + rn50_stem_padded_bytes(*d));
         RN50_TRY(rn50_stem_pad_image(*d, static_cast<const h16*>(x), padded, s));
-        RN50_TRY(rn50_conv_wgrad_launch(*d, padded, static_cast<const h16*>(dy), acc, partials, s));
+        RN50_TRY(rn50_conv_wgrad_launch(*d, padded, static_cast<const h16*>(dy), acc, partials, s, RN50_TILE_AUTO));
         RN50_TRY(rn50_stem_unpack_wgrad(*d, acc, unpacked, s));
         return rn50_cast_f32_to_h16(unpacked, static_cast<h16*>(dw), (size_t)d->k * 147, s);
     }
-    RN50_TRY(rn50_conv_wgrad_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(dy), acc, partials, s));
+    RN50_TRY(rn50_conv_wgrad_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(dy), acc, partials, s, RN50_TILE_AUTO));
     return rn50_cast_f32_to_h16(acc, static_cast<h16*>(dw), acc_floats, s);
 }

@@ -2,6 +2,19 @@
 #pragma once
 #include "common.h"
 
+// Tile variants of the gather GEMM (rows x columns of the output tile, K-slab, ring stages) and of the
+// filter gradient (tile x split target); RN50_TILE_AUTO lets the launcher's heuristic choose.
+enum {
+    RN50_TILE_AUTO = -1,
+    RN50_TILE_128x128 = 0,     // 128x128, 32-wide slabs, 4 stages (needs output channels % 128 == 0)
+    RN50_TILE_128x64,          // 128x64, 32-wide slabs, 4 stages
+    RN50_TILE_64x64_DEEP,      // 64x64, 64-wide slabs, 4 stages, 2 workgroups per compute unit
+    RN50_TILE_64x64_WIDE,      // 64x64, 64-wide slabs, 2 stages, 4 workgroups per compute unit
+    RN50_TILE_64x64_K32,       // 64x64, 32-wide slabs, 4 stages, 4 workgroups per compute unit
+    RN50_NUM_GATHER_TILES,
+    RN50_NUM_WGRAD_VARIANTS = 6
+};
+
 struct GatherArgs {
     const h16* A;        // gathered NHWC tensor
     const h16* B;        // [NO][T][CR]
@@ -60,7 +73,7 @@ int rn50_fill_zero(float* p, size_t n, hipStream_t s);
 int rn50_cast_f32_to_h16(const float* src, h16* dst, size_t n, hipStream_t s);
 // stats_part (nullable): receives per-row-tile BatchNorm partial sums; *stats_tiles = number of row tiles
 int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y, hipStream_t s, float* stats_part,
-                         int* stats_tiles);
+                         int* stats_tiles, int tile);
 size_t rn50_conv_stats_floats(const conv_desc& d);
 // Optional fusion of the ReLU mask and the BN-backward reductions of the layer that produced this
 // convolution's input into the data gradient's epilogue.
@@ -72,9 +85,10 @@ struct DgradBnFuse {
     float* part;           // [row tile][sum g | sum g*xhat][channels], rn50_dgrad_stats_floats(d) floats
 };
 int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s,
-                           const DgradBnFuse* fuse, int* tiles_out);
+                           const DgradBnFuse* fuse, int* tiles_out, int tile);
 size_t rn50_dgrad_stats_floats(const conv_desc& d);
 size_t rn50_wgrad_acc_floats(const conv_desc& d);
 size_t rn50_wgrad_partial_floats(const conv_desc& d);
-int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* out, float* partials, hipStream_t s);
+int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* out, float* partials, hipStream_t s,
+                           int variant);
 int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, float* out, hipStream_t s);

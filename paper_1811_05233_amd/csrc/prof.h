@@ -4,12 +4,12 @@
 #include "common.h"
 
 enum Rn50Kernel {
-    RN50_K_GATHER_128x128x64 = 0,   // conv forward / data gradient, 128x128 tile
-    RN50_K_GATHER_128x64x64,        // conv forward / data gradient, 128x64 tile
-    RN50_K_GATHER_64x64x64,         // conv forward / data gradient, 64x64 tile (few output pixels)
+    RN50_K_GATHER_128x128 = 0,      // conv forward / data gradient, 128x128 tile
+    RN50_K_GATHER_128x64,           // conv forward / data gradient, 128x64 tile
+    RN50_K_GATHER_64x64,            // conv forward / data gradient, 64x64 tiles
     RN50_K_GATHER_STEM,             // stem forward (128x64 tile, 32-wide K slabs)
-    RN50_K_WGRAD_128x128x64,
-    RN50_K_WGRAD_64x64x128,
+    RN50_K_WGRAD_128x128,
+    RN50_K_WGRAD_64x64,
     RN50_K_WGRAD_STEM,
     RN50_K_WGRAD_REDUCE,
     RN50_K_BN_STATS,

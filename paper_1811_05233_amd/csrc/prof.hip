@@ -6,8 +6,8 @@
 namespace {
 
 const char* const kNames[RN50_K_COUNT] = {
-    "gather_gemm_kernel<128,128,64>", "gather_gemm_kernel<128,64,64>", "gather_gemm_kernel<64,64,64>",
-    "gather_gemm_kernel<128,64,32>",
+    "gather_gemm_kernel<128,128,..>", "gather_gemm_kernel<128,64,..>", "gather_gemm_kernel<64,64,..>",
+    "gather_gemm_kernel<128,64,32> (stem)",
     "wgrad_kernel<128,128>", "wgrad_kernel<64,64>", "wgrad_kernel<stem>", "wgrad_reduce_kernel",
     "bn_stats_kernel", "bn_stats_finalize_kernel", "bn_apply_kernel",
     "bn_bwd_reduce_kernel", "bn_bwd_finalize_kernel", "bn_bwd_apply_kernel",

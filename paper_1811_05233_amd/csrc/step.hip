@@ -30,6 +30,8 @@ struct ConvLayer {
     h16* dconv = nullptr;                // gradient w.r.t. the conv output (BN backward result)
     h16* din = nullptr;                  // gradient w.r.t. the conv input (data-gradient result)
     h16* dres = nullptr;                 // conv3 only: masked gradient handed to the shortcut
+    // kernel variants (RN50_TILE_AUTO until rn50_autotune has measured them)
+    int fwd_tile = RN50_TILE_AUTO, dgrad_tile = RN50_TILE_AUTO, wgrad_variant = RN50_TILE_AUTO;
     size_t in_elems() const { return (size_t)d.n * d.h * d.w * d.c; }
     size_t out_elems() const { return (size_t)d.n * P * Q * d.k; }
 };
@@ -176,6 +178,8 @@ struct rn50_ctx {
     hipStream_t side = nullptr;
     std::vector<hipEvent_t> fork_events;   // one per conv layer: "d(conv output) is ready"
     hipEvent_t join_event = nullptr;
+    bool tuning = false;                   // rn50_autotune: every conv launch site times its variants
+    hipEvent_t tune_e0 = nullptr, tune_e1 = nullptr;
     size_t max_act = 0, wt_elems = 0;
 };
 
@@ -339,6 +343,8 @@ extern "C" int rn50_create(rn50_ctx** out, const rn50_config* cfg, void* workspa
     }
     hipError_t e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_event, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreate(&c->tune_e0);
+    if (e == hipSuccess) e = hipEventCreate(&c->tune_e1);
     c->fork_events.assign(c->L.layers.size(), nullptr);
     for (size_t i = 0; e == hipSuccess && i < c->fork_events.size(); ++i)
         e = hipEventCreateWithFlags(&c->fork_events[i], hipEventDisableTiming);
@@ -352,6 +358,8 @@ extern "C" void rn50_destroy(rn50_ctx* ctx)
     if (!ctx) return;
     for (hipEvent_t ev : ctx->fork_events) if (ev) (void)hipEventDestroy(ev);
     if (ctx->join_event) (void)hipEventDestroy(ctx->join_event);
+    if (ctx->tune_e0) (void)hipEventDestroy(ctx->tune_e0);
+    if (ctx->tune_e1) (void)hipEventDestroy(ctx->tune_e1);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
     delete ctx;
 }
@@ -389,6 +397,34 @@ extern "C" int rn50_tensor(rn50_ctx* ctx, const char* name, void** ptr, size_t* 
     return RN50_ERR_SHAPE;
 }
 
+namespace {
+// Launch site with variants.  Normally launches variant *choice.  In tuning mode it times every variant
+// (one warm-up, two timed launches, device-synchronous) on stream s, stores the fastest in *choice and
+// leaves its (identical) result in place.
+template <class F>
+int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch)
+{
+    if (!c.tuning) return launch(*choice);
+    float best_ms = 1e30f;
+    int best = RN50_TILE_AUTO;
+    for (int cand = 0; cand < ncand; ++cand) {
+        RN50_TRY(launch(cand));
+        hipError_t e = hipEventRecord(c.tune_e0, s);
+        if (e != hipSuccess) return rn50_hip_fail(e);
+        RN50_TRY(launch(cand));
+        RN50_TRY(launch(cand));
+        e = hipEventRecord(c.tune_e1, s);
+        if (e == hipSuccess) e = hipEventSynchronize(c.tune_e1);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, c.tune_e0, c.tune_e1);
+        if (e != hipSuccess) return rn50_hip_fail(e);
+        if (ms < best_ms) { best_ms = ms; best = cand; }
+    }
+    *choice = best;
+    return launch(best);
+}
+}  // namespace
+
 extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* labels, float* master_w, float* momentum,
                          void* w_lowp, void* grad_lowp, const rn50_hparams* hp, float* loss_out, void* stream)
 {
@@ -414,7 +450,9 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     // convolution (its epilogue also leaves the BatchNorm partial sums of every row tile), then BN
     auto conv_bn_fwd = [&](ConvLayer& l, const h16* x, const h16* wts, bool relu, const h16* residual) -> int {
         int tiles = 0;
-        RN50_TRY(rn50_conv_fwd_launch(l.d, x, wts, l.conv_out, s, c.bn_ws, &tiles));
+        RN50_TRY(launch_or_tune(c, s, l.d.c == 3 ? 1 : RN50_NUM_GATHER_TILES, &l.fwd_tile, [&](int tile) {
+            return rn50_conv_fwd_launch(l.d, x, wts, l.conv_out, s, c.bn_ws, &tiles, tile);
+        }));
         return rn50_bn_fwd_from_partials_launch((long long)l.d.n * l.P * l.Q, l.d.k, cfg.bn_eps, relu, l.conv_out,
                                                 master_w + l.gamma_off, master_w + l.beta_off, residual, l.bn_out,
                                                 l.mean, l.invstd, c.bn_ws, tiles, s);
@@ -463,7 +501,9 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         hipError_t e = hipEventRecord(ev, s);
         if (e == hipSuccess) e = hipStreamWaitEvent(c.side, ev, 0);
         if (e != hipSuccess) return rn50_hip_fail(e);
-        return rn50_conv_wgrad_launch(l.d, in, l.dconv, out, c.wgrad_part, c.side);
+        return launch_or_tune(c, c.side, l.d.c == 3 ? 3 : RN50_NUM_WGRAD_VARIANTS, &l.wgrad_variant, [&](int variant) {
+            return rn50_conv_wgrad_launch(l.d, in, l.dconv, out, c.wgrad_part, c.side, variant);
+        });
     };
     // BN backward, stand-alone form (reduce, finalize, apply): dy -> l.dconv (and dres)
     auto bn_bwd_std = [&](ConvLayer& l, const h16* dy, bool relu, h16* dres) -> int {
@@ -486,8 +526,10 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     auto dgrad = [&](ConvLayer& l, const h16* addend, ConvLayer* prev, const h16* in) -> int {
         DgradBnFuse f = {in, prev ? prev->conv_out : nullptr, prev ? prev->mean : nullptr,
                          prev ? prev->invstd : nullptr, c.bn_ws};
-        return rn50_conv_dgrad_launch(l.d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s, prev ? &f : nullptr,
-                                      prev ? &fused_tiles : nullptr);
+        return launch_or_tune(c, s, RN50_NUM_GATHER_TILES, &l.dgrad_tile, [&](int tile) {
+            return rn50_conv_dgrad_launch(l.d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s, prev ? &f : nullptr,
+                                          prev ? &fused_tiles : nullptr, tile);
+        });
     };
 
     const h16* dY = c.head_din;
@@ -542,4 +584,16 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         RN50_TRY(sgd_momentum_flat(L.param_count, grad_lowp, RN50_F16, hp->grad_scale, master_w, momentum, w_lowp,
                                    hp->lr, hp->momentum, hp->wd, stream));
     return RN50_OK;
+}
+
+extern "C" int rn50_autotune(rn50_ctx* ctx, const void* images, const int32_t* labels, float* master_w, void* w_lowp,
+                             void* grad_lowp, float* loss_out, void* stream)
+{
+    RN50_REQUIRE_PTR(ctx);
+    ctx->tuning = true;
+    const int rc = rn50_step(ctx, images, labels, master_w, nullptr, w_lowp, grad_lowp, nullptr, loss_out, stream);
+    ctx->tuning = false;
+    if (rc != RN50_OK) return rc;
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RN50_OK : rn50_hip_fail(e);
 }

@@ -37,7 +37,7 @@ def make_problem(batch, image_hw, has_stem, blocks, classes=1000, loss_scale=128
     return cfg, net, w, x, lab
 
 
-def run_gpu(cfg, w, x, lab, hp):
+def run_gpu(cfg, w, x, lab, hp, autotune=False):
     n = w.size
     ctx = P.Rn50Context(cfg)
     wd, vd = dev_f(w), torch.zeros(n, dtype=torch.float32, device=DEV)
@@ -45,7 +45,11 @@ def run_gpu(cfg, w, x, lab, hp):
     g16 = torch.zeros(n, dtype=torch.float16, device=DEV)
     P.rn50_cast_params(n, wd, w16)
     loss = torch.zeros(1, dtype=torch.float32, device=DEV)
-    ctx.step(dev_h(x), dev_i(lab), wd, vd, w16, g16, hp, loss)
+    xd, ld = dev_h(x), dev_i(lab)
+    if autotune:
+        ctx.autotune(xd, ld, wd, w16, g16, loss)
+        assert np.array_equal(host(wd), w.astype(np.float64))       # tuning never touches the parameters
+    ctx.step(xd, ld, wd, vd, w16, g16, hp, loss)
     torch.cuda.synchronize()
     return ctx, dict(w=host(wd), v=host(vd), w16=host(w16), g16=host(g16), loss=float(host(loss)[0]))
 
@@ -173,7 +177,8 @@ def test_step_two_blocks_per_stage_ragged_batch():
     check_step(3, (32, 48), True, (2, 2), fwd_tol=3e-2)
 
 
-def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, loss_scale=1024.0, classes=1000):
+def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, loss_scale=1024.0, classes=1000,
+                       autotune=False):
     """Every kernel launch inside one rn50_step call, checked where it ran: the oracle recomputes
     each layer's result from the GPU's OWN input tensors of that layer (read back from the workspace,
     keep_grads=1), so rounding differences cannot pile up over the depth of the network and the
@@ -187,7 +192,7 @@ def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, 
     cfg.keep_grads = 1
     lr, mu, wd_ = 0.1, 0.9, 1e-4
     hp = P.rn50_hparams(lr, mu, wd_, 1.0 / loss_scale)
-    ctx, out = run_gpu(cfg, w, x, lab, hp)
+    ctx, out = run_gpu(cfg, w, x, lab, hp, autotune)
     tg = gpu_forward_tensors(ctx, net, x, batch)
     w64 = w.astype(f64)
     w16 = O.round_binary16(w64)
@@ -304,14 +309,19 @@ def test_step_resnet50_batch2_in_situ():
 
 
 def test_step_resnet50_batch32_in_situ_sampled():
-    """The benchmarked configuration (batch 32, 224x224): every BN / pooling / loss / FC result in full,
+    """The benchmarked configuration (batch 32, 224x224, kernel variants autotuned as bench.py does): every
+    BN / pooling / loss / FC result in full,
     convolution outputs and data gradients for 2 sampled images, filter gradients for 8 sampled output
     channels per layer (each computed by the oracle from the GPU's own layer inputs)."""
-    check_step_in_situ(32, (224, 224), True, (3, 4, 6, 3), n_img=2, n_k=8)
+    check_step_in_situ(32, (224, 224), True, (3, 4, 6, 3), n_img=2, n_k=8, autotune=True)
 
 
 def test_step_small_in_situ_ragged():
     check_step_in_situ(3, (32, 48), True, (2, 2))
+
+
+def test_step_small_in_situ_autotuned():
+    check_step_in_situ(4, (64, 64), True, (1, 2, 1, 1), autotune=True)
 
 
 def test_step_without_update_and_determinism_of_forward():
