@@ -169,6 +169,7 @@ struct rn50_ctx {
     h16* wt_all = nullptr;        // transposed filters
     float* grad32 = nullptr;      // flat FP32 gradient accumulators
     float* bn_ws = nullptr;
+    float* bn_ws_side = nullptr;  // BN partial sums of the projection branch (forward, side stream)
     float* wgrad_part = nullptr;  // per-split partial tiles of the filter gradient
     h16* head_din = nullptr;      // gradient w.r.t. the last block's output (from the FC / avg-pool backward)
     h16* pool_din = nullptr;      // gradient w.r.t. the stem's BN output (from the max-pool backward)
@@ -231,6 +232,7 @@ size_t carve(rn50_ctx& c, char* base)
             bn_ws_floats = rn50_dgrad_stats_floats(l.d) + 2 * (size_t)l.d.c;
     }
     c.bn_ws = reinterpret_cast<float*>(take(bn_ws_floats * sizeof(float)));
+    c.bn_ws_side = reinterpret_cast<float*>(take(bn_ws_floats * sizeof(float)));
     size_t part_floats = 4;
     for (const ConvLayer& l : L.layers)
         if (rn50_wgrad_partial_floats(l.d) > part_floats) part_floats = rn50_wgrad_partial_floats(l.d);
@@ -448,14 +450,15 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     }
 
     // convolution (its epilogue also leaves the BatchNorm partial sums of every row tile), then BN
-    auto conv_bn_fwd = [&](ConvLayer& l, const h16* x, const h16* wts, bool relu, const h16* residual) -> int {
+    auto conv_bn_fwd = [&](ConvLayer& l, const h16* x, const h16* wts, bool relu, const h16* residual,
+                           hipStream_t st, float* part) -> int {
         int tiles = 0;
-        RN50_TRY(launch_or_tune(c, s, l.d.c == 3 ? 1 : RN50_NUM_GATHER_TILES, &l.fwd_tile, [&](int tile) {
-            return rn50_conv_fwd_launch(l.d, x, wts, l.conv_out, s, c.bn_ws, &tiles, tile);
+        RN50_TRY(launch_or_tune(c, st, l.d.c == 3 ? 1 : RN50_NUM_GATHER_TILES, &l.fwd_tile, [&](int tile) {
+            return rn50_conv_fwd_launch(l.d, x, wts, l.conv_out, st, part, &tiles, tile);
         }));
         return rn50_bn_fwd_from_partials_launch((long long)l.d.n * l.P * l.Q, l.d.k, cfg.bn_eps, relu, l.conv_out,
                                                 master_w + l.gamma_off, master_w + l.beta_off, residual, l.bn_out,
-                                                l.mean, l.invstd, c.bn_ws, tiles, s);
+                                                l.mean, l.invstd, part, tiles, st);
     };
 
     // ================= forward =================
@@ -464,7 +467,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         ConvLayer& st = L.layers[0];
         RN50_TRY(rn50_stem_pad_image(st.d, x, c.stem_padded, s));
         RN50_TRY(rn50_stem_pack_filter(st.d, w16 + st.w_off, c.stem_packed, s));
-        RN50_TRY(conv_bn_fwd(st, c.stem_padded, c.stem_packed, true, nullptr));
+        RN50_TRY(conv_bn_fwd(st, c.stem_padded, c.stem_packed, true, nullptr, s, c.bn_ws));
         RN50_TRY(rn50_maxpool_fwd(B, st.P, st.Q, st.d.k, st.bn_out, c.pool_out, c.pool_arg, s));
         x = c.pool_out;
     }
@@ -472,14 +475,27 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     for (size_t bi = 0; bi < L.blocks.size(); ++bi) {
         const Block& b = L.blocks[bi];
         block_in[bi] = x;
-        RN50_TRY(conv_bn_fwd(L.layers[b.c1], x, w16 + L.layers[b.c1].w_off, true, nullptr));
-        RN50_TRY(conv_bn_fwd(L.layers[b.c2], L.layers[b.c1].bn_out, w16 + L.layers[b.c2].w_off, true, nullptr));
         const h16* shortcut = x;
         if (b.proj >= 0) {
-            RN50_TRY(conv_bn_fwd(L.layers[b.proj], x, w16 + L.layers[b.proj].w_off, false, nullptr));
-            shortcut = L.layers[b.proj].bn_out;
+            // the projection shortcut (conv + BN) only depends on the block input: run it on the side
+            // stream next to conv1 -> conv2 and join before conv3's BN adds it
+            ConvLayer& lp = L.layers[b.proj];
+            hipEvent_t ev = c.fork_events[b.proj];
+            hipError_t e = hipEventRecord(ev, s);
+            if (e == hipSuccess) e = hipStreamWaitEvent(c.side, ev, 0);
+            if (e != hipSuccess) return rn50_hip_fail(e);
+            RN50_TRY(conv_bn_fwd(lp, x, w16 + lp.w_off, false, nullptr, c.side, c.bn_ws_side));
+            e = hipEventRecord(c.join_event, c.side);
+            if (e != hipSuccess) return rn50_hip_fail(e);
+            shortcut = lp.bn_out;
         }
-        RN50_TRY(conv_bn_fwd(L.layers[b.c3], L.layers[b.c2].bn_out, w16 + L.layers[b.c3].w_off, true, shortcut));
+        RN50_TRY(conv_bn_fwd(L.layers[b.c1], x, w16 + L.layers[b.c1].w_off, true, nullptr, s, c.bn_ws));
+        RN50_TRY(conv_bn_fwd(L.layers[b.c2], L.layers[b.c1].bn_out, w16 + L.layers[b.c2].w_off, true, nullptr, s, c.bn_ws));
+        if (b.proj >= 0) {
+            hipError_t e = hipStreamWaitEvent(s, c.join_event, 0);
+            if (e != hipSuccess) return rn50_hip_fail(e);
+        }
+        RN50_TRY(conv_bn_fwd(L.layers[b.c3], L.layers[b.c2].bn_out, w16 + L.layers[b.c3].w_off, true, shortcut, s, c.bn_ws));
         x = L.layers[b.c3].bn_out;
     }
     const int HW = L.final_h * L.final_w;
