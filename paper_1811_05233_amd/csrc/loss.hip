@@ -7,6 +7,7 @@
 namespace {
 
 constexpr int kWaves = 16;
+constexpr int kCache = 16;   // logits per lane kept in registers (rows of up to 1024 classes)
 
 __global__ __launch_bounds__(kWaves * 64) void ls_xent_kernel(
     int batch, int classes, const float* __restrict__ logits, const int32_t* __restrict__ labels,
@@ -19,20 +20,46 @@ __global__ __launch_bounds__(kWaves * 64) void ls_xent_kernel(
     float my_total = 0.f;   // identical on every lane of the wave
     for (int i = wave; i < batch; i += kWaves) {
         const float* z = logits + (size_t)i * classes;
+        // the lane's logits are read once into registers when the row is short enough (<= 64*kCache)
+        float zc[kCache];
+        const bool cached = classes <= 64 * kCache;
         float m = -INFINITY;
-        for (int k = lane; k < classes; k += 64) m = fmaxf(m, z[k]);
+        if (cached) {
+#pragma unroll
+            for (int u = 0; u < kCache; ++u) {
+                const int k = lane + 64 * u;
+                zc[u] = k < classes ? z[k] : -INFINITY;
+                m = fmaxf(m, zc[u]);
+            }
+        } else {
+            for (int k = lane; k < classes; k += 64) m = fmaxf(m, z[k]);
+        }
         m = wave_max(m);
         float se = 0.f;
-        for (int k = lane; k < classes; k += 64) se += expf(z[k] - m);
+        if (cached) {
+#pragma unroll
+            for (int u = 0; u < kCache; ++u) se += expf(zc[u] - m);      // exp(-inf) = 0 for the padding
+        } else {
+            for (int k = lane; k < classes; k += 64) se += expf(z[k] - m);
+        }
         se = wave_sum(se);
         const float lse = m + logf(se);
         const int label = labels[i];
         float li = 0.f;
-        for (int k = lane; k < classes; k += 64) {
-            const float logp = z[k] - lse;
+        auto one = [&](int k, float zk) {
+            const float logp = zk - lse;
             const float q = (k == label ? 1.f - eps : 0.f) + q_off;
             li -= q * logp;
             dlogits[(size_t)i * classes + k] = (h16)((expf(logp) - q) * grad_scale);
+        };
+        if (cached) {
+#pragma unroll
+            for (int u = 0; u < kCache; ++u) {
+                const int k = lane + 64 * u;
+                if (k < classes) one(k, zc[u]);
+            }
+        } else {
+            for (int k = lane; k < classes; k += 64) one(k, z[k]);
         }
         li = wave_sum(li);
         if (loss_per_sample && lane == 0) loss_per_sample[i] = li;

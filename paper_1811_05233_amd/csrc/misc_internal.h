@@ -23,3 +23,5 @@ int rn50_bn_bwd_from_partials_launch(long long m, int c, const h16* g, const h16
                                      const float* save_mean, const float* save_invstd, h16* dx,
                                      float* dgamma32, float* dbeta32, const float* part, int ntiles, float* sums,
                                      hipStream_t s);
+int rn50_sgd_from_f32_launch(size_t n, const float* g32, h16* g16, float grad_scale, float* w, float* v, h16* w16,
+                             float lr, float mu, float wd, hipStream_t s);

@@ -99,7 +99,17 @@ __global__ __launch_bounds__(kThreads) void avgpool_fwd_kernel(int N, int HW, in
     if (i >= N * G) return;
     const int g = i % G, n = i / G;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int k = 0; k < HW; ++k) {
+    int k = 0;
+    for (; k + 7 <= HW; k += 7) {                       // 7 independent loads in flight
+        h16x8 v[7];
+#pragma unroll
+        for (int u = 0; u < 7; ++u) v[u] = *reinterpret_cast<const h16x8*>(x + ((size_t)n * HW + k + u) * C + g * 8);
+#pragma unroll
+        for (int u = 0; u < 7; ++u)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += (float)v[u][j];
+    }
+    for (; k < HW; ++k) {
         const h16x8 v = *reinterpret_cast<const h16x8*>(x + ((size_t)n * HW + k) * C + g * 8);
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] += (float)v[j];
@@ -110,26 +120,40 @@ __global__ __launch_bounds__(kThreads) void avgpool_fwd_kernel(int N, int HW, in
     *reinterpret_cast<h16x8*>(y + (size_t)i * 8) = o;
 }
 
-// z[i,j] = sum_c a[i,c]*Wt[j,c] + b[j]; one wavefront per output column j, the row of Wt stays
-// in registers while the wave walks the batch.  Cin must be a multiple of 8.
+// z[i,j] = sum_c a[i,c]*Wt[j,c] + b[j].  One wavefront per (output column j, group of 8 rows): the
+// lane's chunks of the weight row stay in registers, the 8 rows' loads are independent, and each dot
+// product is finished by a wavefront reduction.  Cin must be a multiple of 8.
+constexpr int kFcRows = 8;
 __global__ __launch_bounds__(kThreads) void fc_fwd_kernel(int B, int Cin, int Cout, const h16* __restrict__ a,
                                                           const h16* __restrict__ Wt, const float* __restrict__ bias,
                                                           float* __restrict__ z)
 {
     const int lane = threadIdx.x & 63;
-    const int j = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    if (j >= Cout) return;
+    const int row_groups = (B + kFcRows - 1) / kFcRows;
+    const int w = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (w >= Cout * row_groups) return;
+    const int j = w / row_groups, i0 = (w % row_groups) * kFcRows;
     const int chunks = Cin / 8;
-    for (int i = 0; i < B; ++i) {
-        float s = 0.f;
-        for (int c = lane; c < chunks; c += 64) {
-            const h16x8 wv = *reinterpret_cast<const h16x8*>(Wt + (size_t)j * Cin + c * 8);
-            const h16x8 av = *reinterpret_cast<const h16x8*>(a + (size_t)i * Cin + c * 8);
+    float acc[kFcRows];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s += (float)wv[e] * (float)av[e];
+    for (int r = 0; r < kFcRows; ++r) acc[r] = 0.f;
+    for (int c = lane; c < chunks; c += 64) {
+        const h16x8 wv = *reinterpret_cast<const h16x8*>(Wt + (size_t)j * Cin + c * 8);
+        h16x8 av[kFcRows];
+#pragma unroll
+        for (int r = 0; r < kFcRows; ++r) {
+            const int i = i0 + r < B ? i0 + r : B - 1;
+            av[r] = *reinterpret_cast<const h16x8*>(a + (size_t)i * Cin + c * 8);
         }
-        s = wave_sum(s);
-        if (lane == 0) z[(size_t)i * Cout + j] = s + bias[j];
+#pragma unroll
+        for (int r = 0; r < kFcRows; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[r] += (float)wv[e] * (float)av[r][e];
+    }
+#pragma unroll
+    for (int r = 0; r < kFcRows; ++r) {
+        const float s = wave_sum(acc[r]);
+        if (lane == 0 && i0 + r < B) z[(size_t)(i0 + r) * Cout + j] = s + bias[j];
     }
 }
 
@@ -158,40 +182,56 @@ __global__ __launch_bounds__(kThreads) void fc_bwd_w_kernel(int B, int Cin, int 
 }
 
 // da[i,c] = sum_j dz[i,j]*Wt[j,c] rounded to half, then spread over the HW positions of the
-// average pool: dx[i,hw,c] = half(da/HW).  Workgroup = (image i, slab of 32 channel groups);
-// 8 row-lanes split the classes and are combined through LDS in a fixed order.
+// average pool: dx[i,hw,c] = half(da/HW).  Workgroup = (image i, slab of 16 channel groups);
+// 16 row-lanes split the classes (4 independent loads in flight each) and are combined through LDS in
+// a fixed order.
 __global__ __launch_bounds__(kThreads) void fc_bwd_a_avgpool_bwd_kernel(int Cin, int Cout, int HW,
                                                                         const h16* __restrict__ Wt,
                                                                         const h16* __restrict__ dz,
                                                                         h16* __restrict__ dx)
 {
-    __shared__ float red[8][32][8];
+    __shared__ float red[16][16][8];
     const int G = Cin / 8;
-    const int slabs = (G + 31) / 32;
+    const int slabs = (G + 15) / 16;
     const int i = blockIdx.x / slabs, slab = blockIdx.x % slabs;
-    const int gl = threadIdx.x & 31, jl = threadIdx.x >> 5;
-    const int g = slab * 32 + gl;
+    const int gl = threadIdx.x & 15, jl = threadIdx.x >> 4;
+    const int g = slab * 16 + gl;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (g < G)
-        for (int j = jl; j < Cout; j += 8) {
+    if (g < G) {
+        int j = jl;
+        for (; j + 48 < Cout; j += 64) {
+            h16x8 wv[4];
+            float d[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                d[u] = (float)dz[(size_t)i * Cout + j + 16 * u];
+                wv[u] = *reinterpret_cast<const h16x8*>(Wt + (size_t)(j + 16 * u) * Cin + g * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += d[u] * (float)wv[u][e];
+        }
+        for (; j < Cout; j += 16) {
             const float d = (float)dz[(size_t)i * Cout + j];
             const h16x8 wv = *reinterpret_cast<const h16x8*>(Wt + (size_t)j * Cin + g * 8);
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[e] += d * (float)wv[e];
         }
+    }
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[jl][gl][e] = acc[e];
     __syncthreads();
-    if (jl == 0 && g < G) {
+    if (g < G) {
         h16x8 o;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             float s = 0.f;
-            for (int k = 0; k < 8; ++k) s += red[k][gl][e];
+            for (int k = 0; k < 16; ++k) s += red[k][gl][e];
             const h16 da = (h16)s;
             o[e] = (h16)((float)da / (float)HW);
         }
-        for (int k = 0; k < HW; ++k) *reinterpret_cast<h16x8*>(dx + ((size_t)i * HW + k) * Cin + g * 8) = o;
+        for (int k = jl; k < HW; k += 16) *reinterpret_cast<h16x8*>(dx + ((size_t)i * HW + k) * Cin + g * 8) = o;
     }
 }
 
@@ -229,7 +269,8 @@ int rn50_avgpool_fwd(int N, int HW, int C, const h16* x, h16* y, hipStream_t s)
 int rn50_fc_fwd(int B, int Cin, int Cout, const h16* a, const h16* Wt, const float* bias, float* z, hipStream_t s)
 {
     ProfScope ps(RN50_K_FC, 2.0 * B * Cin * Cout, 2.0 * Cin * (B + Cout) + 4.0 * B * Cout, s);
-    fc_fwd_kernel<<<rn50_cdiv(Cout, kThreads / 64), kThreads, 0, s>>>(B, Cin, Cout, a, Wt, bias, z);
+    fc_fwd_kernel<<<rn50_cdiv((long long)Cout * ((B + kFcRows - 1) / kFcRows), kThreads / 64), kThreads, 0, s>>>(B, Cin, Cout, a,
+                                                                                                                Wt, bias, z);
     return rn50_check_launch();
 }
 
@@ -238,7 +279,7 @@ int rn50_fc_bwd(int B, int Cin, int Cout, int HW, const h16* a, const h16* Wt, c
 {
     ProfScope ps(RN50_K_FC, 4.0 * B * Cin * Cout, 2.0 * Cin * (B + Cout) + 4.0 * Cin * Cout + 2.0 * B * Cin * HW, s);
     fc_bwd_w_kernel<<<rn50_cdiv((long long)Cout * (Cin / 8), kThreads), kThreads, 0, s>>>(B, Cin, Cout, a, dz, dWt, db);
-    const int slabs = (Cin / 8 + 31) / 32;
+    const int slabs = (Cin / 8 + 15) / 16;
     fc_bwd_a_avgpool_bwd_kernel<<<B * slabs, kThreads, 0, s>>>(Cin, Cout, HW, Wt, dz, dx);
     return rn50_check_launch();
 }

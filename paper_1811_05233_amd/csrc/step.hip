@@ -179,6 +179,7 @@ struct rn50_ctx {
     hipStream_t side = nullptr;
     std::vector<hipEvent_t> fork_events;   // one per conv layer: "d(conv output) is ready"
     hipEvent_t join_event = nullptr;
+    hipEvent_t transpose_fork = nullptr, transpose_done = nullptr;
     bool tuning = false;                   // rn50_autotune: every conv launch site times its variants
     hipEvent_t tune_e0 = nullptr, tune_e1 = nullptr;
     size_t max_act = 0, wt_elems = 0;
@@ -345,6 +346,8 @@ extern "C" int rn50_create(rn50_ctx** out, const rn50_config* cfg, void* workspa
     }
     hipError_t e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_event, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->transpose_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->transpose_done, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreate(&c->tune_e0);
     if (e == hipSuccess) e = hipEventCreate(&c->tune_e1);
     c->fork_events.assign(c->L.layers.size(), nullptr);
@@ -360,6 +363,8 @@ extern "C" void rn50_destroy(rn50_ctx* ctx)
     if (!ctx) return;
     for (hipEvent_t ev : ctx->fork_events) if (ev) (void)hipEventDestroy(ev);
     if (ctx->join_event) (void)hipEventDestroy(ctx->join_event);
+    if (ctx->transpose_fork) (void)hipEventDestroy(ctx->transpose_fork);
+    if (ctx->transpose_done) (void)hipEventDestroy(ctx->transpose_done);
     if (ctx->tune_e0) (void)hipEventDestroy(ctx->tune_e0);
     if (ctx->tune_e1) (void)hipEventDestroy(ctx->tune_e1);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
@@ -442,11 +447,19 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     const h16* w16 = static_cast<const h16*>(w_lowp);
     const int B = cfg.batch;
 
-    // ---- per-step preparation: re-lay the filters for the data gradient ----
+    // ---- per-step preparation: re-lay the filters for the data gradient.  Only the backward pass needs
+    // them, so this runs on the side stream next to the forward pass. ----
     if (c.njobs > 0) {
-        ProfScope ps(RN50_K_TRANSPOSE, 0.0, 4.0 * c.wt_elems, s);
-        transpose_all_kernel<<<c.transpose_blocks, kThreads, 0, s>>>(w16, c.wt_all, c.jobs, c.njobs);
-        RN50_TRY(rn50_check_launch());
+        hipError_t e = hipEventRecord(c.transpose_fork, s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(c.side, c.transpose_fork, 0);
+        if (e != hipSuccess) return rn50_hip_fail(e);
+        {
+            ProfScope ps(RN50_K_TRANSPOSE, 0.0, 4.0 * c.wt_elems, c.side);
+            transpose_all_kernel<<<c.transpose_blocks, kThreads, 0, c.side>>>(w16, c.wt_all, c.jobs, c.njobs);
+            RN50_TRY(rn50_check_launch());
+        }
+        e = hipEventRecord(c.transpose_done, c.side);
+        if (e != hipSuccess) return rn50_hip_fail(e);
     }
 
     // convolution (its epilogue also leaves the BatchNorm partial sums of every row tile), then BN
@@ -507,6 +520,10 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
                              nullptr, c.dlogits, RN50_F16, stream));
 
     // ================= backward =================
+    if (c.njobs > 0) {
+        hipError_t e = hipStreamWaitEvent(s, c.transpose_done, 0);
+        if (e != hipSuccess) return rn50_hip_fail(e);
+    }
     RN50_TRY(rn50_fc_bwd(B, L.feat, cfg.classes, HW, c.feat, w16 + L.fcw_off, c.dlogits, c.grad32 + L.fcw_off,
                          c.grad32 + L.fcb_off, c.head_din, s));
 
@@ -595,10 +612,10 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     }
 
     // ================= flat FP16 gradient, update =================
-    RN50_TRY(rn50_cast_f32_to_h16(c.grad32, static_cast<h16*>(grad_lowp), L.param_count, s));
     if (hp)
-        RN50_TRY(sgd_momentum_flat(L.param_count, grad_lowp, RN50_F16, hp->grad_scale, master_w, momentum, w_lowp,
-                                   hp->lr, hp->momentum, hp->wd, stream));
+        return rn50_sgd_from_f32_launch(L.param_count, c.grad32, static_cast<h16*>(grad_lowp), hp->grad_scale, master_w,
+                                        momentum, static_cast<h16*>(w_lowp), hp->lr, hp->momentum, hp->wd, s);
+    RN50_TRY(rn50_cast_f32_to_h16(c.grad32, static_cast<h16*>(grad_lowp), L.param_count, s));
     return RN50_OK;
 }
 
