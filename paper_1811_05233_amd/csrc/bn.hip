@@ -104,37 +104,92 @@ __global__ __launch_bounds__(kThreads) void bn_stats_kernel(long long m, int c, 
     }
 }
 
-__device__ __forceinline__ double wave_sum_f64(double v) {
+// Column sums of the partials matrix [nblk][2][c] and what follows from them.  A workgroup owns 16
+// channels (both sums): 8 lanes x 16 bytes cover one row's two 64-byte segments, the other lanes take
+// further rows, every thread keeps several rows in flight.  Row lanes are combined in a fixed order
+// (wave shuffles, then across waves in double), so the result does not depend on timing.
+//   kMode 0 (forward): partials are sum (x - pivot), sum (x - pivot)^2 -> mean, 1/sqrt(var + eps);
+//                      pivot_row: first row of x, or nullptr for pivot 0
+//   kMode 1 (backward): partials are sum g, sum g*xhat -> sums[0..c) = d beta, sums[c..2c) = d gamma, plus the
+//                      optional half / float copies
+template <int kMode, int kNT>
+__global__ __launch_bounds__(kNT) void bn_finalize_kernel(long long m, int c, float eps, int nblk,
+                                                          const h16* __restrict__ pivot_row,
+                                                          const float* __restrict__ part, float* __restrict__ out0,
+                                                          float* __restrict__ out1, h16* __restrict__ dgamma,
+                                                          h16* __restrict__ dbeta, float* __restrict__ dgamma32,
+                                                          float* __restrict__ dbeta32)
+{
+    constexpr int kRowLanes = kNT / 8, kWaves = kNT / 64, kBatch = 8;
+    __shared__ float red[kWaves][32];
+    __shared__ double fin[32];
+    const int tid = threadIdx.x;
+    const int cl = tid & 7, rl = tid >> 3;
+    const int which = cl >> 2, ch0 = blockIdx.x * 16 + (cl & 3) * 4;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (ch0 < c) {
+        const float* p = part + (size_t)which * c + ch0;
+        const size_t pitch = 2 * (size_t)c;
+        for (int r0 = rl; r0 < nblk; r0 += kRowLanes * kBatch) {
+            f32x4 v[kBatch];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+            for (int u = 0; u < kBatch; ++u) {
+                const int r = r0 + u * kRowLanes;
+                v[u] = r < nblk ? *reinterpret_cast<const f32x4*>(p + (size_t)r * pitch) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) acc += v[u];
+        }
+    }
+#pragma unroll
+    for (int o = 8; o < 64; o <<= 1)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] += __shfl_xor(acc[j], o, 64);
+    if ((tid & 63) < 8) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) red[tid >> 6][cl * 4 + j] = acc[j];
+    }
+    __syncthreads();
+    if (tid < 32) {
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) s += (double)red[w][tid];
+        fin[tid] = s;
+    }
+    __syncthreads();
+    const int ch = blockIdx.x * 16 + tid;
+    if (tid < 16 && ch < c) {
+        const double sa = fin[tid], sb = fin[16 + tid];
+        if (kMode == 0) {
+            const double pivot = pivot_row ? (double)(float)pivot_row[ch] : 0.0;
+            const double md = sa / (double)m;
+            double var = sb / (double)m - md * md;
+            if (var < 0.0) var = 0.0;
+            out0[ch] = (float)(pivot + md);
+            out1[ch] = (float)(1.0 / sqrt(var + (double)eps));
+        } else {
+            out0[ch] = (float)sa;
+            out0[c + ch] = (float)sb;
+            if (dbeta) dbeta[ch] = (h16)(float)sa;
+            if (dgamma) dgamma[ch] = (h16)(float)sb;
+            if (dbeta32) dbeta32[ch] = (float)sa;
+            if (dgamma32) dgamma32[ch] = (float)sb;
+        }
+    }
 }
 
-// One wavefront per channel: lanes stride over the partials, the 64 lane sums are combined in double.
-// pivot_row: first row of x (the pivot the partials were accumulated around) or nullptr for pivot 0.
-__global__ __launch_bounds__(kThreads) void bn_stats_finalize_kernel(long long m, int c, float eps, int nblk,
-                                                                     const h16* __restrict__ pivot_row,
-                                                                     const float* __restrict__ part,
-                                                                     float* __restrict__ save_mean,
-                                                                     float* __restrict__ save_invstd)
+// many partial rows: 1024 threads (128 row lanes), else 256
+template <int kMode>
+void launch_bn_finalize(long long m, int c, float eps, int nblk, const h16* pivot_row, const float* part, float* out0,
+                        float* out1, h16* dgamma, h16* dbeta, float* dgamma32, float* dbeta32, hipStream_t s)
 {
-    const int lane = threadIdx.x & 63;
-    const int ch = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    if (ch >= c) return;
-    float a = 0.f, b = 0.f;
-    for (int k = lane; k < nblk; k += 64) {
-        a += part[((size_t)k * 2) * c + ch];
-        b += part[((size_t)k * 2 + 1) * c + ch];
-    }
-    const double sa = wave_sum_f64((double)a), sb = wave_sum_f64((double)b);
-    if (lane == 0) {
-        const double pivot = pivot_row ? (double)(float)pivot_row[ch] : 0.0;
-        const double md = sa / (double)m;
-        double var = sb / (double)m - md * md;
-        if (var < 0.0) var = 0.0;
-        save_mean[ch] = (float)(pivot + md);
-        save_invstd[ch] = (float)(1.0 / sqrt(var + (double)eps));
-    }
+    const int grid = rn50_cdiv(c, 16);
+    if (nblk > 256)
+        bn_finalize_kernel<kMode, 1024><<<grid, 1024, 0, s>>>(m, c, eps, nblk, pivot_row, part, out0, out1, dgamma, dbeta,
+                                                             dgamma32, dbeta32);
+    else
+        bn_finalize_kernel<kMode, 256><<<grid, 256, 0, s>>>(m, c, eps, nblk, pivot_row, part, out0, out1, dgamma, dbeta,
+                                                           dgamma32, dbeta32);
 }
 
 // ------------------------------------------------------------------ forward apply
@@ -256,32 +311,6 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_kernel(long long m, in
             for (int j = 0; j < 8; ++j) { p0[j] = acc[j]; p0[c + j] = acc[8 + j]; }
         }
         if (rm.gp > rm.gpb) __syncthreads();
-    }
-}
-
-// sums[0..c) = dbeta, sums[c..2c) = dgamma (float, kept for the apply pass); also the half / float copies.
-__global__ __launch_bounds__(kThreads) void bn_bwd_finalize_kernel(int c, int nblk, const float* __restrict__ part,
-                                                                   float* __restrict__ sums,
-                                                                   h16* __restrict__ dgamma, h16* __restrict__ dbeta,
-                                                                   float* __restrict__ dgamma32,
-                                                                   float* __restrict__ dbeta32)
-{
-    const int lane = threadIdx.x & 63;
-    const int ch = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    if (ch >= c) return;
-    float a = 0.f, b = 0.f;
-    for (int k = lane; k < nblk; k += 64) {
-        a += part[((size_t)k * 2) * c + ch];
-        b += part[((size_t)k * 2 + 1) * c + ch];
-    }
-    const double sa = wave_sum_f64((double)a), sb = wave_sum_f64((double)b);
-    if (lane == 0) {
-        sums[ch] = (float)sa;
-        sums[c + ch] = (float)sb;
-        if (dbeta) dbeta[ch] = (h16)(float)sa;
-        if (dgamma) dgamma[ch] = (h16)(float)sb;
-        if (dbeta32) dbeta32[ch] = (float)sa;
-        if (dgamma32) dgamma32[ch] = (float)sb;
     }
 }
 
@@ -414,7 +443,7 @@ int rn50_bn_fwd_launch(long long m, int c, float eps, bool relu, const h16* x, c
     }
     {
         ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * p.nblk * c, s);
-        bn_stats_finalize_kernel<<<rn50_cdiv(c, kThreads / 64), kThreads, 0, s>>>(m, c, eps, p.nblk, x, ws, save_mean, save_invstd);
+        launch_bn_finalize<0>(m, c, eps, p.nblk, x, ws, save_mean, save_invstd, nullptr, nullptr, nullptr, nullptr, s);
     }
     ProfScope ps(RN50_K_BN_APPLY, 0.0, (res ? 6.0 : 4.0) * elems, s);
     const BnPlan pa = plan_rows_apply(m, c);
@@ -435,8 +464,7 @@ int rn50_bn_fwd_from_partials_launch(long long m, int c, float eps, bool relu, c
     const double elems = (double)m * c;
     {
         ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * ntiles * c, s);
-        bn_stats_finalize_kernel<<<rn50_cdiv(c, kThreads / 64), kThreads, 0, s>>>(m, c, eps, ntiles, nullptr, part,
-                                                                                 save_mean, save_invstd);
+        launch_bn_finalize<0>(m, c, eps, ntiles, nullptr, part, save_mean, save_invstd, nullptr, nullptr, nullptr, nullptr, s);
     }
     ProfScope ps(RN50_K_BN_APPLY, 0.0, (res ? 6.0 : 4.0) * elems, s);
     const BnPlan pa = plan_rows_apply(m, c);
@@ -462,7 +490,7 @@ int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* 
     }
     {
         ProfScope ps(RN50_K_BN_BWD_FINALIZE, 0.0, 8.0 * p.nblk * c, s);
-        bn_bwd_finalize_kernel<<<rn50_cdiv(c, kThreads / 64), kThreads, 0, s>>>(c, p.nblk, ws, sums, dgamma, dbeta, dgamma32, dbeta32);
+        launch_bn_finalize<1>(m, c, 0.f, p.nblk, nullptr, ws, sums, nullptr, dgamma, dbeta, dgamma32, dbeta32, s);
     }
     ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, ((relu ? 6.0 : 4.0) + 2.0 + (dres ? 2.0 : 0.0)) * elems, s);
     const BnPlan pa = plan_rows_apply(m, c);
@@ -484,8 +512,7 @@ int rn50_bn_bwd_from_partials_launch(long long m, int c, const h16* g, const h16
     const double elems = (double)m * c;
     {
         ProfScope ps(RN50_K_BN_BWD_FINALIZE, 0.0, 8.0 * ntiles * c, s);
-        bn_bwd_finalize_kernel<<<rn50_cdiv(c, kThreads / 64), kThreads, 0, s>>>(c, ntiles, part, sums, nullptr, nullptr,
-                                                                               dgamma32, dbeta32);
+        launch_bn_finalize<1>(m, c, 0.f, ntiles, nullptr, part, sums, nullptr, nullptr, nullptr, dgamma32, dbeta32, s);
     }
     ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, 6.0 * elems, s);
     const BnPlan pa = plan_rows_apply(m, c);

@@ -12,7 +12,7 @@
 //
 // The filter gradient reduces over pixels, which is the strided dimension of both operands; its
 // loader transposes 8x8 half blocks in registers on the way into LDS, after which the same MFMA
-// loop applies.  The pixel range is split over workgroups and combined with FP32 atomic adds.
+// loop applies.  The pixel range is split over workgroups; their partial tiles are added in a fixed order.
 #include "common.h"
 #include "conv_internal.h"
 #include "prof.h"
@@ -51,12 +51,6 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {
 #define RN50_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xc07f)
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
-#ifndef RN50_AUX_A
-#define RN50_AUX_A 0
-#endif
-#ifndef RN50_AUX_B
-#define RN50_AUX_B 0
-#endif
 
 // m = q*d + r with 0 <= r < d, for 0 <= m < 2^24, using the precomputed float reciprocal of d.
 __device__ __forceinline__ void fast_divmod(int m, int d, float inv_d, int& q, int& r) {
@@ -155,12 +149,12 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
             const int ih = a_h0[j] + dh, iw = a_w0[j] + dw;
             const bool ok = (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW;
             const unsigned voff = ok ? a_voff[j] + (unsigned)a_delta : kOutOfRange;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(sa + (wave + 4 * j) * 512), 16, (int)voff, 0, 0, RN50_AUX_A);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(sa + (wave + 4 * j) * 512), 16, (int)voff, 0, 0, 0);
         }
 #pragma unroll
         for (int j = 0; j < NB; ++j)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(sb + (wave + 4 * j) * 512), 16,
-                                                     (int)(b_voff[j] + b_delta), 0, 0, RN50_AUX_B);
+                                                     (int)(b_voff[j] + b_delta), 0, 0, 0);
         if (++ld_cc == KC) { ld_cc = 0; ++ld_ti; }
         if (++ld_stage == NST) ld_stage = 0;
     };
