@@ -76,7 +76,8 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     constexpr int KS = BK / 16;
     constexpr int STAGE = (BM + BN) * BK;
     constexpr int EP = BN + 8;             // epilogue row pitch in halfs
-    constexpr int LDS_HALFS = (NST * STAGE > BM * EP) ? NST * STAGE : BM * EP;
+    constexpr int EPI_HALFS = BM * EP + (kThreads / (BN / 8)) * 2 * BN * 2;   // staged tile + statistics scratch (floats)
+    constexpr int LDS_HALFS = (NST * STAGE > EPI_HALFS) ? NST * STAGE : EPI_HALFS;
     constexpr unsigned kOutOfRange = 0x80000000u;
     __shared__ __attribute__((aligned(16))) h16 lds[LDS_HALFS];
 
@@ -627,7 +628,7 @@ int launch_gather(GatherArgs& a, hipStream_t s, int kid, double flops, double by
 bool gather_tile_ok(const GatherArgs& a, int tile)
 {
     if (tile < 0 || tile >= RN50_NUM_GATHER_TILES) return false;
-    return tile != RN50_TILE_128x128 || a.NO % 128 == 0;
+    return (tile != RN50_TILE_128x128 && tile != RN50_TILE_128x128_SHORT) || a.NO % 128 == 0;
 }
 
 // default choice when no tuned tile is given: the large tile while it still yields about two workgroups
@@ -651,6 +652,10 @@ int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, in
         case RN50_TILE_128x64: return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_128x64, flops, bytes);
         case RN50_TILE_64x64_DEEP: return launch_gather<64, 64, 64, 4, 2>(a, s, RN50_K_GATHER_64x64, flops, bytes);
         case RN50_TILE_64x64_WIDE: return launch_gather<64, 64, 64, 2, 4>(a, s, RN50_K_GATHER_64x64, flops, bytes);
+        case RN50_TILE_128x64_SHORT: return launch_gather<128, 64, 32, 2, 4>(a, s, RN50_K_GATHER_128x64, flops, bytes);
+        case RN50_TILE_128x128_SHORT: return launch_gather<128, 128, 32, 2, 3>(a, s, RN50_K_GATHER_128x128, flops, bytes);
+        case RN50_TILE_256x64: return launch_gather<256, 64, 32, 3, 2>(a, s, RN50_K_GATHER_128x64, flops, bytes);
+        case RN50_TILE_128x64_K64: return launch_gather<128, 64, 64, 3, 2>(a, s, RN50_K_GATHER_128x64, flops, bytes);
         default: return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_64x64, flops, bytes);
     }
 }

@@ -11,6 +11,10 @@ enum {
     RN50_TILE_64x64_DEEP,      // 64x64, 64-wide slabs, 4 stages, 2 workgroups per compute unit
     RN50_TILE_64x64_WIDE,      // 64x64, 64-wide slabs, 2 stages, 4 workgroups per compute unit
     RN50_TILE_64x64_K32,       // 64x64, 32-wide slabs, 4 stages, 4 workgroups per compute unit
+    RN50_TILE_128x64_SHORT,    // 128x64, 32-wide slabs, 2 stages, 4 workgroups per compute unit (short reductions)
+    RN50_TILE_128x128_SHORT,   // 128x128, 32-wide slabs, 2 stages, 3 workgroups per compute unit
+    RN50_TILE_256x64,          // 256x64, 32-wide slabs, 3 stages
+    RN50_TILE_128x64_K64,      // 128x64, 64-wide slabs, 3 stages
     RN50_NUM_GATHER_TILES,
     RN50_NUM_WGRAD_VARIANTS = 6
 };

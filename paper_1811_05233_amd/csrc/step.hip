@@ -1,6 +1,8 @@
 // Whole-iteration driver: walks the ResNet-50 v1.5 layer table and enqueues forward, loss,
 // backward and the momentum-SGD update on one stream, with no host synchronisation.
 // The context is a host object; every device byte lives in the caller's workspace.
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -409,9 +411,10 @@ namespace {
 // (one warm-up, two timed launches, device-synchronous) on stream s, stores the fastest in *choice and
 // leaves its (identical) result in place.
 template <class F>
-int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch)
+int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch, const char* what = "", const char* layer = "")
 {
     if (!c.tuning) return launch(*choice);
+    static const bool log = getenv("RN50_TUNE_LOG") != nullptr;     // per-candidate times on stderr
     float best_ms = 1e30f;
     int best = RN50_TILE_AUTO;
     for (int cand = 0; cand < ncand; ++cand) {
@@ -426,7 +429,9 @@ int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch)
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, c.tune_e0, c.tune_e1);
         if (e != hipSuccess) return rn50_hip_fail(e);
         if (ms < best_ms) { best_ms = ms; best = cand; }
+        if (log) fprintf(stderr, "tune %s %s cand %d: %.1f us\n", layer, what, cand, ms * 500.f);
     }
+    if (log) fprintf(stderr, "tune %s %s -> %d (%.1f us)\n", layer, what, best, best_ms * 500.f);
     *choice = best;
     return launch(best);
 }
@@ -468,7 +473,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         int tiles = 0;
         RN50_TRY(launch_or_tune(c, st, l.d.c == 3 ? 1 : RN50_NUM_GATHER_TILES, &l.fwd_tile, [&](int tile) {
             return rn50_conv_fwd_launch(l.d, x, wts, l.conv_out, st, part, &tiles, tile);
-        }));
+        }, "fwd", l.name.c_str()));
         return rn50_bn_fwd_from_partials_launch((long long)l.d.n * l.P * l.Q, l.d.k, cfg.bn_eps, relu, l.conv_out,
                                                 master_w + l.gamma_off, master_w + l.beta_off, residual, l.bn_out,
                                                 l.mean, l.invstd, part, tiles, st);
@@ -536,7 +541,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         if (e != hipSuccess) return rn50_hip_fail(e);
         return launch_or_tune(c, c.side, l.d.c == 3 ? 3 : RN50_NUM_WGRAD_VARIANTS, &l.wgrad_variant, [&](int variant) {
             return rn50_conv_wgrad_launch(l.d, in, l.dconv, out, c.wgrad_part, c.side, variant);
-        });
+        }, "wgrad", l.name.c_str());
     };
     // BN backward, stand-alone form (reduce, finalize, apply): dy -> l.dconv (and dres)
     auto bn_bwd_std = [&](ConvLayer& l, const h16* dy, bool relu, h16* dres) -> int {
@@ -562,7 +567,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         return launch_or_tune(c, s, RN50_NUM_GATHER_TILES, &l.dgrad_tile, [&](int tile) {
             return rn50_conv_dgrad_launch(l.d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s, prev ? &f : nullptr,
                                           prev ? &fused_tiles : nullptr, tile);
-        });
+        }, "dgrad", l.name.c_str());
     };
 
     const h16* dY = c.head_din;
