@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--cpu-sample-batch", type=int, default=4, help="0 disables the cpu_baseline leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-autotune", action="store_true", help="use the built-in tile heuristics")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three plain 256 MiB device copies (a kernel of known traffic, to calibrate "
+                         "hardware byte counters against)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the gradient all-reduce is out of scope); "
@@ -100,6 +103,14 @@ def main():
     if not np.isfinite(loss_val):
         raise RuntimeError("loss is not finite after the timed steps")
 
+    if args.copy_probe:
+        src = torch.zeros(128 << 20, dtype=torch.float16, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     kernels, roof = [], None
     if not args.no_profile:
         P.rn50_profile_begin()
@@ -127,10 +138,12 @@ def main():
                     "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
                     "avg_launch_us": round(1e3 * dom["total_ms"] / dom["launches"], 2),
                     "launches_per_step": dom["launches"] / args.steps}
-        conv = [e for e in prof if e["flops"] > 0 and ("gather" in e["name"] or "wgrad" in e["name"])]
+        # all convolution kernels together: MFMA rate while they run, and over the whole step
+        conv = [e for e in prof if e["flops"] > 0 and ("gather" in e["name"] or "wgrad_kernel" in e["name"])]
         conv_fl = sum(e["flops"] for e in conv)
         conv_ms = sum(e["total_ms"] for e in conv)
         roof["conv_mfma_util_pct"] = round(100.0 * conv_fl / (conv_ms * 1e-3) / 1e12 / PEAK_FP16_TFLOPS, 2)
+        roof["conv_tflops_whole_step"] = round(conv_fl / args.steps / (ms * 1e-3) / 1e12, 1)
         sgd = [e for e in prof if e["name"].startswith("sgd")]
         if sgd:
             roof["sgd_hbm_frac"] = round(sgd[0]["bytes"] / (sgd[0]["total_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)

@@ -350,7 +350,7 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradArgs a)
     const int wm0 = (wave / WC) * WM, wn0 = (wave % WC) * WN;
 
     const int m_tiles = a.K / BM, n_tiles = a.NG * G / BN;
-    int bid = blockIdx.x;
+    int bid = xcd_remap(blockIdx.x, gridDim.x);   // the tiles of one pixel range share the range's dy / x rows: same L2
     const int nt = bid % n_tiles; bid /= n_tiles;
     const int mt = bid % m_tiles;
     const int split = bid / m_tiles;
@@ -647,16 +647,18 @@ int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, in
     if (a.CR == 32)                 // stem forward
         return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
     if (!gather_tile_ok(a, tile)) tile = gather_tile_heuristic(a);
+    static_assert(RN50_K_GATHER_TILE_LAST - RN50_K_GATHER_TILE0 + 1 == RN50_NUM_GATHER_TILES, "one profile id per tile variant");
+    const int kid = RN50_K_GATHER_TILE0 + tile;
     switch (tile) {
-        case RN50_TILE_128x128: return launch_gather<128, 128, 32, 4, 2>(a, s, RN50_K_GATHER_128x128, flops, bytes);
-        case RN50_TILE_128x64: return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_128x64, flops, bytes);
-        case RN50_TILE_64x64_DEEP: return launch_gather<64, 64, 64, 4, 2>(a, s, RN50_K_GATHER_64x64, flops, bytes);
-        case RN50_TILE_64x64_WIDE: return launch_gather<64, 64, 64, 2, 4>(a, s, RN50_K_GATHER_64x64, flops, bytes);
-        case RN50_TILE_128x64_SHORT: return launch_gather<128, 64, 32, 2, 4>(a, s, RN50_K_GATHER_128x64, flops, bytes);
-        case RN50_TILE_128x128_SHORT: return launch_gather<128, 128, 32, 2, 3>(a, s, RN50_K_GATHER_128x128, flops, bytes);
-        case RN50_TILE_256x64: return launch_gather<256, 64, 32, 3, 2>(a, s, RN50_K_GATHER_128x64, flops, bytes);
-        case RN50_TILE_128x64_K64: return launch_gather<128, 64, 64, 3, 2>(a, s, RN50_K_GATHER_128x64, flops, bytes);
-        default: return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_64x64, flops, bytes);
+        case RN50_TILE_128x128: return launch_gather<128, 128, 32, 4, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_128x64: return launch_gather<128, 64, 32, 4, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_64x64_DEEP: return launch_gather<64, 64, 64, 4, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_64x64_WIDE: return launch_gather<64, 64, 64, 2, 4>(a, s, kid, flops, bytes);
+        case RN50_TILE_128x64_SHORT: return launch_gather<128, 64, 32, 2, 4>(a, s, kid, flops, bytes);
+        case RN50_TILE_128x128_SHORT: return launch_gather<128, 128, 32, 2, 3>(a, s, kid, flops, bytes);
+        case RN50_TILE_256x64: return launch_gather<256, 64, 32, 3, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_128x64_K64: return launch_gather<128, 64, 64, 3, 2>(a, s, kid, flops, bytes);
+        default: tile = RN50_TILE_64x64_K32; return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_TILE0 + tile, flops, bytes);
     }
 }
 

@@ -4,9 +4,8 @@
 #include "common.h"
 
 enum Rn50Kernel {
-    RN50_K_GATHER_128x128 = 0,      // conv forward / data gradient, 128x128 tile
-    RN50_K_GATHER_128x64,           // conv forward / data gradient, 128x64 tile
-    RN50_K_GATHER_64x64,            // conv forward / data gradient, 64x64 tiles
+    RN50_K_GATHER_TILE0 = 0,        // conv forward / data gradient: one id per tile variant (RN50_TILE_* order)
+    RN50_K_GATHER_TILE_LAST = 8,
     RN50_K_GATHER_STEM,             // stem forward (128x64 tile, 32-wide K slabs)
     RN50_K_WGRAD_128x128,
     RN50_K_WGRAD_64x64,
