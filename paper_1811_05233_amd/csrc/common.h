@@ -41,3 +41,12 @@ __device__ __forceinline__ float wave_max(float v) {
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
     return v;
 }
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  This maps the hardware index
+// to a logical one such that every XCD gets a contiguous range of logical indices, so that neighbouring
+// tiles, which share operands, share an L2.
+__device__ __forceinline__ int rn50_xcd_remap(int bid, int nblk) {
+    const int full = nblk & ~7;
+    if (bid >= full) return bid;
+    return (bid & 7) * (full >> 3) + (bid >> 3);
+}

@@ -21,14 +21,6 @@ namespace {
 
 constexpr int kThreads = 256;
 
-__device__ __forceinline__ int xcd_remap(int bid, int nblk) {
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give each XCD a
-    // contiguous range of logical tiles so that tiles sharing operands share an L2.
-    const int full = nblk & ~7;
-    if (bid >= full) return bid;
-    return (bid & 7) * (full >> 3) + (bid >> 3);
-}
-
 // LDS tile of ROWS rows x KW halfs (KW = 32, 64 or 128), addressed in 16-byte chunks with an XOR
 // swizzle that keeps both the row-wise MFMA operand reads and the transposing writes conflict-free.
 template <int KW>
@@ -87,7 +79,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     const int wm0 = (wave / WC) * WM, wn0 = (wave % WC) * WN;
 
     // ---- which tile ----
-    const int bid = xcd_remap(blockIdx.x, gridDim.x);
+    const int bid = rn50_xcd_remap(blockIdx.x, gridDim.x);
     const int n_tiles = a.NO / BN;
     const int nt = bid % n_tiles;
     int mt = bid / n_tiles;
@@ -350,7 +342,7 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradArgs a)
     const int wm0 = (wave / WC) * WM, wn0 = (wave % WC) * WN;
 
     const int m_tiles = a.K / BM, n_tiles = a.NG * G / BN;
-    int bid = xcd_remap(blockIdx.x, gridDim.x);   // the tiles of one pixel range share the range's dy / x rows: same L2
+    int bid = rn50_xcd_remap(blockIdx.x, gridDim.x);   // the tiles of one pixel range share the range's dy / x rows: same L2
     const int nt = bid % n_tiles; bid /= n_tiles;
     const int mt = bid % m_tiles;
     const int split = bid / m_tiles;
