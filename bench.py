@@ -10,6 +10,13 @@ Prints ONE JSON line: images/s, the roofline figures of the kernel that takes th
 of the step (HIP-event timing of every launch, collected in a second pass of the same K steps so
 that the events do not perturb the throughput figure), the per-kernel breakdown, and the CPU
 oracle timed on a bounded sample.
+
+Other workloads (each prints one JSON line of its own; the default is the full step):
+  --mode conv-sweep   the 23 distinct ResNet-50 convolution shapes at batch 32 through conv_fwd /
+                      conv_dgrad / conv_wgrad, per shape: microseconds, TFLOP/s, fraction of its own
+                      roofline min(MFMA peak, arithmetic intensity x HBM peak)
+  --mode batch-sweep  the full step at 16, 32, 64 and 128 images per GPU
+  --mode tail         the update alone on the flat 25,557,032-element buffer, 100 steps
 """
 import argparse
 import json
@@ -44,8 +51,130 @@ def cpu_baseline(sample_batch):
                       "storage rounding, %.1f s" % (sample_batch, dt)}
 
 
+# (cin, cout, r, stride, pad, hin, layers with this shape): the 23 distinct convolution shapes of ResNet-50 v1.5
+CONV_SHAPES = [
+    (3, 64, 7, 2, 3, 224, 1), (64, 64, 1, 1, 0, 56, 1), (64, 64, 3, 1, 1, 56, 3), (64, 256, 1, 1, 0, 56, 4),
+    (256, 64, 1, 1, 0, 56, 2), (256, 128, 1, 1, 0, 56, 1), (128, 128, 3, 2, 1, 56, 1), (128, 512, 1, 1, 0, 28, 4),
+    (256, 512, 1, 2, 0, 56, 1), (512, 128, 1, 1, 0, 28, 3), (128, 128, 3, 1, 1, 28, 3), (512, 256, 1, 1, 0, 28, 1),
+    (256, 256, 3, 2, 1, 28, 1), (256, 1024, 1, 1, 0, 14, 6), (512, 1024, 1, 2, 0, 28, 1), (1024, 256, 1, 1, 0, 14, 5),
+    (256, 256, 3, 1, 1, 14, 5), (1024, 512, 1, 1, 0, 14, 1), (512, 512, 3, 2, 1, 14, 1), (512, 2048, 1, 1, 0, 7, 3),
+    (1024, 2048, 1, 2, 0, 14, 1), (2048, 512, 1, 1, 0, 7, 2), (512, 512, 3, 1, 1, 7, 2)]
+
+
+def conv_sweep(args):
+    """Every convolution shape on its own through the C ABI (built-in tile heuristics), each launch timed by
+    the library's HIP-event pairs on the launch stream; operands are re-used between launches (warm)."""
+    import torch
+    import paper_1811_05233_amd as P
+    from paper_1811_05233_amd import synth
+    dev, B, reps = "cuda:0", args.batch, max(args.steps, 5)
+    rows, tot = [], {"fwd": [0.0, 0.0], "dgrad": [0.0, 0.0], "wgrad": [0.0, 0.0]}
+    for i, (cin, cout, r, stride, pad, hin, cnt) in enumerate(CONV_SHAPES):
+        d = P.make_conv_desc(B, hin, hin, cin, cout, r, r, stride, pad)
+        p = (hin + 2 * pad - r) // stride + 1
+        x = torch.from_numpy(synth.normal_f16(100 + i, (B, hin, hin, cin))).to(dev)
+        w = torch.from_numpy(synth.he_normal_f16(130 + i, (cout, r, r, cin), cin * r * r)).to(dev)
+        dy = torch.from_numpy(synth.normal_f16(160 + i, (B, p, p, cout))).to(dev)
+        y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w)
+        ws = [torch.empty(max(P.conv_workspace_bytes(d, k), 16), dtype=torch.uint8, device=dev) for k in range(3)]
+        flops = 2.0 * B * p * p * cout * r * r * cin
+        inp = B * p * p * cin if (r == 1 and stride > 1) else B * hin * hin * cin
+        nbytes = 2.0 * (inp + cout * r * r * cin + B * p * p * cout)
+        floor_us = max(flops / (PEAK_FP16_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)) * 1e6
+        row = {"shape": "%d>%d %dx%d/%d @%d" % (cin, cout, r, r, stride, hin), "layers": cnt,
+               "gflop": round(flops / 1e9, 3), "mbytes": round(nbytes / 1e6, 1), "roofline_us": round(floor_us, 2)}
+        for kind, fn in (("fwd", lambda: P.conv_fwd(d, x, w, y, ws[0])), ("dgrad", lambda: P.conv_dgrad(d, dy, w, dx, ws[1])),
+                         ("wgrad", lambda: P.conv_wgrad(d, x, dy, dw, ws[2]))):
+            if kind == "dgrad" and cin == 3:
+                continue
+            for _ in range(3):
+                fn()
+            P.rn50_profile_begin()
+            for _ in range(reps):
+                fn()
+            prof = P.rn50_profile_end()       # everything the entry point launches (filter transpose, partial-tile sum, ...)
+            us = 1e3 * sum(e["total_ms"] for e in prof) / reps
+            row[kind] = {"us": round(us, 1), "tflops": round(flops / us / 1e6, 1), "roofline_frac": round(floor_us / us, 3)}
+            tot[kind][0] += us * cnt
+            tot[kind][1] += flops * cnt
+        rows.append(row)
+    summary = {k: {"us_all_layers": round(v[0], 1), "tflops": round(v[1] / v[0] / 1e6, 1),
+                   "mfma_util_pct": round(100.0 * v[1] / v[0] / 1e6 / PEAK_FP16_TFLOPS, 2)} for k, v in tot.items()}
+    print(json.dumps({"metric": "conv kernel sweep, ResNet-50 v1.5 shapes @ batch %d" % B, "unit": "TFLOP/s",
+                      "value": summary["fwd"]["tflops"], "n_gpus": 1, "dtype": "f16 storage, f32 accumulate",
+                      "data": "synthetic", "config": {"workload": "23 distinct conv shapes (53 layers), fwd / dgrad / wgrad "
+                      "timed separately, warm operands, built-in tile heuristics"}, "summary": summary, "shapes": rows}))
+
+
+def batch_sweep(args):
+    import torch
+    import paper_1811_05233_amd as P
+    from paper_1811_05233_amd import synth
+    dev, loss_scale, res = "cuda:0", 1024.0, []
+    for B in (16, 32, 64, 128):
+        cfg = P.make_config(B, loss_scale=loss_scale)
+        lay, n = P.rn50_param_layout(cfg), P.rn50_param_count(cfg)
+        w = torch.from_numpy(synth.flat_params(300 + B, lay)).to(dev)
+        v = torch.zeros(n, dtype=torch.float32, device=dev)
+        w16 = torch.empty(n, dtype=torch.float16, device=dev)
+        g16 = torch.empty(n, dtype=torch.float16, device=dev)
+        x = torch.from_numpy(synth.normal_f16(301 + B, (B, 224, 224, 3))).to(torch.float16).to(dev)
+        lab = torch.from_numpy(synth.labels(302 + B, B)).to(dev)
+        loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        ctx = P.Rn50Context(cfg, dev)
+        P.rn50_cast_params(n, w, w16)
+        hp = P.rn50_hparams(0.1, 0.9, 1e-4, 1.0 / loss_scale)
+        if not args.no_autotune:
+            ctx.autotune(x, lab, w, w16, g16, loss)
+        for _ in range(args.warmup):
+            ctx.step(x, lab, w, v, w16, g16, hp, loss)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            ctx.step(x, lab, w, v, w16, g16, hp, loss)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        res.append({"batch": B, "images_per_s": round(B * args.steps / dt, 1), "ms_per_step": round(dt * 1e3 / args.steps, 4),
+                    "loss": round(float(loss.item()), 5)})
+        ctx.close()
+        del ctx, w, v, w16, g16, x
+    print(json.dumps({"metric": "images/sec per MI355X, ResNet-50 fwd+bwd+SGD, per-GPU batch 16/32/64/128", "unit": "images/s",
+                      "value": [r["images_per_s"] for r in res], "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                      "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
+                      "config": {"workload": "full ResNet-50 v1.5 training step at the batch-size-control sizes"}, "batches": res}))
+
+
+def tail(args):
+    import torch
+    import paper_1811_05233_amd as P
+    from paper_1811_05233_amd import synth
+    dev, n, steps = "cuda:0", 25557032, 100
+    g = torch.from_numpy((synth.normal_f32(400, (n,)) * 1e-3).astype("float16")).to(dev)
+    w = torch.from_numpy(synth.normal_f32(401, (n,)) * 0.05).to(dev)
+    v = torch.zeros(n, dtype=torch.float32, device=dev)
+    w16 = torch.empty(n, dtype=torch.float16, device=dev)
+    for _ in range(3):
+        P.sgd_momentum_flat(n, g, 1.0 / 54000.0, w, v, w16, 0.1, 0.9, 1e-4)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        P.sgd_momentum_flat(n, g, 1.0 / 54000.0, w, v, w16, 0.1, 0.9, 1e-4)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / steps
+    gbs = 20.0 * n / us / 1e3
+    print(json.dumps({"metric": "momentum-SGD update of the flat 25,557,032-parameter buffer", "unit": "GB/s", "value": round(gbs, 1),
+                      "n_gpus": 1, "steps": steps, "us_per_step": round(us, 2), "dtype": "f32 (f16 gradient in, f16 weight copy out)",
+                      "data": "synthetic", "config": {"workload": "g ~ N(0,1e-3^2) f16, w ~ N(0,0.05^2), v=0, grad_scale 1/54000, "
+                      "lr 0.1, momentum 0.9, wd 1e-4, 100 steps on the same gradient"},
+                      "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                   "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None, "bytes_per_parameter": 20}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--mode", choices=["step", "conv-sweep", "batch-sweep", "tail"], default="step")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
@@ -61,6 +190,9 @@ def main():
         print("bench.py: this build runs on ONE GPU only (the gradient all-reduce is out of scope); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+
+    if args.mode != "step":
+        return {"conv-sweep": conv_sweep, "batch-sweep": batch_sweep, "tail": tail}[args.mode](args)
 
     import numpy as np
     import torch

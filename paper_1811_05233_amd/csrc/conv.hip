@@ -164,12 +164,18 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
         for (int tm = 0; tm < TM; ++tm) {
             const int m = mt * BM + wm0 + tm * 32 + li;
             size_t opix = 0;
-            const bool ok = m < M;
+            bool ok = m < M;
             if (ok) {
                 int t, wq, n, hq;
                 fast_divmod(m, OWs, inv_ow, t, wq);
                 fast_divmod(t, OHs, inv_oh, n, hq);
-                opix = ((size_t)n * a.OH + hq * a.o_mul + a.oph[cls]) * a.OW + wq * a.o_mul + a.opw[cls];
+                const int oh = hq * a.o_mul + a.oph[cls], ow = wq * a.o_mul + a.opw[cls];
+                if (a.add_sub) {
+                    ok = ((oh | ow) & 1) == 0;
+                    opix = ((size_t)n * a.add_h + (oh >> 1)) * a.add_w + (ow >> 1);
+                } else {
+                    opix = ((size_t)n * a.OH + oh) * a.OW + ow;
+                }
             }
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
@@ -766,7 +772,7 @@ int rn50_conv_fwd_launch(const conv_desc& d, const h16* x, const h16* w, h16* y,
 
 // Data gradient.  wt is the filter transposed to [C][R][S][K].  addend (nullable) has dx's layout.
 int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s,
-                           const DgradBnFuse* fuse, int* tiles_out, int tile)
+                           const DgradBnFuse* fuse, int* tiles_out, int tile, bool addend_even_only)
 {
     GatherArgs a = {};
     if (fuse) {
@@ -775,6 +781,7 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
     }
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     a.A = dy; a.B = wt; a.out = dx; a.addend = addend;
+    a.add_sub = (addend && addend_even_only) ? 1 : 0; a.add_h = (d.h + 1) / 2; a.add_w = (d.w + 1) / 2;
     a.a_bytes = (unsigned)((size_t)d.n * P * Q * d.k * sizeof(h16));
     a.b_bytes = (unsigned)((size_t)d.k * d.r * d.s * d.c * sizeof(h16));
     a.NB = d.n; a.IH = P; a.IW = Q; a.lda = d.k; a.CR = d.k; a.T = d.r * d.s; a.NO = d.c;

@@ -23,7 +23,9 @@ struct GatherArgs {
     const h16* A;        // gathered NHWC tensor
     const h16* B;        // [NO][T][CR]
     h16* out;            // NHWC output, NO channels
-    const h16* addend;   // nullable, same layout as out
+    const h16* addend;   // nullable, same layout as out (or, with add_sub, the compact form below)
+    int add_sub;         // 1: addend holds only out's even pixels, [NB][add_h][add_w][NO]; odd pixels add nothing
+    int add_h, add_w;
     float* stats_part;   // nullable: per row tile, two per-channel sums of the stored output, [tile][2][NO]
     const h16* mask_y;   // nullable (data gradient): zero the output where this tensor (out's layout) is <= 0
     const h16* bn_x;     // nullable (data gradient): input of the BN that produced mask_y; switches the sums
@@ -88,8 +90,10 @@ struct DgradBnFuse {
     const float* invstd;
     float* part;           // [row tile][sum g | sum g*xhat][channels], rn50_dgrad_stats_floats(d) floats
 };
+// addend (nullable) has dx's layout, or with addend_even_only its (even row, even column) pixels only,
+// [n][ceil(h/2)][ceil(w/2)][c] (the data gradient of a strided 1x1 convolution is zero elsewhere).
 int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, const h16* addend, h16* dx, hipStream_t s,
-                           const DgradBnFuse* fuse, int* tiles_out, int tile);
+                           const DgradBnFuse* fuse, int* tiles_out, int tile, bool addend_even_only = false);
 size_t rn50_dgrad_stats_floats(const conv_desc& d);
 size_t rn50_wgrad_acc_floats(const conv_desc& d);
 size_t rn50_wgrad_partial_floats(const conv_desc& d);

@@ -31,6 +31,8 @@ struct ConvLayer {
     float* invstd = nullptr;
     h16* dconv = nullptr;                // gradient w.r.t. the conv output (BN backward result)
     h16* din = nullptr;                  // gradient w.r.t. the conv input (data-gradient result)
+    bool din_compact = false;            // strided 1x1 (projection): din holds the (even, even) input pixels only,
+                                         //   [n][P][Q][c]; the gradient is zero at all other pixels
     h16* dres = nullptr;                 // conv3 only: masked gradient handed to the shortcut
     // kernel variants (RN50_TILE_AUTO until rn50_autotune has measured them)
     int fwd_tile = RN50_TILE_AUTO, dgrad_tile = RN50_TILE_AUTO, wgrad_variant = RN50_TILE_AUTO;
@@ -108,6 +110,7 @@ bool build_layout(const rn50_config& c, Layout& L)
             const int h2 = L.layers[blk.c2].P, w2 = L.layers[blk.c2].Q;
             blk.c3 = add_conv(nm + "c3", h2, w2, width, cout, 1, 1, 0);
             blk.proj = (b == 0) ? add_conv(nm + "p", h, w, cin, cout, 1, stride, 0) : -1;
+            if (blk.proj >= 0 && stride == 2) L.layers[blk.proj].din_compact = true;
             L.blocks.push_back(blk);
             h = h2; w = w2; cin = cout;
         }
@@ -399,7 +402,8 @@ extern "C" int rn50_tensor(rn50_ctx* ctx, const char* name, void** ptr, size_t* 
         if (what == "invstd") return set(l.invstd, (size_t)l.d.k, 4);
         if (cfg.keep_grads) {
             if (what == "dconv") return set(l.dconv, l.out_elems(), 2);
-            if (what == "din" && l.d.c != 3) return set(l.din, l.in_elems(), 2);
+            if (what == "din" && l.d.c != 3)
+                return set(l.din, l.din_compact ? (size_t)l.d.n * l.P * l.Q * l.d.c : l.in_elems(), 2);
             if (what == "dres" && l.dres) return set(l.dres, l.out_elems(), 2);
         }
     }
@@ -561,12 +565,17 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     };
     // data gradient of conv l into l.din.  prev (nullable) = the layer whose BN+ReLU output `in` is l's input:
     // then the result is masked by in > 0 and the BN-backward sums of prev are formed in the epilogue.
-    auto dgrad = [&](ConvLayer& l, const h16* addend, ConvLayer* prev, const h16* in) -> int {
+    // `compact_addend`: addend holds only the (even, even) pixels (see ConvLayer::din_compact).
+    auto dgrad = [&](ConvLayer& l, const h16* addend, ConvLayer* prev, const h16* in, bool compact_addend = false) -> int {
         DgradBnFuse f = {in, prev ? prev->conv_out : nullptr, prev ? prev->mean : nullptr,
                          prev ? prev->invstd : nullptr, c.bn_ws};
+        // a strided 1x1 convolution only reaches the (even, even) input pixels: its data gradient is the
+        // stride-1 data gradient on the output grid, stored compactly
+        conv_desc d = l.d;
+        if (l.din_compact) { d.h = l.P; d.w = l.Q; d.stride = 1; }
         return launch_or_tune(c, s, RN50_NUM_GATHER_TILES, &l.dgrad_tile, [&](int tile) {
-            return rn50_conv_dgrad_launch(l.d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s, prev ? &f : nullptr,
-                                          prev ? &fused_tiles : nullptr, tile);
+            return rn50_conv_dgrad_launch(d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s, prev ? &f : nullptr,
+                                          prev ? &fused_tiles : nullptr, tile, compact_addend);
         }, "dgrad", l.name.c_str());
     };
 
@@ -593,7 +602,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
             RN50_TRY(fork_wgrad(lp, block_in[bi], c.grad32 + lp.w_off));
             if (need_in) {
                 RN50_TRY(dgrad(lp, nullptr, nullptr, nullptr));
-                RN50_TRY(dgrad(l1, lp.din, below, block_in[bi]));     // main path + projection shortcut
+                RN50_TRY(dgrad(l1, lp.din, below, block_in[bi], lp.din_compact));   // main path + projection shortcut
             }
         } else {
             RN50_TRY(dgrad(l1, gres, below, block_in[bi]));           // main path + identity shortcut
