@@ -31,6 +31,21 @@ PEAK_FP16_TFLOPS = 2500.0     # MI355X dense FP16 MFMA peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 
 
+def measured_traffic(kernel_name):
+    """HBM-side bytes per launch of a kernel from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE, calibrated against a plain copy), or None if the summary does not list the kernel."""
+    path = os.path.join(ROOT, "profiles", "rn50_step_batch32_hbm_traffic.txt")
+    key = kernel_name.replace(" ", "")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 4 and "".join(parts[:-3]).replace(" ", "") == key:
+                return int((float(parts[-2]) + float(parts[-1])) * 1024)
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(sample_batch):
     """The CPU oracle as it stands (FP32 instantiation, storage rounding on), one full ResNet-50
     training step at a small batch; images/s = batch / seconds."""
@@ -271,6 +286,16 @@ def main():
                     "avg_launch_us": round(1e3 * dom["total_ms"] / dom["launches"], 2),
                     "launches_per_step": dom["launches"] / args.steps}
         # all convolution kernels together: MFMA rate while they run, and over the whole step
+        roof["traffic"] = measured_traffic(dom["name"])
+        roof["algorithmic_bytes_per_launch"] = int(dom["bytes"] / dom["launches"])
+        # what an event pair reads around an (almost) empty launch: the dispatch latency that avg_launch_us includes
+        # and that a profiler's begin/end timestamps of the kernel do not
+        tiny = torch.empty(8, dtype=torch.float16, device=dev)
+        P.rn50_profile_begin()
+        for _ in range(50):
+            P.rn50_cast_params(8, w, tiny)
+        floor = P.rn50_profile_end()
+        roof["event_floor_us"] = round(1e3 * floor[0]["total_ms"] / floor[0]["launches"], 2)
         conv = [e for e in prof if e["flops"] > 0 and ("gather" in e["name"] or "wgrad_kernel" in e["name"])]
         conv_fl = sum(e["flops"] for e in conv)
         conv_ms = sum(e["total_ms"] for e in conv)
