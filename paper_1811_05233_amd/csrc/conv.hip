@@ -878,6 +878,13 @@ size_t rn50_wgrad_partial_floats(const conv_desc& d)
     return most;
 }
 
+// bytes of partial tiles that variant `variant` writes (and the sum kernel reads back); 0 without a pixel split
+size_t rn50_wgrad_variant_partial_bytes(const conv_desc& d, int variant)
+{
+    const WgradPlan p = wgrad_plan(d, variant);
+    return p.nsplit > 1 ? (size_t)p.nsplit * rn50_wgrad_acc_floats(d) * sizeof(float) : 0;
+}
+
 // Filter gradient in FP32 into out (layout [K][R][S][C]; stem: [K][8][32]); every element is written.
 // partials: scratch of rn50_wgrad_partial_floats(d) floats.  For the stem, x is the padded 4-channel image.
 int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* out, float* partials, hipStream_t s,

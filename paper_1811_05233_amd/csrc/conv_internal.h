@@ -97,6 +97,7 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
 size_t rn50_dgrad_stats_floats(const conv_desc& d);
 size_t rn50_wgrad_acc_floats(const conv_desc& d);
 size_t rn50_wgrad_partial_floats(const conv_desc& d);
+size_t rn50_wgrad_variant_partial_bytes(const conv_desc& d, int variant);
 int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* out, float* partials, hipStream_t s,
                            int variant);
 int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, float* out, hipStream_t s);

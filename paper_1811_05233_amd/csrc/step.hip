@@ -414,8 +414,12 @@ namespace {
 // Launch site with variants.  Normally launches variant *choice.  In tuning mode it times every variant
 // (one warm-up, two timed launches, device-synchronous) on stream s, stores the fastest in *choice and
 // leaves its (identical) result in place.
-template <class F>
-int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch, const char* what = "", const char* layer = "")
+inline float no_penalty(int) { return 0.f; }
+
+// penalty_ms(cand) is added to a candidate's measured time (cost the timing in isolation does not show).
+template <class F, class G = float (*)(int)>
+int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch, const char* what = "", const char* layer = "",
+                   G penalty_ms = no_penalty)
 {
     if (!c.tuning) return launch(*choice);
     static const bool log = getenv("RN50_TUNE_LOG") != nullptr;     // per-candidate times on stderr
@@ -432,10 +436,11 @@ int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch,
         float ms = 0.f;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, c.tune_e0, c.tune_e1);
         if (e != hipSuccess) return rn50_hip_fail(e);
+        ms = ms * 0.5f + penalty_ms(cand);
         if (ms < best_ms) { best_ms = ms; best = cand; }
-        if (log) fprintf(stderr, "tune %s %s cand %d: %.1f us\n", layer, what, cand, ms * 500.f);
+        if (log) fprintf(stderr, "tune %s %s cand %d: %.1f us\n", layer, what, cand, ms * 1000.f);
     }
-    if (log) fprintf(stderr, "tune %s %s -> %d (%.1f us)\n", layer, what, best, best_ms * 500.f);
+    if (log) fprintf(stderr, "tune %s %s -> %d (%.1f us)\n", layer, what, best, best_ms * 1000.f);
     *choice = best;
     return launch(best);
 }
@@ -545,7 +550,13 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         if (e != hipSuccess) return rn50_hip_fail(e);
         return launch_or_tune(c, c.side, l.d.c == 3 ? 3 : RN50_NUM_WGRAD_VARIANTS, &l.wgrad_variant, [&](int variant) {
             return rn50_conv_wgrad_launch(l.d, in, l.dconv, out, c.wgrad_part, c.side, variant);
-        }, "wgrad", l.name.c_str());
+        }, "wgrad", l.name.c_str(), [&](int variant) {
+            // the partial tiles of a pixel split are written and read back through HBM, which the rest of the
+            // step competes for; timing the variant on its own does not show that, so the traffic is charged at
+            // a nominal 1.5 TB/s (the value that gave the shortest step among 0.7 .. 6 TB/s)
+            const float gbs = 1500.f;
+            return 2.f * (float)rn50_wgrad_variant_partial_bytes(l.d, variant) / (gbs * 1e6f);
+        });
     };
     // BN backward, stand-alone form (reduce, finalize, apply): dy -> l.dconv (and dres)
     auto bn_bwd_std = [&](ConvLayer& l, const h16* dy, bool relu, h16* dres) -> int {
