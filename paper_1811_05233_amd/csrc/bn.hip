@@ -379,6 +379,154 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(long long m, int
     }
 }
 
+// ------------------------------------------------------------------ finalize + apply in one launch
+// For layers with few row tiles (small feature maps) a separate finalize launch costs more than the work it
+// does.  Here every workgroup owns a 64-channel slice and kSliceRows rows, first adds up the partials of its own
+// 64 channels (redundantly with the other workgroups of the slice: ntiles x 512 bytes from L2) and then applies.
+// The first row chunk of each slice also stores the per-channel results.
+constexpr int kSliceRows = 128;          // 32 row lanes x 4 rows in flight
+constexpr int kFusedMaxTiles = 400;      // beyond this the redundant summing costs more than the finalize launch (measured: 128, 400, 800)
+
+// Column sums of part[ntiles][2][c] for channels [ch0, ch0 + 64): s[0..63] = first sums, s[64..127] = second sums.
+__device__ __forceinline__ void slice_partial_sums(const float* __restrict__ part, int c, int ntiles, int ch0, double* s)
+{
+    __shared__ float red[4][128];
+    const int tid = threadIdx.x;
+    const int cl = tid & 31, rl = tid >> 5;                       // 32 x 16-byte columns, 8 row lanes
+    const float* p = part + (size_t)(cl >> 4) * c + ch0 + (cl & 15) * 4;
+    const size_t pitch = 2 * (size_t)c;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int r0 = rl; r0 < ntiles; r0 += 64) {
+        f32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int r = r0 + u * 8;
+            v[u] = r < ntiles ? *reinterpret_cast<const f32x4*>(p + (size_t)r * pitch) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] += __shfl_xor(acc[j], 32, 64);
+    if ((tid & 63) < 32) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) red[tid >> 6][cl * 4 + j] = acc[j];
+    }
+    __syncthreads();
+    if (tid < 128) s[tid] = (double)red[0][tid] + (double)red[1][tid] + (double)red[2][tid] + (double)red[3][tid];
+    __syncthreads();
+}
+
+template <bool kRelu, bool kRes>
+__global__ __launch_bounds__(kThreads) void bn_fused_apply_kernel(long long m, int c, float eps, int ntiles,
+                                                                  const float* __restrict__ part,
+                                                                  const h16* __restrict__ x,
+                                                                  const float* __restrict__ gamma,
+                                                                  const float* __restrict__ beta,
+                                                                  const h16* __restrict__ res, h16* __restrict__ y,
+                                                                  float* __restrict__ save_mean,
+                                                                  float* __restrict__ save_invstd)
+{
+    __shared__ double sums[128];
+    __shared__ float s_mean[64], s_inv[64];
+    const int tid = threadIdx.x;
+    const int ch0 = blockIdx.y * 64;
+    const int cg = tid & 7, rl = tid >> 3;                         // 8 channel groups of 8, 32 row lanes
+    const long long row0 = (long long)blockIdx.x * kSliceRows + rl;
+    const size_t col = (size_t)ch0 + cg * 8;
+    // the rows of x (and the residual) are requested before the statistics are known
+    h16x8 v[4], rv[4] = {};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const long long r = row0 + u * 32;
+        v[u] = r < m ? *reinterpret_cast<const h16x8*>(x + (size_t)r * c + col) : h16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        if (kRes && r < m) rv[u] = *reinterpret_cast<const h16x8*>(res + (size_t)r * c + col);
+    }
+    slice_partial_sums(part, c, ntiles, ch0, sums);
+    if (tid < 64) {
+        const double md = sums[tid] / (double)m;
+        double var = sums[64 + tid] / (double)m - md * md;
+        if (var < 0.0) var = 0.0;
+        const float mean = (float)md, inv = (float)(1.0 / sqrt(var + (double)eps));
+        s_mean[tid] = mean; s_inv[tid] = inv;
+        if (blockIdx.x == 0) { save_mean[ch0 + tid] = mean; save_invstd[ch0 + tid] = inv; }
+    }
+    __syncthreads();
+    float g[8], b[8], mu[8], is[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        g[j] = gamma[col + j]; b[j] = beta[col + j];
+        mu[j] = s_mean[cg * 8 + j]; is[j] = s_inv[cg * 8 + j];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const long long r = row0 + u * 32;
+        if (r >= m) continue;
+        h16x8 o;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float t = g[j] * (((float)v[u][j] - mu[j]) * is[j]) + b[j];
+            if (kRes) t += (float)rv[u][j];
+            if (kRelu) t = t > 0.f ? t : 0.f;
+            o[j] = (h16)t;
+        }
+        *reinterpret_cast<h16x8*>(y + (size_t)r * c + col) = o;
+    }
+}
+
+// backward: partials are (sum g | sum g*xhat) of the already masked gradient g; dx = gamma*invstd*(g - mean(g) - xhat*mean(g*xhat))
+__global__ __launch_bounds__(kThreads) void bn_bwd_fused_apply_kernel(long long m, int c, int ntiles,
+                                                                      const float* __restrict__ part,
+                                                                      const h16* __restrict__ gr,
+                                                                      const h16* __restrict__ x,
+                                                                      const float* __restrict__ gamma,
+                                                                      const float* __restrict__ mean,
+                                                                      const float* __restrict__ invstd,
+                                                                      h16* __restrict__ dx, float* __restrict__ dgamma32,
+                                                                      float* __restrict__ dbeta32)
+{
+    __shared__ double sums[128];
+    const int tid = threadIdx.x;
+    const int ch0 = blockIdx.y * 64;
+    const int cg = tid & 7, rl = tid >> 3;
+    const long long row0 = (long long)blockIdx.x * kSliceRows + rl;
+    const size_t col = (size_t)ch0 + cg * 8;
+    h16x8 gv[4], xv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const long long r = row0 + u * 32;
+        gv[u] = r < m ? *reinterpret_cast<const h16x8*>(gr + (size_t)r * c + col) : h16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        xv[u] = r < m ? *reinterpret_cast<const h16x8*>(x + (size_t)r * c + col) : h16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    slice_partial_sums(part, c, ntiles, ch0, sums);
+    if (blockIdx.x == 0 && tid < 64) {
+        if (dbeta32) dbeta32[ch0 + tid] = (float)sums[tid];
+        if (dgamma32) dgamma32[ch0 + tid] = (float)sums[64 + tid];
+    }
+    const float inv_m = 1.f / (float)m;
+    float mu[8], is[8], sc[8], mb[8], mg[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        mu[j] = mean[col + j]; is[j] = invstd[col + j];
+        sc[j] = gamma[col + j] * is[j];
+        mb[j] = (float)sums[cg * 8 + j] * inv_m;
+        mg[j] = (float)sums[64 + cg * 8 + j] * inv_m;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const long long r = row0 + u * 32;
+        if (r >= m) continue;
+        h16x8 o;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float g = (float)gv[u][j];
+            const float xh = ((float)xv[u][j] - mu[j]) * is[j];
+            o[j] = (h16)(sc[j] * (g - mb[j] - xh * mg[j]));
+        }
+        *reinterpret_cast<h16x8*>(dx + (size_t)r * c + col) = o;
+    }
+}
+
 struct BnPlan { int nblk; int rows_per_block; };
 
 // Elementwise passes: 4 rows per thread (one unrolled batch), as many workgroups as that takes.
@@ -462,6 +610,16 @@ int rn50_bn_fwd_from_partials_launch(long long m, int c, float eps, bool relu, c
                                      const float* part, int ntiles, hipStream_t s)
 {
     const double elems = (double)m * c;
+    if (ntiles <= kFusedMaxTiles && c % 64 == 0) {
+        ProfScope ps(RN50_K_BN_FUSED_APPLY, 0.0, (res ? 6.0 : 4.0) * elems, s);
+        const dim3 grid((unsigned)rn50_cdiv(m, kSliceRows), (unsigned)(c / 64));
+#define RN50_BN_FUSED(R, Z) bn_fused_apply_kernel<R, Z><<<grid, kThreads, 0, s>>>(m, c, eps, ntiles, part, x, gamma, beta, res, \
+                                                                                y, save_mean, save_invstd)
+        if (relu) { if (res) RN50_BN_FUSED(true, true); else RN50_BN_FUSED(true, false); }
+        else      { if (res) RN50_BN_FUSED(false, true); else RN50_BN_FUSED(false, false); }
+#undef RN50_BN_FUSED
+        return rn50_check_launch();
+    }
     {
         ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * ntiles * c, s);
         launch_bn_finalize<0>(m, c, eps, ntiles, nullptr, part, save_mean, save_invstd, nullptr, nullptr, nullptr, nullptr, s);
@@ -510,6 +668,13 @@ int rn50_bn_bwd_from_partials_launch(long long m, int c, const h16* g, const h16
                                      hipStream_t s)
 {
     const double elems = (double)m * c;
+    if (ntiles <= kFusedMaxTiles && c % 64 == 0) {
+        ProfScope ps(RN50_K_BN_BWD_FUSED_APPLY, 0.0, 6.0 * elems, s);
+        const dim3 grid((unsigned)rn50_cdiv(m, kSliceRows), (unsigned)(c / 64));
+        bn_bwd_fused_apply_kernel<<<grid, kThreads, 0, s>>>(m, c, ntiles, part, g, x, gamma, save_mean, save_invstd, dx,
+                                                            dgamma32, dbeta32);
+        return rn50_check_launch();
+    }
     {
         ProfScope ps(RN50_K_BN_BWD_FINALIZE, 0.0, 8.0 * ntiles * c, s);
         launch_bn_finalize<1>(m, c, 0.f, ntiles, nullptr, part, sums, nullptr, nullptr, nullptr, dgamma32, dbeta32, s);

@@ -14,9 +14,11 @@ enum Rn50Kernel {
     RN50_K_BN_STATS,
     RN50_K_BN_STATS_FINALIZE,
     RN50_K_BN_APPLY,
+    RN50_K_BN_FUSED_APPLY,
     RN50_K_BN_BWD_REDUCE,
     RN50_K_BN_BWD_FINALIZE,
     RN50_K_BN_BWD_APPLY,
+    RN50_K_BN_BWD_FUSED_APPLY,
     RN50_K_SGD,
     RN50_K_CAST,
     RN50_K_FILL,

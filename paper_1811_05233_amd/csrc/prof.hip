@@ -12,8 +12,8 @@ const char* const kNames[RN50_K_COUNT] = {
     "gather_gemm_kernel<128,64,32,4,2> (stem)",
     "wgrad_kernel<128,128,4,64,false>", "wgrad_kernel<64,64,4,64,false>", "wgrad_kernel<64,64,4,32,true> (stem)",
     "wgrad_reduce_kernel",
-    "bn_stats_kernel", "bn_finalize_kernel<0,*> (forward statistics)", "bn_apply_kernel",
-    "bn_bwd_reduce_kernel", "bn_finalize_kernel<1,*> (backward sums)", "bn_bwd_apply_kernel",
+    "bn_stats_kernel", "bn_finalize_kernel<0,*> (forward statistics)", "bn_apply_kernel", "bn_fused_apply_kernel (finalize + apply)",
+    "bn_bwd_reduce_kernel", "bn_finalize_kernel<1,*> (backward sums)", "bn_bwd_apply_kernel", "bn_bwd_fused_apply_kernel (finalize + apply)",
     "sgd_momentum_kernel", "cast_f32_to_h16_kernel", "fill_zero_kernel", "transpose_all_kernel",
     "maxpool/avgpool kernels", "fc kernels", "ls_xent_kernel", "stem pad/pack/unpack kernels"};
 
