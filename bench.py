@@ -78,7 +78,8 @@ CONV_SHAPES = [
 
 def conv_sweep(args):
     """Every convolution shape on its own through the C ABI (built-in tile heuristics), each launch timed by
-    the library's HIP-event pairs on the launch stream; operands are re-used between launches (warm)."""
+    the library's HIP-event pairs on the launch stream; operands are re-used between launches (warm) or, with
+    --cold, rotated among enough distinct sets to exceed the Infinity Cache."""
     import torch
     import paper_1811_05233_amd as P
     from paper_1811_05233_amd import synth
@@ -87,19 +88,41 @@ def conv_sweep(args):
     for i, (cin, cout, r, stride, pad, hin, cnt) in enumerate(CONV_SHAPES):
         d = P.make_conv_desc(B, hin, hin, cin, cout, r, r, stride, pad)
         p = (hin + 2 * pad - r) // stride + 1
-        x = torch.from_numpy(synth.normal_f16(100 + i, (B, hin, hin, cin))).to(dev)
-        w = torch.from_numpy(synth.he_normal_f16(130 + i, (cout, r, r, cin), cin * r * r)).to(dev)
-        dy = torch.from_numpy(synth.normal_f16(160 + i, (B, p, p, cout))).to(dev)
-        y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w)
+        x0 = torch.from_numpy(synth.normal_f16(100 + i, (B, hin, hin, cin))).to(dev)
+        w0 = torch.from_numpy(synth.he_normal_f16(130 + i, (cout, r, r, cin), cin * r * r)).to(dev)
+        dy0 = torch.from_numpy(synth.normal_f16(160 + i, (B, p, p, cout))).to(dev)
+        set_bytes = 2 * (x0.numel() + w0.numel() + dy0.numel())
+        nset = max(2, -(-(300 << 20) // set_bytes)) if args.cold else 1          # > 256 MB of distinct operands
+        xs, wts, dys = [x0] + [x0.clone() for _ in range(nset - 1)], [w0] + [w0.clone() for _ in range(nset - 1)], \
+            [dy0] + [dy0.clone() for _ in range(nset - 1)]
+        ys, dxs, dws = [torch.empty_like(t) for t in dys], [torch.empty_like(t) for t in xs], [torch.empty_like(t) for t in wts]
         ws = [torch.empty(max(P.conv_workspace_bytes(d, k), 16), dtype=torch.uint8, device=dev) for k in range(3)]
+        turn = [0]
+
+        def nxt():
+            turn[0] = (turn[0] + 1) % nset
+            return turn[0]
+
         flops = 2.0 * B * p * p * cout * r * r * cin
         inp = B * p * p * cin if (r == 1 and stride > 1) else B * hin * hin * cin
         nbytes = 2.0 * (inp + cout * r * r * cin + B * p * p * cout)
         floor_us = max(flops / (PEAK_FP16_TFLOPS * 1e12), nbytes / (PEAK_HBM_GBS * 1e9)) * 1e6
         row = {"shape": "%d>%d %dx%d/%d @%d" % (cin, cout, r, r, stride, hin), "layers": cnt,
                "gflop": round(flops / 1e9, 3), "mbytes": round(nbytes / 1e6, 1), "roofline_us": round(floor_us, 2)}
-        for kind, fn in (("fwd", lambda: P.conv_fwd(d, x, w, y, ws[0])), ("dgrad", lambda: P.conv_dgrad(d, dy, w, dx, ws[1])),
-                         ("wgrad", lambda: P.conv_wgrad(d, x, dy, dw, ws[2]))):
+
+        def f_fwd():
+            j = nxt()
+            P.conv_fwd(d, xs[j], wts[j], ys[j], ws[0])
+
+        def f_dgrad():
+            j = nxt()
+            P.conv_dgrad(d, dys[j], wts[j], dxs[j], ws[1])
+
+        def f_wgrad():
+            j = nxt()
+            P.conv_wgrad(d, xs[j], dys[j], dws[j], ws[2])
+
+        for kind, fn in (("fwd", f_fwd), ("dgrad", f_dgrad), ("wgrad", f_wgrad)):
             if kind == "dgrad" and cin == 3:
                 continue
             for _ in range(3):
@@ -118,7 +141,8 @@ def conv_sweep(args):
     print(json.dumps({"metric": "conv kernel sweep, ResNet-50 v1.5 shapes @ batch %d" % B, "unit": "TFLOP/s",
                       "value": summary["fwd"]["tflops"], "n_gpus": 1, "dtype": "f16 storage, f32 accumulate",
                       "data": "synthetic", "config": {"workload": "23 distinct conv shapes (53 layers), fwd / dgrad / wgrad "
-                      "timed separately, warm operands, built-in tile heuristics"}, "summary": summary, "shapes": rows}))
+                      "timed separately, %s operands, built-in tile heuristics" % ("cold (rotating sets > 256 MB)" if args.cold else "warm")},
+                      "summary": summary, "shapes": rows}))
 
 
 def batch_sweep(args):
@@ -197,6 +221,8 @@ def main():
     ap.add_argument("--cpu-sample-batch", type=int, default=4, help="0 disables the cpu_baseline leg")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-autotune", action="store_true", help="use the built-in tile heuristics")
+    ap.add_argument("--cold", action="store_true",
+                    help="conv-sweep: rotate every launch among enough operand sets to exceed the 256 MB Infinity Cache")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three plain 256 MiB device copies (a kernel of known traffic, to calibrate "
                          "hardware byte counters against)")
