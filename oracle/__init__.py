@@ -218,6 +218,25 @@ def sgd_momentum_flat(g, w, v, lr, mu, wd, grad_scale=1.0, want_lowp=True):
     return lowp
 
 
+def lars_momentum_flat(g, w, v, segments, lr, mu, wd, eta, eps, grad_scale=1.0, want_lowp=True):
+    """LARS with momentum; segments = [(offset, count, use_lars), ...].  Updates w and v IN PLACE.
+    Returns (w rounded to binary16 or None, per-segment rate)."""
+    dt = w.dtype
+    assert g.dtype == dt and v.dtype == dt and w.flags["C_CONTIGUOUS"] and v.flags["C_CONTIGUOUS"]
+    g = _c(g, dt)
+    nseg = len(segments)
+    off = np.array([s[0] for s in segments], dtype=np.uint64)
+    cnt = np.array([s[1] for s in segments], dtype=np.uint64)
+    use = np.array([1 if s[2] else 0 for s in segments], dtype=np.int32)
+    assert all(int(o) + int(c) <= w.size for o, c in zip(off, cnt))
+    lowp = np.array(w, copy=True) if want_lowp else None
+    rate = np.empty(nseg, dt)
+    getattr(lib(), "lars_momentum_flat" + _sfx(w))(
+        ctypes.c_size_t(nseg), _p(off), _p(cnt), _p(use), _p(g), _real(dt, grad_scale), _p(w), _p(v), _p(lowp),
+        _real(dt, lr), _real(dt, mu), _real(dt, wd), _real(dt, eta), _real(dt, eps), _p(rate))
+    return lowp, rate
+
+
 def round_binary16(a):
     """Copy of a with every element rounded to the nearest binary16 value (ties to even)."""
     out = np.array(a, copy=True, order="C")

@@ -355,6 +355,68 @@ def test_sgd_closed_forms():
     assert np.allclose(w32, w0 - lr * (g * s + wd * w0), rtol=1e-6, atol=1e-7)
 
 
+def test_lars_worked_example_and_invariants():
+    """LARS with momentum (Sec. 3.2, training configurations: coefficient 0.01, eps 1e-6, FP32)."""
+    # worked by hand: w = (3,4) so ||w|| = 5, g = (1,0) so ||g|| = 1, wd = 0.2, eta = 0.01, eps = 0:
+    #   rate = 0.01*5 / (1 + 0.2*5) = 0.025; g + wd*w = (1.6, 0.8); lr = 2, mu = 0.5, v0 = (1,1)
+    #   v = 0.5*(1,1) + 2*0.025*(1.6,0.8) = (0.58, 0.54); w = (3,4) - v = (2.42, 3.46)
+    w, v = np.array([3.0, 4.0]), np.array([1.0, 1.0])
+    _, rate = O.lars_momentum_flat(np.array([1.0, 0.0]), w, v, [(0, 2, True)], 2.0, 0.5, 0.2, 0.01, 0.0)
+    assert abs(rate[0] - 0.025) < 1e-15
+    assert np.allclose(v, [0.58, 0.54], rtol=0, atol=1e-15) and np.allclose(w, [2.42, 3.46], rtol=0, atol=1e-15)
+    # a gradient parallel to the weights: rate*(g + wd*w) = eta*||w||*g/||g||, whatever wd is
+    for wd in (0.0, 0.1, 0.7):
+        w, v = np.array([3.0, 4.0]), np.zeros(2)
+        O.lars_momentum_flat(np.array([0.6, 0.8]), w, v, [(0, 2, True)], 2.0, 0.9, wd, 0.01, 0.0)
+        assert np.allclose(v, 2.0 * 0.01 * 5.0 * np.array([0.6, 0.8]), rtol=1e-14)
+    n = 4096
+    g, w0 = RNG.standard_normal(n), RNG.standard_normal(n)
+    segs = [(0, 1000, True), (1000, 24, False), (1024, 3072, True)]
+    lr, mu, eta = 0.3, 0.9, 0.01
+    # wd = 0, eps = 0, v = 0: the step of a LARS segment has length lr*eta*||w|| and does not depend on the
+    # scale of the gradient; a plain segment takes lr*g (the momentum-SGD oracle with wd = 0 on its first step)
+    ref = None
+    for c in (1.0, 1e-3, 512.0):
+        w, v = w0.copy(), np.zeros(n)
+        O.lars_momentum_flat(g * c, w, v, segs, lr, mu, 0.0, eta, 0.0, want_lowp=False)
+        for o, cnt, use in segs:
+            if use:
+                assert abs(np.linalg.norm(w[o:o + cnt] - w0[o:o + cnt]) / (lr * eta * np.linalg.norm(w0[o:o + cnt])) - 1) < 1e-12
+        lars_part = np.concatenate([w[:1000], w[1024:]])
+        ref = lars_part if ref is None else ref
+        assert np.allclose(lars_part, ref, rtol=1e-11, atol=1e-13)
+        ws, vs = w0[1000:1024].copy(), np.zeros(24)
+        O.sgd_momentum_flat(g[1000:1024] * c, ws, vs, lr, mu, 0.0, 1.0, want_lowp=False)
+        assert np.allclose(w[1000:1024], ws, rtol=1e-14)
+    # grad_scale multiplies the gradient before anything else: same result as a pre-scaled gradient
+    w1, v1, w2, v2 = w0.copy(), np.zeros(n), w0.copy(), np.zeros(n)
+    O.lars_momentum_flat(g, w1, v1, segs, lr, mu, 1e-4, eta, 1e-6, grad_scale=1 / 64.0, want_lowp=False)
+    O.lars_momentum_flat(g / 64.0, w2, v2, segs, lr, mu, 1e-4, eta, 1e-6, want_lowp=False)
+    assert np.allclose(w1, w2, rtol=1e-13) and np.allclose(v1, v2, rtol=1e-13)
+    # segments are independent of each other and of their order; elements outside every segment stay untouched
+    w3, v3 = w0.copy(), np.zeros(n)
+    low, rate = O.lars_momentum_flat(g / 64.0, w3, v3, [segs[2], segs[0]], lr, mu, 1e-4, eta, 1e-6)
+    assert np.array_equal(w3[:1000], w2[:1000]) and np.array_equal(w3[1024:], w2[1024:])
+    assert np.array_equal(w3[1000:1024], w0[1000:1024]) and np.all(v3[1000:1024] == 0)
+    touched = np.r_[0:1000, 1024:n]
+    assert np.array_equal(low[touched], w3[touched].astype(np.float16).astype(np.float64))
+    # eps only matters when the norms are tiny: rate = eta*||w|| / (||g|| + wd*||w|| + eps)
+    wt, vt = np.full(4, 1e-7), np.zeros(4)
+    _, r = O.lars_momentum_flat(np.full(4, 2e-7), wt, vt, [(0, 4, True)], 1.0, 0.0, 0.0, 0.01, 1e-6)
+    assert abs(r[0] - 0.01 * 2e-7 / (4e-7 + 1e-6)) < 1e-15
+    # a zero gradient or zero weights switch the layer-wise scaling off (rate 1) instead of dividing by zero
+    wz, vz = np.zeros(8), np.zeros(8)
+    _, r = O.lars_momentum_flat(np.ones(8), wz, vz, [(0, 8, True)], 0.5, 0.0, 0.0, 0.01, 0.0)
+    assert r[0] == 1.0 and np.allclose(wz, -0.5)
+    wz, vz = np.ones(8), np.full(8, 2.0)
+    _, r = O.lars_momentum_flat(np.zeros(8), wz, vz, [(0, 8, True)], 0.5, 0.5, 0.0, 0.01, 0.0)
+    assert r[0] == 1.0 and np.allclose(vz, 1.0) and np.allclose(wz, 0.0)
+    # fp32 instantiation agrees with fp64 to fp32 rounding
+    w32, v32 = w0.astype(np.float32), np.zeros(n, np.float32)
+    O.lars_momentum_flat((g / 64.0).astype(np.float32), w32, v32, segs, lr, mu, 1e-4, eta, 1e-6, want_lowp=False)
+    assert np.allclose(w32, w2, rtol=2e-6, atol=1e-7)
+
+
 # ------------------------------------------------------------------ layout + whole step
 def test_flat_layout_counts():
     gold = golden()
