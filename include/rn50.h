@@ -134,6 +134,34 @@ int sgd_momentum_flat(size_t n, const void* grad, int grad_dt, float grad_scale,
                       float lr, float mu, float wd, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * LARS with momentum over the flat buffer (Sec. 3.2, training configurations: the optimizer the
+ * paper used, coefficient eta = 0.01, eps = 1e-6, computed in FP32 on the FP16 gradient).  The
+ * paper prints no formula; the published layer-wise rule is used.  Per segment l (one layer
+ * tensor), with g' = float(grad)*grad_scale and the 2-norms taken over the segment:
+ *   rate_l = eta*||w_l|| / (||g'_l|| + wd*||w_l|| + eps)        (1 if either norm is zero)
+ *   v = mu*v + lr*rate_l*(g' + wd*w);  w -= v;  w_lowp_out = half(w)
+ * Segments with use_lars == 0 (BN scale / shift, biases) take  v = mu*v + lr*g';  w -= v.
+ * Note that lr sits inside the momentum buffer here, unlike sgd_momentum_flat.
+ *
+ * A plan turns the segment table into device tables once; lars_plan_create copies them into
+ * `workspace` (device memory, lars_workspace_bytes(...) bytes, 16-byte aligned, owned by the
+ * caller and in use until lars_plan_destroy) with synchronous copies.  Segment offsets must be
+ * multiples of 8 elements and segments must not overlap (RN50_ERR_SHAPE otherwise); elements
+ * outside every segment are not touched.  lars_momentum_flat enqueues three kernels on `stream`
+ * and allocates nothing; rates_out (nullable, device, one float per segment) receives rate_l.
+ * Calls that share a plan must not overlap (they share its scratch).
+ * ---------------------------------------------------------------------------------------- */
+typedef struct { size_t offset, count; int use_lars; } rn50_lars_segment;
+typedef struct lars_plan lars_plan; /* host object */
+size_t lars_workspace_bytes(const rn50_lars_segment* segments, int nseg); /* 0 on a bad table */
+int lars_plan_create(lars_plan** out, const rn50_lars_segment* segments /* host */, int nseg,
+                     void* workspace, size_t workspace_bytes);
+void lars_plan_destroy(lars_plan* plan);
+int lars_momentum_flat(const lars_plan* plan, const void* grad, int grad_dt, float grad_scale,
+                       float* master_w, float* momentum, void* w_lowp_out,
+                       float lr, float mu, float wd, float eta, float eps, float* rates_out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Whole iteration (Sec. 2 + Sec. 3.2) on a ResNet-50 v1.5 style network:
  *   [stem 7x7/2 conv 3->base_width, BN, ReLU, 3x3/2 max-pool]  (iff has_stem)
  *   num_stages stages of blocks[s] bottleneck blocks (1x1, 3x3, 1x1; widths w,w,4w with
@@ -166,7 +194,10 @@ typedef struct {
                          own buffer (larger workspace) and rn50_tensor can return it; for checking. */
 } rn50_config;
 
-typedef struct { float lr, momentum, wd, grad_scale; } rn50_hparams;
+/* lars_eta == 0: momentum SGD as in sgd_momentum_flat.  lars_eta > 0: LARS as in lars_momentum_flat, with
+ * layer-wise scaling on the convolution filters and the FC weight and plain momentum (no weight decay) on
+ * BN scale / shift and the FC bias. */
+typedef struct { float lr, momentum, wd, grad_scale, lars_eta, lars_eps; } rn50_hparams;
 
 typedef struct rn50_ctx rn50_ctx; /* host object: descriptors + pointers into the workspace */
 

@@ -42,9 +42,17 @@ class rn50_profile_entry(ctypes.Structure):
                 ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
+RN50_KIND_CONV, RN50_KIND_GAMMA, RN50_KIND_BETA, RN50_KIND_FCW, RN50_KIND_FCB = 0, 1, 2, 3, 4
+
+
 class rn50_hparams(ctypes.Structure):
+    """lars_eta == 0: momentum SGD; lars_eta > 0: LARS with momentum (coefficient lars_eta, lars_eps)."""
     _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float), ("wd", ctypes.c_float),
-                ("grad_scale", ctypes.c_float)]
+                ("grad_scale", ctypes.c_float), ("lars_eta", ctypes.c_float), ("lars_eps", ctypes.c_float)]
+
+
+class rn50_lars_segment(ctypes.Structure):
+    _fields_ = [("offset", ctypes.c_size_t), ("count", ctypes.c_size_t), ("use_lars", ctypes.c_int)]
 
 
 _lib = None
@@ -62,6 +70,10 @@ _SIGNATURES = {
     "bn_relu_bwd": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "ls_xent_fwd_bwd": (_i, [_i, _i, _vp, _vp, _f, _f, _vp, _vp, _vp, _i, _vp]),
     "sgd_momentum_flat": (_i, [_sz, _vp, _i, _f, _vp, _vp, _vp, _f, _f, _f, _vp]),
+    "lars_workspace_bytes": (_sz, [ctypes.POINTER(rn50_lars_segment), _i]),
+    "lars_plan_create": (_i, [ctypes.POINTER(_vp), ctypes.POINTER(rn50_lars_segment), _i, _vp, _sz]),
+    "lars_plan_destroy": (None, [_vp]),
+    "lars_momentum_flat": (_i, [_vp, _vp, _i, _f, _vp, _vp, _vp, _f, _f, _f, _f, _f, _vp, _vp]),
     "rn50_param_count": (_sz, [ctypes.POINTER(rn50_config)]),
     "rn50_num_segments": (_i, [ctypes.POINTER(rn50_config)]),
     "rn50_param_layout": (_i, [ctypes.POINTER(rn50_config), _i, ctypes.POINTER(_sz), ctypes.POINTER(_sz),
@@ -184,6 +196,37 @@ def ls_xent_fwd_bwd(batch, classes, logits, labels, eps, grad_scale, loss_mean, 
 def sgd_momentum_flat(n, grad, grad_scale, master_w, momentum, w_lowp_out, lr, mu, wd, grad_dt=RN50_F16):
     _check(lib().sgd_momentum_flat(n, _ptr(grad), grad_dt, grad_scale, _ptr(master_w), _ptr(momentum),
                                    _ptr(w_lowp_out), lr, mu, wd, _stream()), "sgd_momentum_flat")
+
+
+class LarsPlan:
+    """Device tables for lars_momentum_flat over segments [(offset, count, use_lars), ...]; owns its workspace."""
+
+    def __init__(self, segments, device):
+        import torch
+        self.nseg = len(segments)
+        arr = (rn50_lars_segment * max(self.nseg, 1))(*[rn50_lars_segment(int(o), int(c), 1 if u else 0) for o, c, u in segments])
+        need = int(lib().lars_workspace_bytes(arr, self.nseg))
+        if need == 0 and self.nseg:
+            raise Rn50Error("lars_workspace_bytes: bad segment table")
+        self.workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
+        h = _vp()
+        _check(lib().lars_plan_create(ctypes.byref(h), arr, self.nseg, _ptr(self.workspace), need), "lars_plan_create")
+        self.handle = h
+
+    def step(self, grad, grad_scale, master_w, momentum, w_lowp_out, lr, mu, wd, eta, eps, rates_out=None, grad_dt=RN50_F16):
+        _check(lib().lars_momentum_flat(self.handle, _ptr(grad), grad_dt, grad_scale, _ptr(master_w), _ptr(momentum),
+                                        _ptr(w_lowp_out), lr, mu, wd, eta, eps, _ptr(rates_out), _stream()), "lars_momentum_flat")
+
+    def close(self):
+        if self.handle:
+            lib().lars_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def rn50_cast_params(n, master_w, w_lowp, dt=RN50_F16):

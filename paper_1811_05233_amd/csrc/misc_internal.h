@@ -25,3 +25,7 @@ int rn50_bn_bwd_from_partials_launch(long long m, int c, const h16* g, const h16
                                      hipStream_t s);
 int rn50_sgd_from_f32_launch(size_t n, const float* g32, h16* g16, float grad_scale, float* w, float* v, h16* w16,
                              float lr, float mu, float wd, hipStream_t s);
+struct lars_plan;
+// grad: FP16 gradient, or with f32_grad FP32 accumulators whose half-rounded values are also written to g16
+int rn50_lars_launch(const lars_plan* p, const void* grad, bool f32_grad, h16* g16, float grad_scale, float* w, float* v,
+                     h16* w16, float lr, float mu, float wd, float eta, float eps, float* rates_out, hipStream_t s);

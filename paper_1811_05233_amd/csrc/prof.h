@@ -20,6 +20,9 @@ enum Rn50Kernel {
     RN50_K_BN_BWD_APPLY,
     RN50_K_BN_BWD_FUSED_APPLY,
     RN50_K_SGD,
+    RN50_K_LARS_NORM,
+    RN50_K_LARS_RATE,
+    RN50_K_LARS_UPDATE,
     RN50_K_CAST,
     RN50_K_FILL,
     RN50_K_TRANSPOSE,

@@ -14,7 +14,7 @@ const char* const kNames[RN50_K_COUNT] = {
     "wgrad_reduce_kernel",
     "bn_stats_kernel", "bn_finalize_kernel<0,*> (forward statistics)", "bn_apply_kernel", "bn_fused_apply_kernel (finalize + apply)",
     "bn_bwd_reduce_kernel", "bn_finalize_kernel<1,*> (backward sums)", "bn_bwd_apply_kernel", "bn_bwd_fused_apply_kernel (finalize + apply)",
-    "sgd_momentum_kernel", "cast_f32_to_h16_kernel", "fill_zero_kernel", "transpose_all_kernel",
+    "sgd_momentum_kernel", "lars_norm_kernel", "lars_rate_kernel", "lars_update_kernel", "cast_f32_to_h16_kernel", "fill_zero_kernel", "transpose_all_kernel",
     "maxpool/avgpool kernels", "fc kernels", "ls_xent_kernel", "stem pad/pack/unpack kernels"};
 
 struct Span { int kernel; double flops, bytes; hipEvent_t e0, e1; };

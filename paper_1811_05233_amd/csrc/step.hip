@@ -176,6 +176,9 @@ struct rn50_ctx {
     float* bn_ws = nullptr;
     float* bn_ws_side = nullptr;  // BN partial sums of the projection branch (forward, side stream)
     float* wgrad_part = nullptr;  // per-split partial tiles of the filter gradient
+    void* lars_ws = nullptr;      // device tables and scratch of the LARS plan
+    size_t lars_ws_bytes = 0;
+    lars_plan* lars = nullptr;
     h16* head_din = nullptr;      // gradient w.r.t. the last block's output (from the FC / avg-pool backward)
     h16* pool_din = nullptr;      // gradient w.r.t. the stem's BN output (from the max-pool backward)
     TransposeJob* jobs = nullptr;
@@ -191,6 +194,16 @@ struct rn50_ctx {
 };
 
 namespace {
+
+// Layer-wise scaling applies to the convolution filters and the FC weight; BN scale / shift and the FC bias
+// are updated with plain momentum.
+std::vector<rn50_lars_segment> lars_segments(const Layout& L)
+{
+    std::vector<rn50_lars_segment> segs;
+    for (const Segment& sg : L.segments)
+        segs.push_back({sg.offset, sg.count, (sg.kind == RN50_KIND_CONV || sg.kind == RN50_KIND_FCW) ? 1 : 0});
+    return segs;
+}
 
 // Lays the workspace out; with base == nullptr only the size is computed.
 size_t carve(rn50_ctx& c, char* base)
@@ -277,6 +290,11 @@ size_t carve(rn50_ctx& c, char* base)
     // produced by the next block's conv1 data gradient; only the last block keeps a buffer of its own
     for (int bi = 0; bi + 1 < nb; ++bi) L.layers[L.blocks[bi].c3].dres = L.layers[L.blocks[bi + 1].c1].din;
     c.jobs = reinterpret_cast<TransposeJob*>(take(L.layers.size() * sizeof(TransposeJob)));
+    {
+        const std::vector<rn50_lars_segment> segs = lars_segments(L);
+        c.lars_ws_bytes = lars_workspace_bytes(segs.data(), (int)segs.size());
+        c.lars_ws = take(c.lars_ws_bytes);
+    }
     return off;
 }
 
@@ -349,6 +367,11 @@ extern "C" int rn50_create(rn50_ctx** out, const rn50_config* cfg, void* workspa
         hipError_t e = hipMemcpy(c->jobs, jobs.data(), jobs.size() * sizeof(TransposeJob), hipMemcpyHostToDevice);
         if (e != hipSuccess) { delete c; return rn50_hip_fail(e); }
     }
+    {
+        const std::vector<rn50_lars_segment> segs = lars_segments(c->L);
+        const int rc = lars_plan_create(&c->lars, segs.data(), (int)segs.size(), c->lars_ws, c->lars_ws_bytes);
+        if (rc != RN50_OK) { delete c; return rc; }
+    }
     hipError_t e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_event, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->transpose_fork, hipEventDisableTiming);
@@ -373,6 +396,7 @@ extern "C" void rn50_destroy(rn50_ctx* ctx)
     if (ctx->tune_e0) (void)hipEventDestroy(ctx->tune_e0);
     if (ctx->tune_e1) (void)hipEventDestroy(ctx->tune_e1);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    lars_plan_destroy(ctx->lars);
     delete ctx;
 }
 
@@ -637,6 +661,10 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     }
 
     // ================= flat FP16 gradient, update =================
+    if (hp && hp->lars_eta > 0.f)
+        return rn50_lars_launch(c.lars, c.grad32, true, static_cast<h16*>(grad_lowp), hp->grad_scale, master_w, momentum,
+                                static_cast<h16*>(w_lowp), hp->lr, hp->momentum, hp->wd, hp->lars_eta, hp->lars_eps,
+                                nullptr, s);
     if (hp)
         return rn50_sgd_from_f32_launch(L.param_count, c.grad32, static_cast<h16*>(grad_lowp), hp->grad_scale, master_w,
                                         momentum, static_cast<h16*>(w_lowp), hp->lr, hp->momentum, hp->wd, s);

@@ -82,6 +82,96 @@ def test_sgd_no_lowp_and_errors():
         P.sgd_momentum_flat(n, g, 1.0, w, v, None, 0.5, 0.0, 0.0, grad_dt=P.RN50_BF16)
 
 
+# ------------------------------------------------------------------ LARS
+def _lars_case(n, segments, seed, steps=1, wd=1e-4, s=1.0 / 1024, g_std=1.0):
+    g = synth.normal_f16(seed, (n,), g_std)
+    w0 = synth.normal_f32(seed + 1, (n,), 0.05)
+    v0 = synth.normal_f32(seed + 2, (n,), 0.01)
+    lr, mu, eta, eps = 0.5, 0.9, 0.01, 1e-6
+    gd, wdv, vd = dev_h(g), dev_f(w0), dev_f(v0)
+    lo = torch.full((max(n, 1),), 7.0, dtype=torch.float16, device=DEV)
+    rates = torch.zeros(max(len(segments), 1), dtype=torch.float32, device=DEV)
+    plan = P.LarsPlan(segments, DEV)
+    w32, v32 = w0.copy(), v0.copy()
+    w64, v64 = w0.astype(np.float64), v0.astype(np.float64)
+    f = lambda x: float(np.float32(x))   # noqa: E731
+    for step in range(steps):
+        plan.step(gd, s, wdv, vd, lo, lr, mu, wd, eta, eps, rates)
+        _, r32 = O.lars_momentum_flat(g.astype(np.float32), w32, v32, segments, np.float32(lr), np.float32(mu), np.float32(wd),
+                                      np.float32(eta), np.float32(eps), np.float32(s), want_lowp=False)
+        _, r64 = O.lars_momentum_flat(g.astype(np.float64), w64, v64, segments, f(lr), f(mu), f(wd), f(eta), f(eps), f(s),
+                                      want_lowp=False)
+        gw, gv, gr = host(wdv), host(vd), host(rates)[:len(segments)]
+        if len(segments):
+            # the layer rates: norms are summed in a different order than the oracle's, everything else is identical
+            assert np.max(np.abs(gr - r64) / np.abs(r64)) <= TOL32, "rates step %d" % step
+            assert np.max(np.abs(gr - r32.astype(np.float64)) / np.abs(r64)) <= TOL32
+        if n:
+            # FP32 oracle (the paper's optimizer precision, same operation order): 1e-5 with the usual floor.  Against
+            # the FP64 oracle the FP32 rounding of v (which enters w undamped here: w -= v) is measured against 1e-2
+            # of the largest element.
+            assert rel_err_fp32(gw, w32.astype(np.float64), 1e-3) <= TOL32 and rel_err_fp32(gv, v32.astype(np.float64), 1e-3) <= TOL32, \
+                "step %d" % step
+            assert rel_err_fp32(gw, w64, 1e-2) <= TOL32 and rel_err_fp32(gv, v64, 1e-2) <= TOL32, "step %d" % step
+    if n:
+        covered = np.zeros(n, bool)
+        for o, c, _ in segments:
+            covered[o:o + c] = True
+        gw, gv, glo = host(wdv), host(vd), host(lo)[:n]
+        # outside every segment nothing is touched; inside, the half copy is the rounding of the GPU's own FP32 weight
+        assert np.array_equal(gw[~covered], w0[~covered].astype(np.float64)) and np.array_equal(gv[~covered], v0[~covered].astype(np.float64))
+        assert np.all(glo[~covered] == 7.0)
+        assert np.array_equal(glo[covered], O.round_binary16(gw)[covered])
+    plan.close()
+
+
+@pytest.mark.parametrize("case", [
+    (0, []), (8, [(0, 8, True)]), (64, [(0, 1, True), (8, 7, False), (16, 48, True)]),
+    (5000, [(0, 2048, True), (2048, 2049, True), (4104, 1, False), (4112, 880, True)]),
+    (2 ** 20 + 24, [(8, 2 ** 20 + 11, True), (0, 8, False)]),
+    (70000, [(i * 1000, 999 - (i % 7), i % 3 != 0) for i in range(70)])])
+def test_lars_small_and_ragged(case):
+    n, segments = case
+    _progress("lars n=%d nseg=%d" % (n, len(segments)))
+    _lars_case(n, segments, 500, steps=2)
+
+
+def test_lars_resnet50_layout_three_steps():
+    """The flat 25,557,032-parameter buffer with the real segment table (161 tensors: filters and the FC weight with
+    layer-wise scaling, BN scale / shift and the FC bias without), three steps on the same gradient."""
+    cfg = P.make_config(32)
+    lay = P.rn50_param_layout(cfg)
+    segments = [(off, cnt, kind in (P.RN50_KIND_CONV, P.RN50_KIND_FCW)) for (kind, off, cnt, fan) in lay]
+    n = P.rn50_param_count(cfg)
+    assert n == 25557032 and len(segments) == 161
+    _progress("lars full n=%d" % n)
+    _lars_case(n, segments, 510, steps=3, s=1.0 / 54000, g_std=1e-3)
+
+
+def test_lars_degenerate_norms_and_errors():
+    # zero gradient / zero weights: rate 1
+    n = 4096
+    plan = P.LarsPlan([(0, 2048, True), (2048, 2048, True)], DEV)
+    g = np.zeros(n, np.float16); g[2048:] = 0.5
+    w0 = np.ones(n, np.float32); w0[2048:] = 0
+    gd, wdv, vd = dev_h(g), dev_f(w0), torch.zeros(n, dtype=torch.float32, device=DEV)
+    rates = torch.zeros(2, dtype=torch.float32, device=DEV)
+    plan.step(gd, 1.0, wdv, vd, None, 0.5, 0.0, 0.0, 0.01, 0.0, rates)
+    assert np.array_equal(host(rates), [1.0, 1.0])
+    assert np.all(host(wdv)[:2048] == 1.0) and np.all(host(wdv)[2048:] == -0.25)
+    plan.close()
+    for bad in ([(4, 8, True)], [(0, 16, True), (8, 16, False)]):      # misaligned offset, overlap
+        with pytest.raises(P.Rn50Error):
+            P.LarsPlan(bad, DEV)
+    plan = P.LarsPlan([(0, 64, True)], DEV)
+    x = torch.zeros(64, dtype=torch.float32, device=DEV)
+    with pytest.raises(P.Rn50Error):
+        plan.step(None, 1.0, x, x.clone(), None, 0.1, 0.9, 0.0, 0.01, 1e-6)
+    with pytest.raises(P.Rn50Error):
+        plan.step(x.half(), 1.0, x, x.clone(), None, 0.1, 0.9, 0.0, 0.0, 1e-6)     # eta must be positive
+    plan.close()
+
+
 # ------------------------------------------------------------------ loss
 @pytest.mark.parametrize("batch,classes", [(1, 2), (2, 10), (32, 1000), (16, 1000), (128, 1000), (37, 1001), (3, 4096)])
 def test_ls_xent(batch, classes):

@@ -178,7 +178,7 @@ def test_step_two_blocks_per_stage_ragged_batch():
 
 
 def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, loss_scale=1024.0, classes=1000,
-                       autotune=False):
+                       autotune=False, lars=None):
     """Every kernel launch inside one rn50_step call, checked where it ran: the oracle recomputes
     each layer's result from the GPU's OWN input tensors of that layer (read back from the workspace,
     keep_grads=1), so rounding differences cannot pile up over the depth of the network and the
@@ -191,7 +191,7 @@ def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, 
     cfg, net, w, x, lab = make_problem(batch, image_hw, has_stem, blocks, classes, loss_scale)
     cfg.keep_grads = 1
     lr, mu, wd_ = 0.1, 0.9, 1e-4
-    hp = P.rn50_hparams(lr, mu, wd_, 1.0 / loss_scale)
+    hp = P.rn50_hparams(lr, mu, wd_, 1.0 / loss_scale, *(lars or (0.0, 0.0)))
     ctx, out = run_gpu(cfg, w, x, lab, hp, autotune)
     tg = gpu_forward_tensors(ctx, net, x, batch)
     w64 = w.astype(f64)
@@ -307,9 +307,17 @@ def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, 
     print("[info] in-situ: worst element-wise error %.3e (%s)" % (worst[0], worst[1]), flush=True)
     # update: exact FP32 formula applied to the GPU's own FP16 gradient
     w32, v32 = w.astype(np.float32), np.zeros(w.size, np.float32)
-    O.sgd_momentum_flat(g16.astype(np.float32), w32, v32, np.float32(lr), np.float32(mu), np.float32(wd_),
-                        np.float32(1.0 / loss_scale), want_lowp=False)
-    assert np.array_equal(out["w"], w32.astype(f64)) and np.array_equal(out["v"], v32.astype(f64))
+    if lars:
+        # LARS (Sec. 3.2): layer-wise scaling on filters and the FC weight, plain momentum on BN parameters and
+        # the FC bias.  The layer norms are summed in another order than the oracle's, hence a tolerance.
+        segs = [(sg.offset, sg.count, sg.kind in (R.KIND_CONV, R.KIND_FCW)) for sg in net.segments]
+        O.lars_momentum_flat(g16.astype(np.float32), w32, v32, segs, np.float32(lr), np.float32(mu), np.float32(wd_),
+                             np.float32(lars[0]), np.float32(lars[1]), np.float32(1.0 / loss_scale), want_lowp=False)
+        assert rel_err_fp32(out["w"], w32.astype(f64), 1e-3) <= TOL32 and rel_err_fp32(out["v"], v32.astype(f64), 1e-3) <= TOL32
+    else:
+        O.sgd_momentum_flat(g16.astype(np.float32), w32, v32, np.float32(lr), np.float32(mu), np.float32(wd_),
+                            np.float32(1.0 / loss_scale), want_lowp=False)
+        assert np.array_equal(out["w"], w32.astype(f64)) and np.array_equal(out["v"], v32.astype(f64))
     assert np.array_equal(out["w16"], O.round_binary16(out["w"]))
     ctx.close()
 
@@ -328,6 +336,14 @@ def test_step_resnet50_batch32_in_situ_sampled():
 
 def test_step_small_in_situ_ragged():
     check_step_in_situ(3, (32, 48), True, (2, 2))
+
+
+def test_step_small_in_situ_lars_update():
+    check_step_in_situ(4, (64, 64), True, (1, 2, 1, 1), lars=(0.01, 1e-6))
+
+
+def test_step_resnet50_batch2_lars_update():
+    check_step_in_situ(2, (224, 224), True, (3, 4, 6, 3), n_img=1, n_k=2, lars=(0.01, 1e-6))
 
 
 def test_step_small_in_situ_autotuned():
