@@ -82,3 +82,29 @@ def test_bad_configs_and_null_arguments():
     assert l.ls_xent_fwd_bwd(4, 10, None, None, 0.1, 1.0, None, None, None, 1, None) == -3
     assert l.sgd_momentum_flat(8, None, 0, 1.0, None, None, None, 0.1, 0.9, 0.0, None) == -1
     assert l.sgd_momentum_flat(0, None, 0, 1.0, None, None, None, 0.1, 0.9, 0.0, None) == 0
+
+
+def test_lars_table_validation_without_a_gpu():
+    """lars_workspace_bytes / lars_plan_create reject bad segment tables before anything touches the device."""
+    l = P.lib()
+
+    def table(segs):
+        return (P.rn50_lars_segment * len(segs))(*[P.rn50_lars_segment(o, c, u) for o, c, u in segs]), len(segs)
+
+    good, n = table([(0, 1000, 1), (1000, 24, 0), (1024, 5000, 1)])
+    need = l.lars_workspace_bytes(good, n)
+    assert need > 0 and need % 256 == 0
+    assert l.lars_workspace_bytes(None, 0) > 0                       # an empty table is a valid (no-op) plan
+    bad_align, nb = table([(4, 8, 1)])
+    assert l.lars_workspace_bytes(bad_align, nb) == 0
+    h = ctypes.c_void_p()
+    fake = ctypes.c_void_p(1 << 20)                                  # aligned, never dereferenced on these paths
+    assert l.lars_plan_create(ctypes.byref(h), bad_align, nb, fake, 1 << 20) == -2 and not h.value      # RN50_ERR_SHAPE
+    overlap, no = table([(0, 16, 1), (8, 16, 0)])
+    assert l.lars_plan_create(ctypes.byref(h), overlap, no, fake, 1 << 20) == -2 and not h.value
+    assert l.lars_plan_create(ctypes.byref(h), good, n, None, 0) == -4                                  # RN50_ERR_WORKSPACE
+    assert l.lars_plan_create(ctypes.byref(h), good, n, fake, need - 1) == -4
+    assert l.lars_plan_create(ctypes.byref(h), good, n, ctypes.c_void_p((1 << 20) + 4), need) == -5     # RN50_ERR_ALIGN
+    assert l.lars_plan_create(None, good, n, fake, need) == -1                                          # RN50_ERR_NULL
+    assert l.lars_momentum_flat(None, fake, 0, 1.0, fake, fake, None, 0.1, 0.9, 0.0, 0.01, 1e-6, None, None) == -1
+    l.lars_plan_destroy(None)
