@@ -162,6 +162,23 @@ int lars_momentum_flat(const lars_plan* plan, const void* grad, int grad_dt, flo
                        float lr, float mu, float wd, float eta, float eps, float* rates_out, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Training recipe, host-side pure functions (Sec. 3.2 "Training Configurations": the printed formulas of
+ * configuration B, and Table 3).  epoch = processed samples / data-set size, a real number in [0, 90].
+ *   LR(epoch)         = 0.2 + (29 - 0.2)*epoch/5            epoch < 5
+ *                       29*(1 - epoch/90)^2                 epoch < 30
+ *                       50*(1 - epoch/90)^2                 otherwise
+ *   NoiseScale(epoch) = LR(epoch)*32*1024/(1 - 0.9)
+ *   Momentum(epoch)   = 1 - LR(epoch)*B/NoiseScale(epoch),  B = total mini-batch size
+ * rn50_sched_batch: per-worker and total mini-batch size of Table 3's experiments (0 = Reference, 1..4) at
+ * `epoch`; RN50_ERR_SHAPE for an unknown experiment or an epoch outside [0, 90].  Configuration A is not
+ * offered: the paper states only its warm-up (34 epochs from 1e-5 to 34.0) and refers elsewhere for the rest.
+ * ---------------------------------------------------------------------------------------- */
+double rn50_sched_lr_b(double epoch);
+double rn50_sched_noise_scale_b(double epoch);
+double rn50_sched_momentum_b(double epoch, double total_batch);
+int rn50_sched_batch(int experiment, double epoch, int* per_worker, int* total);
+
+/* ------------------------------------------------------------------------------------------
  * Whole iteration (Sec. 2 + Sec. 3.2) on a ResNet-50 v1.5 style network:
  *   [stem 7x7/2 conv 3->base_width, BN, ReLU, 3x3/2 max-pool]  (iff has_stem)
  *   num_stages stages of blocks[s] bottleneck blocks (1x1, 3x3, 1x1; widths w,w,4w with

@@ -74,6 +74,10 @@ _SIGNATURES = {
     "lars_plan_create": (_i, [ctypes.POINTER(_vp), ctypes.POINTER(rn50_lars_segment), _i, _vp, _sz]),
     "lars_plan_destroy": (None, [_vp]),
     "lars_momentum_flat": (_i, [_vp, _vp, _i, _f, _vp, _vp, _vp, _f, _f, _f, _f, _f, _vp, _vp]),
+    "rn50_sched_lr_b": (ctypes.c_double, [ctypes.c_double]),
+    "rn50_sched_noise_scale_b": (ctypes.c_double, [ctypes.c_double]),
+    "rn50_sched_momentum_b": (ctypes.c_double, [ctypes.c_double, ctypes.c_double]),
+    "rn50_sched_batch": (_i, [_i, ctypes.c_double, ctypes.POINTER(_i), ctypes.POINTER(_i)]),
     "rn50_param_count": (_sz, [ctypes.POINTER(rn50_config)]),
     "rn50_num_segments": (_i, [ctypes.POINTER(rn50_config)]),
     "rn50_param_layout": (_i, [ctypes.POINTER(rn50_config), _i, ctypes.POINTER(_sz), ctypes.POINTER(_sz),
@@ -196,6 +200,21 @@ def ls_xent_fwd_bwd(batch, classes, logits, labels, eps, grad_scale, loss_mean, 
 def sgd_momentum_flat(n, grad, grad_scale, master_w, momentum, w_lowp_out, lr, mu, wd, grad_dt=RN50_F16):
     _check(lib().sgd_momentum_flat(n, _ptr(grad), grad_dt, grad_scale, _ptr(master_w), _ptr(momentum),
                                    _ptr(w_lowp_out), lr, mu, wd, _stream()), "sgd_momentum_flat")
+
+
+def sched_lr_b(epoch):
+    return float(lib().rn50_sched_lr_b(float(epoch)))
+
+
+def sched_momentum_b(epoch, total_batch):
+    return float(lib().rn50_sched_momentum_b(float(epoch), float(total_batch)))
+
+
+def sched_batch(experiment, epoch):
+    """(per-worker, total) mini-batch size of Table 3's experiment at `epoch`."""
+    pw, tot = _i(), _i()
+    _check(lib().rn50_sched_batch(experiment, float(epoch), ctypes.byref(pw), ctypes.byref(tot)), "rn50_sched_batch")
+    return pw.value, tot.value
 
 
 class LarsPlan:

@@ -108,3 +108,18 @@ def test_lars_table_validation_without_a_gpu():
     assert l.lars_plan_create(None, good, n, fake, need) == -1                                          # RN50_ERR_NULL
     assert l.lars_momentum_flat(None, fake, 0, 1.0, fake, fake, None, 0.1, 0.9, 0.0, 0.01, 1e-6, None, None) == -1
     l.lars_plan_destroy(None)
+
+
+def test_schedule_functions_match_the_oracle():
+    from oracle import schedule as S
+    for e in np.linspace(0, 90, 361):
+        assert abs(P.sched_lr_b(e) - S.lr_b(e)) <= 1e-12 * max(1.0, S.lr_b(e))
+        if e < 90:
+            for b in (32768, 55296, 65536, 121856):
+                assert abs(P.sched_momentum_b(e, b) - S.momentum_b(e, b)) <= 1e-12
+        for x in range(5):
+            assert P.sched_batch(x, e) == S.batch(x, e)
+    assert abs(P.sched_momentum_b(90, 55296) - 0.83125) < 1e-12       # LR = 0: the constant ratio is used
+    for bad in [(5, 1.0), (-1, 1.0), (2, -0.5), (2, 90.5), (2, float("nan"))]:
+        with pytest.raises(P.Rn50Error):
+            P.sched_batch(*bad)

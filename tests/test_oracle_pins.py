@@ -417,6 +417,30 @@ def test_lars_worked_example_and_invariants():
     assert np.allclose(w32, w2, rtol=2e-6, atol=1e-7)
 
 
+def test_schedule_config_b_and_table3():
+    """Values worked by hand from the printed formulas of configuration B and read off Table 3."""
+    from oracle import schedule as S
+    assert S.lr_b(0) == 0.2 and abs(S.lr_b(2.5) - 14.6) < 1e-12            # 0.2 + 28.8/2
+    assert abs(S.lr_b(5) - 29 * (85 / 90) ** 2) < 1e-12                     # the warm-up ends just below 29
+    assert abs(S.lr_b(5 - 1e-9) - 29.0) < 1e-6                              # ... which the warm-up reaches
+    assert abs(S.lr_b(29.999999) - 29 * 4 / 9) < 1e-5 and abs(S.lr_b(30) - 50 * 4 / 9) < 1e-12   # base LR 29 -> 50 at epoch 30
+    assert abs(S.lr_b(45) - 12.5) < 1e-12 and S.lr_b(90) == 0.0            # 50 * (1/2)^2
+    assert abs(S.noise_scale_b(45) - 12.5 * 327680) < 1e-6                 # 32*1024/0.1 = 327680
+    # the learning rate cancels: Momentum = 1 - 0.1*B/32768; B = 32K reproduces the 0.9 the noise scale is built on
+    for e in (0.0, 3.0, 17.0, 60.0):
+        assert abs(S.momentum_b(e, 32 * 1024) - 0.9) < 1e-12
+        assert abs(S.momentum_b(e, 54 * 1024) - 0.83125) < 1e-12
+        assert abs(S.momentum_b(e, 64 * 1024) - 0.8) < 1e-12
+    assert S.batch(0, 10) == (32, 32768) and S.batch(0, 89) == (32, 32768)
+    assert S.batch(1, 29.9) == (16, 34816) and S.batch(1, 30) == (32, 69632)
+    assert S.batch(2, 0) == (16, 55296) and S.batch(2, 60) == (32, 55296)
+    assert S.batch(3, 29) == (16, 55296) and S.batch(3, 31) == (32, 65536)
+    assert [S.batch(4, e) for e in (0, 30, 44.9, 45, 74.9, 75, 90)] == [
+        (16, 34816), (16, 69632), (16, 69632), (32, 87040), (32, 87040), (32, 121856), (32, 121856)]
+    # 3456 workers x 16 = 54K, 2176 x 16 = 34K (the #GPUs column of the same table)
+    assert 3456 * 16 == S.batch(2, 0)[1] and 2176 * 16 == S.batch(1, 0)[1] and 2176 * 32 == S.batch(1, 40)[1]
+
+
 # ------------------------------------------------------------------ layout + whole step
 def test_flat_layout_counts():
     gold = golden()
