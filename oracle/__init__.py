@@ -131,6 +131,49 @@ def bn_relu_bwd(dy, x, y, gamma, mean, invstd, relu=True, want_dresidual=False):
     return dx, dres, dgamma, dbeta
 
 
+# ---- batch normalisation split at the points where GPUs would exchange statistics (Sec. 3.2: "the communication
+# to synchronize batch mean and batch squared mean was also conducted in FP32").  Plain numpy, double inside.
+def bn_moments(x):
+    """Per-channel (mean, mean of squares) over all rows of x [..., C]."""
+    x2 = np.asarray(x, np.float64).reshape(-1, x.shape[-1])
+    return x2.mean(axis=0).astype(x.dtype), (x2 * x2).mean(axis=0).astype(x.dtype)
+
+
+def bn_relu_fwd_from_moments(x, gamma, beta, mean, sqmean, eps=1e-5, relu=True, residual=None):
+    """y = gamma*(x-mean)*invstd + beta (+residual)(ReLU) with var = max(sqmean - mean^2, 0).  Returns y, invstd."""
+    f = np.float64
+    mean64, sq64 = np.asarray(mean, f), np.asarray(sqmean, f)
+    invstd = 1.0 / np.sqrt(np.maximum(sq64 - mean64 * mean64, 0.0) + eps)
+    y = np.asarray(gamma, f) * ((np.asarray(x, f) - mean64) * invstd) + np.asarray(beta, f)
+    if residual is not None:
+        y = y + np.asarray(residual, f)
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y.astype(x.dtype), invstd.astype(x.dtype)
+
+
+def bn_bwd_sums(dy, x, y, mean, invstd, relu=True):
+    """Per-channel (sum g, sum g*xhat) with g = dy*[y>0] if relu else dy."""
+    f = np.float64
+    c = x.shape[-1]
+    g = np.asarray(dy, f).reshape(-1, c)
+    if relu:
+        g = g * (np.asarray(y).reshape(-1, c) > 0)
+    xh = (np.asarray(x, f).reshape(-1, c) - np.asarray(mean, f)) * np.asarray(invstd, f)
+    return g.sum(axis=0).astype(x.dtype), (g * xh).sum(axis=0).astype(x.dtype)
+
+
+def bn_relu_bwd_from_sums(dy, x, y, gamma, mean, invstd, sum_g, sum_gxhat, total_rows, relu=True, want_dresidual=False):
+    """dx = gamma*invstd*(g - sum_g/M - xhat*sum_gxhat/M) with M = total_rows (rows of ALL participants)."""
+    f = np.float64
+    g = np.asarray(dy, f)
+    if relu:
+        g = g * (np.asarray(y) > 0)
+    xh = (np.asarray(x, f) - np.asarray(mean, f)) * np.asarray(invstd, f)
+    dx = np.asarray(gamma, f) * np.asarray(invstd, f) * (g - np.asarray(sum_g, f) / total_rows - xh * np.asarray(sum_gxhat, f) / total_rows)
+    return dx.astype(x.dtype), (g.astype(x.dtype) if want_dresidual else None)
+
+
 def maxpool_fwd(x, r=3, stride=2, pad=1):
     dt = x.dtype
     x = _c(x, dt)

@@ -329,6 +329,43 @@ def test_ls_xent_finite_differences():
             assert abs((lp - lm) / 2e-6 - dz[i, j]) < 1e-8
 
 
+def test_bn_split_at_the_exchange_points_equals_whole_batch_bn():
+    """Two "GPUs" with different local batches: averaging their (mean, mean of squares) weighted by rows and
+    applying from those moments must reproduce batch norm over the union; adding their backward sums must
+    reproduce its backward pass (both already pinned above)."""
+    c = 16
+    xa, xb = RNG.standard_normal((3, 5, 4, c)) * 2 + 1, RNG.standard_normal((2, 5, 4, c)) - 0.5
+    gamma, beta = RNG.standard_normal(c), RNG.standard_normal(c)
+    res = RNG.standard_normal((5, 5, 4, c))
+    x = np.concatenate([xa, xb])
+    y, mean, invstd, sqmean = O.bn_relu_fwd(x, gamma, beta, 1e-5, True, res)
+    ma, qa = O.bn_moments(xa)
+    mb, qb = O.bn_moments(xb)
+    na, nb = xa.size // c, xb.size // c
+    m_all, q_all = (ma * na + mb * nb) / (na + nb), (qa * na + qb * nb) / (na + nb)
+    assert np.allclose(m_all, mean, rtol=1e-12, atol=1e-14) and np.allclose(q_all, sqmean, rtol=1e-12)
+    ya, inv_a = O.bn_relu_fwd_from_moments(xa, gamma, beta, m_all, q_all, 1e-5, True, res[:3])
+    yb, _ = O.bn_relu_fwd_from_moments(xb, gamma, beta, m_all, q_all, 1e-5, True, res[3:])
+    assert np.allclose(np.concatenate([ya, yb]), y, rtol=1e-10, atol=1e-12) and np.allclose(inv_a, invstd, rtol=1e-10)
+    dy = RNG.standard_normal(x.shape)
+    dx, dres, dgamma, dbeta = O.bn_relu_bwd(dy, x, y, gamma, mean, invstd, True, True)
+    sa = O.bn_bwd_sums(dy[:3], xa, y[:3], mean, invstd, True)
+    sb = O.bn_bwd_sums(dy[3:], xb, y[3:], mean, invstd, True)
+    sg, sgx = sa[0] + sb[0], sa[1] + sb[1]
+    assert np.allclose(sg, dbeta, rtol=1e-10, atol=1e-12) and np.allclose(sgx, dgamma, rtol=1e-10, atol=1e-12)
+    dxa, dra = O.bn_relu_bwd_from_sums(dy[:3], xa, y[:3], gamma, mean, invstd, sg, sgx, na + nb, True, True)
+    dxb, drb = O.bn_relu_bwd_from_sums(dy[3:], xb, y[3:], gamma, mean, invstd, sg, sgx, na + nb, True, True)
+    assert np.allclose(np.concatenate([dxa, dxb]), dx, rtol=1e-9, atol=1e-11)
+    assert np.array_equal(np.concatenate([dra, drb]), dres)
+    # without ReLU and residual
+    y2, mean2, invstd2, _ = O.bn_relu_fwd(x, gamma, beta, 1e-5, False)
+    ya2, _ = O.bn_relu_fwd_from_moments(xa, gamma, beta, m_all, q_all, 1e-5, False)
+    assert np.allclose(ya2, y2[:3], rtol=1e-10, atol=1e-12)
+    dx2 = O.bn_relu_bwd(dy, x, y2, gamma, mean2, invstd2, False)[0]
+    s2 = O.bn_bwd_sums(dy, x, y2, mean2, invstd2, False)
+    assert np.allclose(O.bn_relu_bwd_from_sums(dy, x, y2, gamma, mean2, invstd2, s2[0], s2[1], na + nb, False)[0], dx2, rtol=1e-9, atol=1e-11)
+
+
 # ------------------------------------------------------------------ update
 def test_sgd_closed_forms():
     n = 1000
