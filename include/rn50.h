@@ -110,6 +110,29 @@ int bn_relu_bwd(const bn_desc* d, const void* dy, const void* x, const void* y /
                 void* dx, void* dresidual /* NULL unless has_residual */, void* dgamma, void* dbeta,
                 void* ws, size_t ws_bytes, void* stream);
 
+/* The same two operators split at the points where GPUs exchange statistics (Sec. 3.2: batch mean and
+ * batch squared mean are synchronised in FP32): every GPU computes its local moments / sums, the caller
+ * combines them across GPUs (row-weighted average of the moments, sum of the backward sums), and every GPU
+ * applies with the combined values.
+ *   bn_batch_moments:          moments[0..c) = E[x], moments[c..2c) = E[x^2] over this GPU's m rows
+ *   bn_relu_fwd_from_moments:  bn_relu_fwd with mean = moments[0..c), var = max(moments[c..2c) - mean^2, 0);
+ *                              also writes save_mean / save_invstd for the backward pass
+ *   bn_relu_bwd_sums:          sums[0..c) = sum g, sums[c..2c) = sum g*xhat over this GPU's rows (g as above)
+ *   bn_relu_bwd_from_sums:     dx = gamma*invstd*(g - sums[0..c)/M - xhat*sums[c..2c)/M), M = total_rows over all
+ *                              GPUs (>= m, else RN50_ERR_SHAPE); dresidual = g.  d gamma / d beta are the
+ *                              combined sums themselves.
+ * moments, sums: float [2c], device.  ws: bn_workspace_bytes(d). */
+int bn_batch_moments(const bn_desc* d, const void* x, float* moments, void* ws, size_t ws_bytes, void* stream);
+int bn_relu_fwd_from_moments(const bn_desc* d, const void* x, const float* gamma, const float* beta,
+                             const void* residual /* NULL unless has_residual */, void* y, const float* moments,
+                             float* save_mean, float* save_invstd, void* stream);
+int bn_relu_bwd_sums(const bn_desc* d, const void* dy, const void* x, const void* y /* NULL unless relu */,
+                     const float* save_mean, const float* save_invstd, float* sums, void* ws, size_t ws_bytes,
+                     void* stream);
+int bn_relu_bwd_from_sums(const bn_desc* d, const void* dy, const void* x, const void* y /* NULL unless relu */,
+                          const float* gamma, const float* save_mean, const float* save_invstd, const float* sums,
+                          long long total_rows, void* dx, void* dresidual /* NULL unless has_residual */, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Softmax cross-entropy with label smoothing (Sec. 2.1).  Target q = (1-eps)*onehot + eps/K.
  *   l_i = -sum_k q_k log softmax(logits_i)_k ; *loss_mean = mean_i l_i

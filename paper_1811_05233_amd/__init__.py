@@ -68,6 +68,10 @@ _SIGNATURES = {
     "bn_workspace_bytes": (_sz, [ctypes.POINTER(bn_desc)]),
     "bn_relu_fwd": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_relu_bwd": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_batch_moments": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _sz, _vp]),
+    "bn_relu_fwd_from_moments": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "bn_relu_bwd_sums": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_relu_bwd_from_sums": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_longlong, _vp, _vp, _vp]),
     "ls_xent_fwd_bwd": (_i, [_i, _i, _vp, _vp, _f, _f, _vp, _vp, _vp, _i, _vp]),
     "sgd_momentum_flat": (_i, [_sz, _vp, _i, _f, _vp, _vp, _vp, _f, _f, _f, _vp]),
     "lars_workspace_bytes": (_sz, [ctypes.POINTER(rn50_lars_segment), _i]),
@@ -188,6 +192,32 @@ def bn_relu_bwd(d, dy, x, y, gamma, save_mean, save_invstd, dx, dresidual, dgamm
     _check(lib().bn_relu_bwd(ctypes.byref(d), _ptr(dy), _ptr(x), _ptr(y), _ptr(gamma), _ptr(save_mean),
                              _ptr(save_invstd), _ptr(dx), _ptr(dresidual), _ptr(dgamma), _ptr(dbeta),
                              _ptr(ws), ws.numel(), _stream()), "bn_relu_bwd")
+    return dx
+
+
+def bn_batch_moments(d, x, moments, ws=None):
+    ws = ws if ws is not None else _ws(bn_workspace_bytes(d), x)
+    _check(lib().bn_batch_moments(ctypes.byref(d), _ptr(x), _ptr(moments), _ptr(ws), ws.numel(), _stream()), "bn_batch_moments")
+    return moments
+
+
+def bn_relu_fwd_from_moments(d, x, gamma, beta, residual, y, moments, save_mean, save_invstd):
+    _check(lib().bn_relu_fwd_from_moments(ctypes.byref(d), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(residual), _ptr(y),
+                                          _ptr(moments), _ptr(save_mean), _ptr(save_invstd), _stream()), "bn_relu_fwd_from_moments")
+    return y
+
+
+def bn_relu_bwd_sums(d, dy, x, y, save_mean, save_invstd, sums, ws=None):
+    ws = ws if ws is not None else _ws(bn_workspace_bytes(d), x)
+    _check(lib().bn_relu_bwd_sums(ctypes.byref(d), _ptr(dy), _ptr(x), _ptr(y), _ptr(save_mean), _ptr(save_invstd), _ptr(sums),
+                                  _ptr(ws), ws.numel(), _stream()), "bn_relu_bwd_sums")
+    return sums
+
+
+def bn_relu_bwd_from_sums(d, dy, x, y, gamma, save_mean, save_invstd, sums, total_rows, dx, dresidual):
+    _check(lib().bn_relu_bwd_from_sums(ctypes.byref(d), _ptr(dy), _ptr(x), _ptr(y), _ptr(gamma), _ptr(save_mean),
+                                       _ptr(save_invstd), _ptr(sums), int(total_rows), _ptr(dx), _ptr(dresidual), _stream()),
+           "bn_relu_bwd_from_sums")
     return dx
 
 

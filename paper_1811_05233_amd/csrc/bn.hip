@@ -112,6 +112,7 @@ __global__ __launch_bounds__(kThreads) void bn_stats_kernel(long long m, int c, 
 //                      pivot_row: first row of x, or nullptr for pivot 0
 //   kMode 1 (backward): partials are sum g, sum g*xhat -> sums[0..c) = d beta, sums[c..2c) = d gamma, plus the
 //                      optional half / float copies
+//   kMode 2 (moments):  as kMode 0 but out0[0..c) = mean, out0[c..2c) = mean of squares (what GPUs exchange)
 template <int kMode, int kNT>
 __global__ __launch_bounds__(kNT) void bn_finalize_kernel(long long m, int c, float eps, int nblk,
                                                           const h16* __restrict__ pivot_row,
@@ -167,6 +168,12 @@ __global__ __launch_bounds__(kNT) void bn_finalize_kernel(long long m, int c, fl
             if (var < 0.0) var = 0.0;
             out0[ch] = (float)(pivot + md);
             out1[ch] = (float)(1.0 / sqrt(var + (double)eps));
+        } else if (kMode == 2) {
+            // E[x] = p + E[x-p];  E[x^2] = E[(x-p)^2] + 2p E[x-p] + p^2
+            const double pivot = pivot_row ? (double)(float)pivot_row[ch] : 0.0;
+            const double md = sa / (double)m;
+            out0[ch] = (float)(pivot + md);
+            out0[c + ch] = (float)(sb / (double)m + 2.0 * pivot * md + pivot * pivot);
         } else {
             out0[ch] = (float)sa;
             out0[c + ch] = (float)sb;
@@ -323,7 +330,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(long long m, int
                                                                 const float* __restrict__ invstd,
                                                                 const float* __restrict__ sums,
                                                                 h16* __restrict__ dx, h16* __restrict__ dres,
-                                                                int rows_per_block)
+                                                                int rows_per_block, float inv_m)
 {
     const RowMap rm = make_rowmap(c);
     const int tid = threadIdx.x;
@@ -331,7 +338,6 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(long long m, int
     const long long row0 = (long long)blockIdx.x * rows_per_block;
     long long row1 = row0 + rows_per_block;
     if (row1 > m) row1 = m;
-    const float inv_m = 1.f / (float)m;
     const int rp = rm.rows_par;
     for (int cg = cgl; cg < rm.gp; cg += rm.gpb) {
         float mu[8], is[8], sc[8], mb[8], mg[8];
@@ -527,6 +533,20 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_fused_apply_kernel(long long 
     }
 }
 
+// (mean, mean of squares) -> (mean, 1/sqrt(var + eps)) with var = max(E[x^2] - mean^2, 0), in double
+__global__ __launch_bounds__(kThreads) void bn_moments_to_stats_kernel(int c, float eps, const float* __restrict__ moments,
+                                                                       float* __restrict__ save_mean,
+                                                                       float* __restrict__ save_invstd)
+{
+    const int ch = blockIdx.x * kThreads + threadIdx.x;
+    if (ch >= c) return;
+    const double mean = (double)moments[ch];
+    double var = (double)moments[c + ch] - mean * mean;
+    if (var < 0.0) var = 0.0;
+    save_mean[ch] = (float)mean;
+    save_invstd[ch] = (float)(1.0 / sqrt(var + (double)eps));
+}
+
 struct BnPlan { int nblk; int rows_per_block; };
 
 // Elementwise passes: 4 rows per thread (one unrolled batch), as many workgroups as that takes.
@@ -653,7 +673,7 @@ int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* 
     ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, ((relu ? 6.0 : 4.0) + 2.0 + (dres ? 2.0 : 0.0)) * elems, s);
     const BnPlan pa = plan_rows_apply(m, c);
 #define RN50_BN_BWD(R, Z) bn_bwd_apply_kernel<R, Z><<<pa.nblk, kThreads, 0, s>>>(m, c, dy, x, y, gamma, save_mean, \
-                                                                                 save_invstd, sums, dx, dres, pa.rows_per_block)
+                                                                                 save_invstd, sums, dx, dres, pa.rows_per_block, 1.f / (float)m)
     if (relu) { if (dres) RN50_BN_BWD(true, true); else RN50_BN_BWD(true, false); }
     else      { if (dres) RN50_BN_BWD(false, true); else RN50_BN_BWD(false, false); }
 #undef RN50_BN_BWD
@@ -682,7 +702,7 @@ int rn50_bn_bwd_from_partials_launch(long long m, int c, const h16* g, const h16
     ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, 6.0 * elems, s);
     const BnPlan pa = plan_rows_apply(m, c);
     bn_bwd_apply_kernel<false, false><<<pa.nblk, kThreads, 0, s>>>(m, c, g, x, nullptr, gamma, save_mean, save_invstd,
-                                                                   sums, dx, nullptr, pa.rows_per_block);
+                                                                   sums, dx, nullptr, pa.rows_per_block, 1.f / (float)m);
     return rn50_check_launch();
 }
 
@@ -718,4 +738,102 @@ extern "C" int bn_relu_bwd(const bn_desc* d, const void* dy, const void* x, cons
                               d->has_residual ? static_cast<h16*>(dresidual) : nullptr, static_cast<h16*>(dgamma),
                               static_cast<h16*>(dbeta), nullptr, nullptr, static_cast<float*>(ws),
                               static_cast<hipStream_t>(stream));
+}
+
+
+// ---- the same operators split at the points where GPUs exchange statistics (synchronised BN) ----
+extern "C" int bn_batch_moments(const bn_desc* d, const void* x, float* moments, void* ws, size_t ws_bytes, void* stream)
+{
+    RN50_TRY(validate(d));
+    RN50_REQUIRE_PTR(x); RN50_REQUIRE_PTR(moments);
+    if (!ws || ws_bytes < bn_workspace_bytes(d)) return RN50_ERR_WORKSPACE;
+    RN50_REQUIRE_ALIGNED(x); RN50_REQUIRE_ALIGNED(ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const BnPlan p = plan_rows(d->m, d->c);
+    const h16* xh = static_cast<const h16*>(x);
+    float* part = static_cast<float*>(ws);
+    {
+        ProfScope ps(RN50_K_BN_STATS, 0.0, 2.0 * (double)d->m * d->c, s);
+        bn_stats_kernel<<<p.nblk, kThreads, 0, s>>>(d->m, d->c, xh, part, p.rows_per_block);
+    }
+    ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * p.nblk * d->c, s);
+    launch_bn_finalize<2>(d->m, d->c, 0.f, p.nblk, xh, part, moments, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    return rn50_check_launch();
+}
+
+extern "C" int bn_relu_fwd_from_moments(const bn_desc* d, const void* x, const float* gamma, const float* beta,
+                                        const void* residual, void* y, const float* moments, float* save_mean,
+                                        float* save_invstd, void* stream)
+{
+    RN50_TRY(validate(d));
+    RN50_REQUIRE_PTR(x); RN50_REQUIRE_PTR(gamma); RN50_REQUIRE_PTR(beta); RN50_REQUIRE_PTR(y); RN50_REQUIRE_PTR(moments);
+    RN50_REQUIRE_PTR(save_mean); RN50_REQUIRE_PTR(save_invstd);
+    if (d->has_residual) RN50_REQUIRE_PTR(residual);
+    RN50_REQUIRE_ALIGNED(x); RN50_REQUIRE_ALIGNED(y); RN50_REQUIRE_ALIGNED(residual);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const long long m = d->m;
+    const int c = d->c;
+    bn_moments_to_stats_kernel<<<rn50_cdiv(c, kThreads), kThreads, 0, s>>>(c, d->eps, moments, save_mean, save_invstd);
+    RN50_TRY(rn50_check_launch());
+    const h16* res = d->has_residual ? static_cast<const h16*>(residual) : nullptr;
+    ProfScope ps(RN50_K_BN_APPLY, 0.0, (res ? 6.0 : 4.0) * (double)m * c, s);
+    const BnPlan pa = plan_rows_apply(m, c);
+#define RN50_BN_APPLY(R, Z) bn_apply_kernel<R, Z><<<pa.nblk, kThreads, 0, s>>>(m, c, static_cast<const h16*>(x), gamma, beta, \
+                                                                               save_mean, save_invstd, res, static_cast<h16*>(y), \
+                                                                               pa.rows_per_block)
+    if (d->relu) { if (res) RN50_BN_APPLY(true, true); else RN50_BN_APPLY(true, false); }
+    else         { if (res) RN50_BN_APPLY(false, true); else RN50_BN_APPLY(false, false); }
+#undef RN50_BN_APPLY
+    return rn50_check_launch();
+}
+
+extern "C" int bn_relu_bwd_sums(const bn_desc* d, const void* dy, const void* x, const void* y, const float* save_mean,
+                                const float* save_invstd, float* sums, void* ws, size_t ws_bytes, void* stream)
+{
+    RN50_TRY(validate(d));
+    RN50_REQUIRE_PTR(dy); RN50_REQUIRE_PTR(x); RN50_REQUIRE_PTR(save_mean); RN50_REQUIRE_PTR(save_invstd); RN50_REQUIRE_PTR(sums);
+    if (d->relu) RN50_REQUIRE_PTR(y);
+    if (!ws || ws_bytes < bn_workspace_bytes(d)) return RN50_ERR_WORKSPACE;
+    RN50_REQUIRE_ALIGNED(dy); RN50_REQUIRE_ALIGNED(x); RN50_REQUIRE_ALIGNED(y); RN50_REQUIRE_ALIGNED(ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const long long m = d->m;
+    const int c = d->c;
+    const BnPlan p = plan_rows(m, c);
+    float* part = static_cast<float*>(ws);
+    const h16 *dyh = static_cast<const h16*>(dy), *xh = static_cast<const h16*>(x), *yh = static_cast<const h16*>(y);
+    {
+        ProfScope ps(RN50_K_BN_BWD_REDUCE, 0.0, (d->relu ? 6.0 : 4.0) * (double)m * c, s);
+        if (d->relu) bn_bwd_reduce_kernel<true><<<p.nblk, kThreads, 0, s>>>(m, c, dyh, xh, yh, save_mean, save_invstd, part, p.rows_per_block);
+        else         bn_bwd_reduce_kernel<false><<<p.nblk, kThreads, 0, s>>>(m, c, dyh, xh, yh, save_mean, save_invstd, part, p.rows_per_block);
+    }
+    ProfScope ps(RN50_K_BN_BWD_FINALIZE, 0.0, 8.0 * p.nblk * c, s);
+    launch_bn_finalize<1>(m, c, 0.f, p.nblk, nullptr, part, sums, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    return rn50_check_launch();
+}
+
+extern "C" int bn_relu_bwd_from_sums(const bn_desc* d, const void* dy, const void* x, const void* y, const float* gamma,
+                                     const float* save_mean, const float* save_invstd, const float* sums,
+                                     long long total_rows, void* dx, void* dresidual, void* stream)
+{
+    RN50_TRY(validate(d));
+    RN50_REQUIRE_PTR(dy); RN50_REQUIRE_PTR(x); RN50_REQUIRE_PTR(gamma); RN50_REQUIRE_PTR(save_mean);
+    RN50_REQUIRE_PTR(save_invstd); RN50_REQUIRE_PTR(sums); RN50_REQUIRE_PTR(dx);
+    if (d->relu) RN50_REQUIRE_PTR(y);
+    if (d->has_residual) RN50_REQUIRE_PTR(dresidual);
+    if (total_rows < d->m) return RN50_ERR_SHAPE;
+    RN50_REQUIRE_ALIGNED(dy); RN50_REQUIRE_ALIGNED(x); RN50_REQUIRE_ALIGNED(y); RN50_REQUIRE_ALIGNED(dx); RN50_REQUIRE_ALIGNED(dresidual);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const long long m = d->m;
+    const int c = d->c;
+    h16* dres = d->has_residual ? static_cast<h16*>(dresidual) : nullptr;
+    ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, ((d->relu ? 6.0 : 4.0) + 2.0 + (dres ? 2.0 : 0.0)) * (double)m * c, s);
+    const BnPlan pa = plan_rows_apply(m, c);
+    const float inv_m = (float)(1.0 / (double)total_rows);
+#define RN50_BN_BWD(R, Z) bn_bwd_apply_kernel<R, Z><<<pa.nblk, kThreads, 0, s>>>(m, c, static_cast<const h16*>(dy), \
+        static_cast<const h16*>(x), static_cast<const h16*>(y), gamma, save_mean, save_invstd, sums, static_cast<h16*>(dx), dres, \
+        pa.rows_per_block, inv_m)
+    if (d->relu) { if (dres) RN50_BN_BWD(true, true); else RN50_BN_BWD(true, false); }
+    else         { if (dres) RN50_BN_BWD(false, true); else RN50_BN_BWD(false, false); }
+#undef RN50_BN_BWD
+    return rn50_check_launch();
 }

@@ -256,6 +256,74 @@ def test_bn_relu_fwd_bwd(m, c, relu, res):
         assert np.array_equal(host(dres), rdres)          # pure masking of FP16 values: exact
 
 
+@pytest.mark.parametrize("m_a,m_b,c,relu,res", [(700, 324, 64, True, True), (2 * 28 * 28, 3 * 28 * 28, 128, True, False),
+                                                 (5, 3000, 512, False, False), (1, 1, 8, True, False)])
+def test_bn_split_at_exchange_points_two_way(m_a, m_b, c, relu, res):
+    """Synchronised batch norm built from the four split entry points: two local batches ("two GPUs"), moments
+    averaged by rows and backward sums added on the host, must match the oracle's batch norm over the union."""
+    _progress("bn split m=%d+%d c=%d relu=%d res=%d" % (m_a, m_b, c, relu, res))
+    m = m_a + m_b
+    x = synth.normal_f16(620, (m, c)) * 1.5
+    x = (x + synth.normal_f32(621, (c,), 0.7)).astype(np.float16).astype(np.float32)
+    x[m_a:] += np.float32(0.5)                                  # the two halves have different statistics
+    x = x.astype(np.float16).astype(np.float32)
+    gamma, beta = 1.0 + synth.normal_f32(622, (c,), 0.2), synth.normal_f32(623, (c,), 0.3)
+    r = synth.normal_f16(624, (m, c)) if res else None
+    dy = synth.normal_f16(625, (m, c), 0.05)
+    f64 = np.float64
+    ry, rmean, rinv, rsq = O.bn_relu_fwd(x.astype(f64), gamma.astype(f64), beta.astype(f64), 1e-5, relu, r.astype(f64) if res else None)
+    parts = [(0, m_a), (m_a, m)]
+    gd, bd = dev_f(gamma), dev_f(beta)
+    descs, xs, moms = [], [], []
+    for lo, hi in parts:
+        d = P.make_bn_desc(hi - lo, c, 1e-5, relu, res)
+        xd = dev_h(x[lo:hi])
+        mom = torch.zeros(2 * c, dtype=torch.float32, device=DEV)
+        P.bn_batch_moments(d, xd, mom)
+        ma, qa = O.bn_moments(x[lo:hi].astype(f64))
+        assert np.max(np.abs(host(mom)[:c] - ma)) <= 1e-5 * max(1.0, np.max(np.abs(ma)))
+        assert rel_err_fp32(host(mom)[c:], qa) <= 1e-5
+        descs.append(d); xs.append(xd); moms.append(host(mom))
+    comb = (moms[0] * m_a + moms[1] * m_b) / m                                 # what an all-reduce would deliver
+    assert np.max(np.abs(comb[:c] - rmean)) <= 1e-5 * max(1.0, np.max(np.abs(rmean))) and rel_err_fp32(comb[c:], rsq) <= 1e-5
+    combd = dev_f(comb.astype(np.float32))
+    ys, means, invs = [], [], []
+    for (lo, hi), d, xd in zip(parts, descs, xs):
+        y = torch.zeros(hi - lo, c, dtype=torch.float16, device=DEV)
+        mean, inv = torch.zeros(c, dtype=torch.float32, device=DEV), torch.zeros(c, dtype=torch.float32, device=DEV)
+        P.bn_relu_fwd_from_moments(d, xd, gd, bd, dev_h(r[lo:hi]) if res else None, y, combd, mean, inv)
+        ys.append(host(y)); means.append(mean); invs.append(inv)
+    if m > 2:
+        assert rel_err_fp32(host(invs[0]), rinv) <= 1e-4
+        assert rel_err(np.concatenate(ys), ry) <= TOL16
+    # backward with the oracle's rounded forward output and statistics
+    y16 = O.round_binary16(ry)
+    m32, i32 = rmean.astype(np.float32), rinv.astype(np.float32)
+    rdx, rdres, rdg, rdb = O.bn_relu_bwd(dy.astype(f64), x.astype(f64), y16, gamma.astype(f64), m32.astype(f64), i32.astype(f64), relu, res)
+    md, idv = dev_f(m32), dev_f(i32)
+    sums = []
+    for (lo, hi), d, xd in zip(parts, descs, xs):
+        sm = torch.zeros(2 * c, dtype=torch.float32, device=DEV)
+        P.bn_relu_bwd_sums(d, dev_h(dy[lo:hi]), xd, dev_h(y16[lo:hi]) if relu else None, md, idv, sm)
+        sums.append(host(sm))
+    tot = sums[0] + sums[1]
+    assert rel_err_fp32(tot[:c], rdb, 1e-3) <= 1e-4 and rel_err_fp32(tot[c:], rdg, 1e-3) <= 1e-4
+    totd = dev_f(tot.astype(np.float32))
+    dxs, drs = [], []
+    for (lo, hi), d, xd in zip(parts, descs, xs):
+        dx = torch.zeros(hi - lo, c, dtype=torch.float16, device=DEV)
+        dres = torch.zeros(hi - lo, c, dtype=torch.float16, device=DEV) if res else None
+        P.bn_relu_bwd_from_sums(d, dev_h(dy[lo:hi]), xd, dev_h(y16[lo:hi]) if relu else None, gd, md, idv, totd, m, dx, dres)
+        dxs.append(host(dx)); drs.append(host(dres) if res else None)
+    assert rel_err(np.concatenate(dxs), rdx) <= TOL16
+    if res:
+        assert np.array_equal(np.concatenate(drs), rdres)
+    with pytest.raises(P.Rn50Error):                                   # the total row count cannot be below the local one
+        P.bn_relu_bwd_from_sums(descs[1], dev_h(dy[m_a:]), xs[1], dev_h(y16[m_a:]) if relu else None, gd, md, idv, totd, m_b - 1,
+                                torch.zeros(m_b, c, dtype=torch.float16, device=DEV),
+                                torch.zeros(m_b, c, dtype=torch.float16, device=DEV) if res else None)
+
+
 def test_bn_large_mean_channel_and_determinism():
     m, c = 5000, 64
     x = synth.normal_f16(610, (m, c))
