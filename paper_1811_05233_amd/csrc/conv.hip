@@ -52,6 +52,127 @@ __device__ __forceinline__ void fast_divmod(int m, int d, float inv_d, int& q, i
     else if (r >= d) { r -= d; ++q; }
 }
 
+// Accumulator start: zero, or the addend at the tile's output positions (out = addend + A*B, rounded once).
+// row_pix(row, n, oh, ow) -> bool maps a tile row to its output pixel (false: the row is outside the tensor).
+template <int BN, int TM, int TN, class RowPix>
+__device__ __forceinline__ void gather_init_acc(const GatherArgs& a, f32x16 (&acc)[TM][TN], int wm0, int wn0, int li, int lg,
+                                                int nt, RowPix row_pix)
+{
+    if (a.addend) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            int n, oh, ow;
+            bool ok = row_pix(wm0 + tm * 32 + li, n, oh, ow);
+            size_t opix = 0;
+            if (ok) {
+                if (a.add_sub) {
+                    ok = ((oh | ow) & 1) == 0;
+                    opix = ((size_t)n * a.add_h + (oh >> 1)) * a.add_w + (ow >> 1);
+                } else {
+                    opix = ((size_t)n * a.OH + oh) * a.OW + ow;
+                }
+            }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    h16x4 v = {0, 0, 0, 0};
+                    if (ok) v = *reinterpret_cast<const h16x4*>(a.addend + opix * a.NO + nt * BN + wn0 + tn * 32 + q * 8 + lg * 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[tm][tn][q * 4 + e] = (float)v[e];
+                }
+        }
+    } else {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+    }
+}
+
+// Epilogue: FP32 -> half, through LDS so that global stores are full 16-byte rows, plus the optional per-channel
+// sums over the tile's rows.  Forward: sum and sum of squares of the stored halves (BN statistics of the layer that
+// follows).  Data gradient with bn_x set: the stored gradient g is first masked by the ReLU of the tensor it belongs
+// to (mask_y), then sum g and sum g*xhat are formed for the backward pass of the BN that produced that tensor.
+// The caller has made sure that no wave still reads the part of LDS used here.  tile_row: index of the row tile
+// (first index of the partial sums).
+template <int BM, int BN, int TM, int TN, int LDS_HALFS, class RowPix>
+__device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f32x16 (&acc)[TM][TN], int wm0, int wn0, int li,
+                                                int lg, int tid, int nt, int tile_row, RowPix row_pix)
+{
+    constexpr int EP = BN + 8;                   // row pitch of the staged tile in halfs
+    constexpr int OCPR = BN / 8;                 // output chunks per row
+    constexpr int ORPP = kThreads / OCPR;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                h16x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = (h16)acc[tm][tn][q * 4 + e];
+                *reinterpret_cast<h16x4*>(lds + (wm0 + tm * 32 + li) * EP + wn0 + tn * 32 + q * 8 + lg * 4) = v;
+            }
+    __syncthreads();
+    const int oc = tid % OCPR, orl = tid / OCPR;
+    float st[16], mu[8], is[8];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) st[j] = 0.f;
+    const bool bwd_stats = a.bn_x != nullptr;
+    if (bwd_stats) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { mu[j] = a.bn_mean[nt * BN + oc * 8 + j]; is[j] = a.bn_invstd[nt * BN + oc * 8 + j]; }
+    }
+#pragma unroll
+    for (int i = 0; i < BM / ORPP; ++i) {
+        const int row = orl + i * ORPP;
+        int n, oh, ow;
+        if (row_pix(row, n, oh, ow)) {
+            const size_t opix = ((size_t)n * a.OH + oh) * a.OW + ow;
+            const size_t gidx = opix * a.NO + nt * BN + oc * 8;
+            h16x8 v = *reinterpret_cast<const h16x8*>(lds + row * EP + oc * 8);
+            if (a.mask_y) {
+                const h16x8 yv = *reinterpret_cast<const h16x8*>(a.mask_y + gidx);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = (float)yv[j] > 0.f ? v[j] : (h16)0.f;
+            }
+            *reinterpret_cast<h16x8*>(a.out + gidx) = v;
+            if (bwd_stats) {
+                const h16x8 xv = *reinterpret_cast<const h16x8*>(a.bn_x + gidx);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float g = (float)v[j];
+                    st[j] += g;
+                    st[8 + j] += g * (((float)xv[j] - mu[j]) * is[j]);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) { const float f = (float)v[j]; st[j] += f; st[8 + j] += f * f; }
+            }
+        }
+    }
+    if (a.stats_part) {
+        // per-channel sums of this row tile, added in a fixed order: [tile][first | second sum][channel]
+        float* red = reinterpret_cast<float*>(lds + BM * EP);          // ORPP x 2 x BN floats behind the staged tile
+        static_assert(BM * EP * 2 + ORPP * 2 * BN * 4 <= LDS_HALFS * 2, "statistics scratch must fit in LDS");
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            red[(orl * 2 + 0) * BN + oc * 8 + j] = st[j];
+            red[(orl * 2 + 1) * BN + oc * 8 + j] = st[8 + j];
+        }
+        __syncthreads();
+        if (tid < 2 * BN) {
+            const int which = tid / BN, col = tid % BN;
+            float sum = 0.f;
+            for (int r = 0; r < ORPP; ++r) sum += red[(r * 2 + which) * BN + col];
+            a.stats_part[((size_t)tile_row * 2 + which) * a.NO + nt * BN + col] = sum;
+        }
+    }
+}
+
 // K-slabs travel global memory -> LDS directly (buffer_load ... lds, 16 bytes per lane, no staging
 // registers) into a ring of NST stages, so that NST-1 slabs are in flight while one is consumed.
 // Rows outside the image (zero padding, ragged last tile) use an out-of-range buffer offset, which
@@ -67,7 +188,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
     constexpr int KS = BK / 16;
     constexpr int STAGE = (BM + BN) * BK;
-    constexpr int EP = BN + 8;             // epilogue row pitch in halfs
+    constexpr int EP = BN + 8;             // epilogue row pitch in halfs (see gather_epilogue)
     constexpr int EPI_HALFS = BM * EP + (kThreads / (BN / 8)) * 2 * BN * 2;   // staged tile + statistics scratch (floats)
     constexpr int LDS_HALFS = (NST * STAGE > EPI_HALFS) ? NST * STAGE : EPI_HALFS;
     constexpr unsigned kOutOfRange = 0x80000000u;
@@ -157,44 +278,19 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     for (int p = 0; p < NST - 1; ++p)
         if (p < kiters) issue_slab();
 
+    // tile row -> output pixel
+    auto row_pix = [&](int row, int& n, int& oh, int& ow) -> bool {
+        const int m = mt * BM + row;
+        if (m >= M) return false;
+        int t, wq, hq;
+        fast_divmod(m, OWs, inv_ow, t, wq);
+        fast_divmod(t, OHs, inv_oh, n, hq);
+        oh = hq * a.o_mul + a.oph[cls];
+        ow = wq * a.o_mul + a.opw[cls];
+        return true;
+    };
     f32x16 acc[TM][TN];
-    if (a.addend) {
-        // accumulators start from the addend (out = addend + A*B, rounded once)
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            const int m = mt * BM + wm0 + tm * 32 + li;
-            size_t opix = 0;
-            bool ok = m < M;
-            if (ok) {
-                int t, wq, n, hq;
-                fast_divmod(m, OWs, inv_ow, t, wq);
-                fast_divmod(t, OHs, inv_oh, n, hq);
-                const int oh = hq * a.o_mul + a.oph[cls], ow = wq * a.o_mul + a.opw[cls];
-                if (a.add_sub) {
-                    ok = ((oh | ow) & 1) == 0;
-                    opix = ((size_t)n * a.add_h + (oh >> 1)) * a.add_w + (ow >> 1);
-                } else {
-                    opix = ((size_t)n * a.OH + oh) * a.OW + ow;
-                }
-            }
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    h16x4 v = {0, 0, 0, 0};
-                    if (ok) v = *reinterpret_cast<const h16x4*>(a.addend + opix * a.NO + nt * BN + wn0 + tn * 32 + q * 8 + lg * 4);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[tm][tn][q * 4 + e] = (float)v[e];
-                }
-        }
-    } else {
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
-    }
+    gather_init_acc<BN>(a, acc, wm0, wn0, li, lg, nt, row_pix);
 
     int cur = 0;
     for (int kit = 0; kit < kiters; ++kit) {
@@ -228,82 +324,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     RN50_WAIT_LGKMCNT0();
     __builtin_amdgcn_s_barrier();             // all waves are done reading the ring before it is reused
 
-    // ---- epilogue: FP32 -> half, through LDS so that global stores are full 16-byte rows ----
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                h16x4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (h16)acc[tm][tn][q * 4 + e];
-                *reinterpret_cast<h16x4*>(lds + (wm0 + tm * 32 + li) * EP + wn0 + tn * 32 + q * 8 + lg * 4) = v;
-            }
-    __syncthreads();
-    constexpr int OCPR = BN / 8;                 // output chunks per row
-    constexpr int ORPP = kThreads / OCPR;
-    const int oc = tid % OCPR, orl = tid / OCPR;
-    // Per-channel sums over this tile's rows.  Forward: sum and sum of squares of the stored halves (BN
-    // statistics of the layer that follows).  Data gradient with bn_x set: the stored gradient g is first
-    // masked by the ReLU of the tensor it belongs to (mask_y), then sum g and sum g*xhat are formed for the
-    // backward pass of the BN that produced that tensor.
-    float st[16], mu[8], is[8];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) st[j] = 0.f;
-    const bool bwd_stats = a.bn_x != nullptr;
-    if (bwd_stats) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) { mu[j] = a.bn_mean[nt * BN + oc * 8 + j]; is[j] = a.bn_invstd[nt * BN + oc * 8 + j]; }
-    }
-#pragma unroll
-    for (int i = 0; i < BM / ORPP; ++i) {
-        const int row = orl + i * ORPP;
-        const int m = mt * BM + row;
-        if (m < M) {
-            int t, wq, n, hq;
-            fast_divmod(m, OWs, inv_ow, t, wq);
-            fast_divmod(t, OHs, inv_oh, n, hq);
-            const size_t opix = ((size_t)n * a.OH + hq * a.o_mul + a.oph[cls]) * a.OW + wq * a.o_mul + a.opw[cls];
-            const size_t gidx = opix * a.NO + nt * BN + oc * 8;
-            h16x8 v = *reinterpret_cast<const h16x8*>(lds + row * EP + oc * 8);
-            if (a.mask_y) {
-                const h16x8 yv = *reinterpret_cast<const h16x8*>(a.mask_y + gidx);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = (float)yv[j] > 0.f ? v[j] : (h16)0.f;
-            }
-            *reinterpret_cast<h16x8*>(a.out + gidx) = v;
-            if (bwd_stats) {
-                const h16x8 xv = *reinterpret_cast<const h16x8*>(a.bn_x + gidx);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float g = (float)v[j];
-                    st[j] += g;
-                    st[8 + j] += g * (((float)xv[j] - mu[j]) * is[j]);
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) { const float f = (float)v[j]; st[j] += f; st[8 + j] += f * f; }
-            }
-        }
-    }
-    if (a.stats_part) {
-        // per-channel sums of this row tile, added in a fixed order: [tile][first | second sum][channel]
-        float* red = reinterpret_cast<float*>(lds + BM * EP);          // ORPP x 2 x BN floats behind the staged tile
-        static_assert(BM * EP * 2 + ORPP * 2 * BN * 4 <= LDS_HALFS * 2, "statistics scratch must fit in LDS");
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            red[(orl * 2 + 0) * BN + oc * 8 + j] = st[j];
-            red[(orl * 2 + 1) * BN + oc * 8 + j] = st[8 + j];
-        }
-        __syncthreads();
-        if (tid < 2 * BN) {
-            const int which = tid / BN, col = tid % BN;
-            float sum = 0.f;
-            for (int r = 0; r < ORPP; ++r) sum += red[(r * 2 + which) * BN + col];
-            a.stats_part[((size_t)(bid / n_tiles) * 2 + which) * a.NO + nt * BN + col] = sum;
-        }
-    }
+    gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, bid / n_tiles, row_pix);
 }
 
 // ------------------------------------------------------------------------------------------------
