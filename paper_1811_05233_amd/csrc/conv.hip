@@ -250,9 +250,12 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     const int KC = CR / BK;
     const int kiters = ntaps * KC;
     int ld_ti = 0, ld_cc = 0, ld_stage = 0;      // next slab to load: tap, channel slab, ring stage (wave-uniform)
+    // The tap table lives in the kernel-argument segment.  The entry of the tap being loaded is held in a register
+    // and replaced when the tap changes, so that no slab waits on a scalar memory read.
+    int ld_tap = a.tap[cls][0];                  // packed: dh | dw << 8 | filter tap << 16
 
     auto issue_slab = [&]() {
-        const int tap = a.tap[cls][ld_ti];                 // packed: dh | dw << 8 | filter tap << 16
+        const int tap = ld_tap;
         const int dh = (int)(signed char)(tap & 0xff), dw = (int)(signed char)((tap >> 8) & 0xff), bt = tap >> 16;
         const int a_delta = ((dh * IW + dw) * lda + ld_cc * BK) * 2;          // bytes, wave-uniform
         const unsigned b_delta = (unsigned)(bt * CR + ld_cc * BK) * 2u;
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
         for (int j = 0; j < NB; ++j)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(sb + (wave + 4 * j) * 512), 16,
                                                      (int)(b_voff[j] + b_delta), 0, 0, 0);
-        if (++ld_cc == KC) { ld_cc = 0; ++ld_ti; }
+        if (++ld_cc == KC) { ld_cc = 0; ++ld_ti; ld_tap = a.tap[cls][ld_ti < ntaps ? ld_ti : 0]; }
         if (++ld_stage == NST) ld_stage = 0;
     };
 
@@ -959,6 +962,22 @@ int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, float* out, hip
 // ------------------------------------------------------------------------------------------------
 // C ABI
 // ------------------------------------------------------------------------------------------------
+namespace {
+// The stand-alone entry points pick a kernel variant by a shape heuristic.  For tests and experiments the
+// environment can name one instead: RN50_GATHER_TILE (forward and data gradient, an RN50_TILE_* value) and
+// RN50_WGRAD_VARIANT (0 .. RN50_NUM_WGRAD_VARIANTS-1).  A value that is absent, malformed, out of range or not
+// applicable to the shape leaves the heuristic in charge.
+int variant_from_env(const char* name, int count)
+{
+    const char* v = getenv(name);
+    if (!v || !*v) return RN50_TILE_AUTO;
+    char* end = nullptr;
+    const long x = strtol(v, &end, 10);
+    if (*end != 0 || x < 0 || x >= count) return RN50_TILE_AUTO;
+    return (int)x;
+}
+}  // namespace
+
 extern "C" size_t conv_workspace_bytes(const conv_desc* d, int which)
 {
     if (rn50_conv_validate(d) != RN50_OK) return 0;
@@ -1000,7 +1019,7 @@ extern "C" int conv_fwd(const conv_desc* d, const void* x, const void* w, void* 
         return rn50_conv_fwd_launch(*d, padded, packed, static_cast<h16*>(y), s, nullptr, nullptr, RN50_TILE_AUTO);
     }
     return rn50_conv_fwd_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(w), static_cast<h16*>(y), s, nullptr,
-                                nullptr, RN50_TILE_AUTO);
+                                nullptr, variant_from_env("RN50_GATHER_TILE", RN50_NUM_GATHER_TILES));
 }
 
 extern "C" int conv_dgrad(const conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, void* stream)
@@ -1012,7 +1031,7 @@ extern "C" int conv_dgrad(const conv_desc* d, const void* dy, const void* w, voi
     h16* wt = static_cast<h16*>(ws);
     RN50_TRY(rn50_transpose_filter(*d, static_cast<const h16*>(w), wt, s));
     return rn50_conv_dgrad_launch(*d, static_cast<const h16*>(dy), wt, nullptr, static_cast<h16*>(dx), s, nullptr, nullptr,
-                                  RN50_TILE_AUTO);
+                                  variant_from_env("RN50_GATHER_TILE", RN50_NUM_GATHER_TILES));
 }
 
 extern "C" int conv_wgrad(const conv_desc* d, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes, void* stream)
@@ -1032,6 +1051,7 @@ extern "C" int conv_wgrad(const conv_desc* d, const void* x, const void* dy, voi
         RN50_TRY(rn50_stem_unpack_wgrad(*d, acc, unpacked, s));
         return rn50_cast_f32_to_h16(unpacked, static_cast<h16*>(dw), (size_t)d->k * 147, s);
     }
-    RN50_TRY(rn50_conv_wgrad_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(dy), acc, partials, s, RN50_TILE_AUTO));
+    RN50_TRY(rn50_conv_wgrad_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(dy), acc, partials, s,
+                                    variant_from_env("RN50_WGRAD_VARIANT", RN50_NUM_WGRAD_VARIANTS)));
     return rn50_cast_f32_to_h16(acc, static_cast<h16*>(dw), acc_floats, s);
 }
