@@ -862,21 +862,23 @@ size_t rn50_wgrad_acc_floats(const conv_desc& d)
 namespace {
 struct WgradPlan { int BM, BN, G, NG, tiles, nsplit, pix_per_split; bool stem; };
 
-// variant: RN50_TILE_AUTO, or tile_index * 3 + split_index with tile 0 = 128x128 (if the shape allows),
-// 1 = 64x64 and split targets of 256, 512, 1024 workgroups
+// variant: RN50_TILE_AUTO, or tile_index * 3 + split_index with tile 0 = 128x128, 1 = 64x64, 2 = 64x128,
+// 3 = 128x64 (filters x filter-element columns; 64x64 where the shape does not allow the tile) and split targets
+// of 256, 512, 1024 workgroups
 WgradPlan wgrad_plan(const conv_desc& d, int variant)
 {
     WgradPlan p;
     const int want_blocks = variant < 0 ? 512 : 256 << (variant % 3);
-    const bool small_tile = variant >= 3;
+    const int tile = variant < 0 ? 0 : variant / 3;
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     const long long npix = (long long)d.n * P * Q;
     p.stem = rn50_conv_is_stem(d);
     if (p.stem) { p.BM = 64; p.BN = 64; p.G = 32; p.NG = 8; }
     else {
         p.G = 64; p.NG = d.r * d.s * d.c / 64;
-        if (d.k % 128 == 0 && p.NG % 2 == 0 && !small_tile) { p.BM = 128; p.BN = 128; }
-        else { p.BM = 64; p.BN = 64; }
+        p.BM = (tile == 0 || tile == 3) ? 128 : 64;
+        p.BN = (tile == 0 || tile == 2) ? 128 : 64;
+        if ((p.BM == 128 && d.k % 128 != 0) || (p.BN == 128 && p.NG % 2 != 0)) { p.BM = 64; p.BN = 64; }
     }
     p.tiles = (d.k / p.BM) * (p.NG * p.G / p.BN);
     // pixel splits: about want_blocks workgroups, but at least 8 K-slabs of 32 pixels each
@@ -935,10 +937,14 @@ int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, floa
     const int grid = p.tiles * p.nsplit;
     {
         const double bytes = 2.0 * ((double)d.n * d.h * d.w * d.c + (double)d.n * P * Q * d.k) + 4.0 * d.k * d.r * d.s * d.c;
-        ProfScope ps(p.stem ? RN50_K_WGRAD_STEM : (p.BM == 128 ? RN50_K_WGRAD_128x128 : RN50_K_WGRAD_64x64),
-                     conv_flops(d, P, Q), bytes, s);
+        const int kid = p.stem ? RN50_K_WGRAD_STEM
+                      : p.BM == 128 ? (p.BN == 128 ? RN50_K_WGRAD_128x128 : RN50_K_WGRAD_128x64)
+                                    : (p.BN == 128 ? RN50_K_WGRAD_64x128 : RN50_K_WGRAD_64x64);
+        ProfScope ps(kid, conv_flops(d, P, Q), bytes, s);
         if (p.stem) wgrad_kernel<64, 64, 4, 32, true><<<grid, kThreads, 0, s>>>(a);
-        else if (p.BM == 128) wgrad_kernel<128, 128, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
+        else if (p.BM == 128 && p.BN == 128) wgrad_kernel<128, 128, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
+        else if (p.BM == 128) wgrad_kernel<128, 64, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
+        else if (p.BN == 128) wgrad_kernel<64, 128, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
         else wgrad_kernel<64, 64, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
         RN50_TRY(rn50_check_launch());
     }

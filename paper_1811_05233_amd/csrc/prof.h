@@ -9,6 +9,8 @@ enum Rn50Kernel {
     RN50_K_GATHER_STEM,             // stem forward (128x64 tile, 32-wide K slabs)
     RN50_K_WGRAD_128x128,
     RN50_K_WGRAD_64x64,
+    RN50_K_WGRAD_64x128,
+    RN50_K_WGRAD_128x64,
     RN50_K_WGRAD_STEM,
     RN50_K_WGRAD_REDUCE,
     RN50_K_BN_STATS,

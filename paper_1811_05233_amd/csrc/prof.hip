@@ -10,7 +10,8 @@ const char* const kNames[RN50_K_COUNT] = {
     "gather_gemm_kernel<64,64,64,2,4>", "gather_gemm_kernel<64,64,32,4,4>", "gather_gemm_kernel<128,64,32,2,4>",
     "gather_gemm_kernel<128,128,32,2,3>", "gather_gemm_kernel<256,64,32,3,2>", "gather_gemm_kernel<128,64,64,3,2>",
     "gather_gemm_kernel<128,64,32,4,2> (stem)",
-    "wgrad_kernel<128,128,4,64,false>", "wgrad_kernel<64,64,4,64,false>", "wgrad_kernel<64,64,4,32,true> (stem)",
+    "wgrad_kernel<128,128,4,64,false>", "wgrad_kernel<64,64,4,64,false>", "wgrad_kernel<64,128,4,64,false>",
+    "wgrad_kernel<128,64,4,64,false>", "wgrad_kernel<64,64,4,32,true> (stem)",
     "wgrad_reduce_kernel",
     "bn_stats_kernel", "bn_finalize_kernel<0,*> (forward statistics)", "bn_apply_kernel", "bn_fused_apply_kernel (finalize + apply)",
     "bn_bwd_reduce_kernel", "bn_finalize_kernel<1,*> (backward sums)", "bn_bwd_apply_kernel", "bn_bwd_fused_apply_kernel (finalize + apply)",
