@@ -1,6 +1,9 @@
 // Whole-iteration driver: walks the ResNet-50 v1.5 layer table and enqueues forward, loss,
-// backward and the momentum-SGD update on one stream, with no host synchronisation.
-// The context is a host object; every device byte lives in the caller's workspace.
+// backward and the momentum-SGD (or LARS) update with no host synchronisation.  The caller's
+// stream carries the dependent chain; a second stream owned by the context takes the work that
+// only branches off it (projection shortcuts, filter gradients, the filter re-layout) and is
+// joined back before the update.  The context is a host object; every device byte lives in the
+// caller's workspace.
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
