@@ -48,8 +48,9 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 __device__ __forceinline__ void fast_divmod(int m, int d, float inv_d, int& q, int& r) {
     q = (int)((float)m * inv_d);
     r = m - q * d;
-    if (r < 0) { r += d; --q; }
-    else if (r >= d) { r -= d; ++q; }
+    const int fix = (r >= d ? 1 : 0) - (r < 0 ? 1 : 0);     // the float quotient is off by at most one; no branches
+    q += fix;
+    r -= fix * d;
 }
 
 // Accumulator start: zero, or the addend at the tile's output positions (out = addend + A*B, rounded once).
@@ -353,10 +354,9 @@ __device__ __forceinline__ h16x4 lds_read_tr(const h16* p) {
     return __builtin_bit_cast(h16x4, v);
 }
 
-template <int BM, int BN, int NST, int G, bool kStem>
+template <int BM, int BN, int NST, int G, bool kStem, int BKP>      // BKP: pixels per K-slab
 __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradArgs a)
 {
-    constexpr int BKP = 32;                                   // pixels per K-slab
     constexpr int A_LPR = BM / 8, A_RPI = 64 / A_LPR, NA = BKP / A_RPI / 4;
     constexpr int B_LPR = BN / 8, B_RPI = 64 / B_LPR, NB = BKP / B_RPI / 4;
     constexpr int NL = NA + NB;
@@ -860,25 +860,33 @@ size_t rn50_wgrad_acc_floats(const conv_desc& d)
 }
 
 namespace {
-struct WgradPlan { int BM, BN, G, NG, tiles, nsplit, pix_per_split; bool stem; };
+// Tile variants of the filter gradient: (filters) x (filter-element columns), ring stages, pixels per K-slab.
+// A shape that does not allow a 128-wide side runs the 64x64 tile of the same slab depth instead.
+struct WgradTile { int BM, BN, NST, BKP; };
+constexpr WgradTile kWgradTiles[RN50_NUM_WGRAD_TILES] = {
+    {128, 128, 4, 32}, {64, 64, 4, 32}, {64, 128, 4, 32}, {128, 64, 4, 32},
+    {64, 64, 3, 64}, {64, 64, 2, 64}, {64, 64, 2, 128}, {64, 128, 3, 64}, {128, 64, 3, 64}, {128, 128, 2, 64}};
+constexpr int kWgradFallback32 = 1, kWgradFallback64 = 4, kWgradFallback128 = 6;   // the 64x64 tile per slab depth
 
-// variant: RN50_TILE_AUTO, or tile_index * 3 + split_index with tile 0 = 128x128, 1 = 64x64, 2 = 64x128,
-// 3 = 128x64 (filters x filter-element columns; 64x64 where the shape does not allow the tile) and split targets
-// of 256, 512, 1024 workgroups
+struct WgradPlan { int tile, BM, BN, G, NG, tiles, nsplit, pix_per_split; bool stem; };
+
+// variant: RN50_TILE_AUTO, or tile_index * 3 + split_index: a kWgradTiles entry and a split target of 256, 512 or
+// 1024 workgroups
 WgradPlan wgrad_plan(const conv_desc& d, int variant)
 {
     WgradPlan p;
     const int want_blocks = variant < 0 ? 512 : 256 << (variant % 3);
-    const int tile = variant < 0 ? 0 : variant / 3;
+    p.tile = variant < 0 ? 0 : variant / 3;
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     const long long npix = (long long)d.n * P * Q;
     p.stem = rn50_conv_is_stem(d);
-    if (p.stem) { p.BM = 64; p.BN = 64; p.G = 32; p.NG = 8; }
+    if (p.stem) { p.tile = -1; p.BM = 64; p.BN = 64; p.G = 32; p.NG = 8; }
     else {
         p.G = 64; p.NG = d.r * d.s * d.c / 64;
-        p.BM = (tile == 0 || tile == 3) ? 128 : 64;
-        p.BN = (tile == 0 || tile == 2) ? 128 : 64;
-        if ((p.BM == 128 && d.k % 128 != 0) || (p.BN == 128 && p.NG % 2 != 0)) { p.BM = 64; p.BN = 64; }
+        const WgradTile& t = kWgradTiles[p.tile];
+        if ((t.BM == 128 && d.k % 128 != 0) || (t.BN == 128 && p.NG % 2 != 0))
+            p.tile = t.BKP == 32 ? kWgradFallback32 : t.BKP == 64 ? kWgradFallback64 : kWgradFallback128;
+        p.BM = kWgradTiles[p.tile].BM; p.BN = kWgradTiles[p.tile].BN;
     }
     p.tiles = (d.k / p.BM) * (p.NG * p.G / p.BN);
     // pixel splits: about want_blocks workgroups, but at least 8 K-slabs of 32 pixels each
@@ -889,6 +897,13 @@ WgradPlan wgrad_plan(const conv_desc& d, int variant)
     p.pix_per_split = (int)(slabs_per * 32);
     p.nsplit = (int)((slabs + slabs_per - 1) / slabs_per);
     return p;
+}
+
+template <int TILE>
+void launch_wgrad_tile(const WgradArgs& a, int grid, hipStream_t s)
+{
+    constexpr WgradTile t = kWgradTiles[TILE];
+    wgrad_kernel<t.BM, t.BN, t.NST, 64, false, t.BKP><<<grid, kThreads, 0, s>>>(a);
 }
 }  // namespace
 
@@ -937,15 +952,21 @@ int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, floa
     const int grid = p.tiles * p.nsplit;
     {
         const double bytes = 2.0 * ((double)d.n * d.h * d.w * d.c + (double)d.n * P * Q * d.k) + 4.0 * d.k * d.r * d.s * d.c;
-        const int kid = p.stem ? RN50_K_WGRAD_STEM
-                      : p.BM == 128 ? (p.BN == 128 ? RN50_K_WGRAD_128x128 : RN50_K_WGRAD_128x64)
-                                    : (p.BN == 128 ? RN50_K_WGRAD_64x128 : RN50_K_WGRAD_64x64);
-        ProfScope ps(kid, conv_flops(d, P, Q), bytes, s);
-        if (p.stem) wgrad_kernel<64, 64, 4, 32, true><<<grid, kThreads, 0, s>>>(a);
-        else if (p.BM == 128 && p.BN == 128) wgrad_kernel<128, 128, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
-        else if (p.BM == 128) wgrad_kernel<128, 64, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
-        else if (p.BN == 128) wgrad_kernel<64, 128, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
-        else wgrad_kernel<64, 64, 4, 64, false><<<grid, kThreads, 0, s>>>(a);
+        static_assert(RN50_K_WGRAD_TILE_LAST - RN50_K_WGRAD_TILE0 + 1 == RN50_NUM_WGRAD_TILES, "one profile id per tile variant");
+        ProfScope ps(p.stem ? RN50_K_WGRAD_STEM : RN50_K_WGRAD_TILE0 + p.tile, conv_flops(d, P, Q), bytes, s);
+        switch (p.tile) {
+            case -1: wgrad_kernel<64, 64, 4, 32, true, 32><<<grid, kThreads, 0, s>>>(a); break;
+            case 0: launch_wgrad_tile<0>(a, grid, s); break;
+            case 1: launch_wgrad_tile<1>(a, grid, s); break;
+            case 2: launch_wgrad_tile<2>(a, grid, s); break;
+            case 3: launch_wgrad_tile<3>(a, grid, s); break;
+            case 4: launch_wgrad_tile<4>(a, grid, s); break;
+            case 5: launch_wgrad_tile<5>(a, grid, s); break;
+            case 6: launch_wgrad_tile<6>(a, grid, s); break;
+            case 7: launch_wgrad_tile<7>(a, grid, s); break;
+            case 8: launch_wgrad_tile<8>(a, grid, s); break;
+            default: launch_wgrad_tile<9>(a, grid, s); break;
+        }
         RN50_TRY(rn50_check_launch());
     }
     if (p.nsplit > 1) {

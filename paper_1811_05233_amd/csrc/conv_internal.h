@@ -16,7 +16,8 @@ enum {
     RN50_TILE_256x64,          // 256x64, 32-wide slabs, 3 stages
     RN50_TILE_128x64_K64,      // 128x64, 64-wide slabs, 3 stages
     RN50_NUM_GATHER_TILES,
-    RN50_NUM_WGRAD_VARIANTS = 12
+    RN50_NUM_WGRAD_TILES = 10,
+    RN50_NUM_WGRAD_VARIANTS = 3 * RN50_NUM_WGRAD_TILES      // tile x split target
 };
 
 struct GatherArgs {
