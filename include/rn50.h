@@ -67,7 +67,7 @@ typedef struct {
 enum { RN50_CONV_FWD = 0, RN50_CONV_DGRAD = 1, RN50_CONV_WGRAD = 2 };
 /* The three stand-alone calls below choose among the library's kernel variants (tile shapes, pipeline depths,
  * split counts) by a shape heuristic; all variants compute the same result up to summation order.  For tests the
- * environment may name one: RN50_GATHER_TILE=0..8 (conv_fwd, conv_dgrad), RN50_WGRAD_VARIANT=0..29 (conv_wgrad); a
+ * environment may name one: RN50_GATHER_TILE=0..11 (conv_fwd, conv_dgrad), RN50_WGRAD_VARIANT=0..29 (conv_wgrad); a
  * value that does not parse, is out of range or does not fit the shape is ignored. */
 size_t conv_workspace_bytes(const conv_desc* d, int which);
 

@@ -216,10 +216,10 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
 
     // ---- this lane's place in a wave-wide load: row inside the group of RPI rows, logical chunk ----
     int row_in_grp, phys;
-    if (BK == 64) { row_in_grp = lane >> 3; phys = lane & 7; }
+    if (BK >= 64) { row_in_grp = lane / CPR; phys = lane % CPR; }
     else { row_in_grp = 2 * (lane >> 3) + ((lane & 7) >> 2); phys = lane & 3; }
     auto logical_chunk = [&](int row) {
-        if (BK == 64) return phys ^ ((row ^ (row >> 3)) & 7);
+        if (BK >= 64) return phys ^ ((row ^ (row >> 3)) & 7);
         return phys ^ ((row >> 1) & 3);
     };
 
@@ -650,6 +650,8 @@ int launch_gather(GatherArgs& a, hipStream_t s, int kid, double flops, double by
 bool gather_tile_ok(const GatherArgs& a, int tile)
 {
     if (tile < 0 || tile >= RN50_NUM_GATHER_TILES) return false;
+    if (tile == RN50_TILE_64x64_K128 || tile == RN50_TILE_128x64_K128) return a.CR % 128 == 0;
+    if (tile == RN50_TILE_64x64_K256) return a.CR % 256 == 0;
     return (tile != RN50_TILE_128x128 && tile != RN50_TILE_128x128_SHORT) || a.NO % 128 == 0;
 }
 
@@ -680,6 +682,9 @@ int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, in
         case RN50_TILE_128x128_SHORT: return launch_gather<128, 128, 32, 2, 3>(a, s, kid, flops, bytes);
         case RN50_TILE_256x64: return launch_gather<256, 64, 32, 3, 2>(a, s, kid, flops, bytes);
         case RN50_TILE_128x64_K64: return launch_gather<128, 64, 64, 3, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_64x64_K128: return launch_gather<64, 64, 128, 2, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_128x64_K128: return launch_gather<128, 64, 128, 2, 1>(a, s, kid, flops, bytes);
+        case RN50_TILE_64x64_K256: return launch_gather<64, 64, 256, 2, 1>(a, s, kid, flops, bytes);
         default: tile = RN50_TILE_64x64_K32; return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_TILE0 + tile, flops, bytes);
     }
 }

@@ -15,6 +15,9 @@ enum {
     RN50_TILE_128x128_SHORT,   // 128x128, 32-wide slabs, 2 stages, 3 workgroups per compute unit
     RN50_TILE_256x64,          // 256x64, 32-wide slabs, 3 stages
     RN50_TILE_128x64_K64,      // 128x64, 64-wide slabs, 3 stages
+    RN50_TILE_64x64_K128,      // 64x64, 128-wide slabs, 2 stages (reduction length a multiple of 128)
+    RN50_TILE_128x64_K128,     // 128x64, 128-wide slabs, 2 stages (reduction length a multiple of 128)
+    RN50_TILE_64x64_K256,      // 64x64, 256-wide slabs, 2 stages (reduction length a multiple of 256)
     RN50_NUM_GATHER_TILES,
     RN50_NUM_WGRAD_TILES = 10,
     RN50_NUM_WGRAD_VARIANTS = 3 * RN50_NUM_WGRAD_TILES      // tile x split target

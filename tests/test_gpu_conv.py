@@ -78,8 +78,8 @@ def test_conv_edge_shapes(shape):
 VARIANT_SHAPES = [
     (3, 14, 14, 128, 128, 3, 1, 1), (5, 7, 7, 64, 256, 3, 1, 1), (2, 28, 28, 96 + 32, 64, 3, 1, 1),
     (2, 56, 56, 64, 64, 3, 1, 1), (7, 5, 3, 64, 128, 3, 1, 1), (1, 6, 70, 64, 64, 3, 1, 1), (40, 2, 2, 64, 64, 3, 1, 1),
-    (2, 14, 14, 256, 128, 1, 1, 0), (2, 15, 13, 128, 128, 3, 2, 1)]
-N_GATHER_TILES, N_WGRAD_VARIANTS = 9, 30
+    (2, 14, 14, 256, 256, 1, 1, 0), (2, 15, 13, 128, 128, 3, 2, 1)]
+N_GATHER_TILES, N_WGRAD_VARIANTS = 12, 30
 
 
 @pytest.mark.parametrize("tile", range(N_GATHER_TILES))
