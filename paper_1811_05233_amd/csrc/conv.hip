@@ -201,10 +201,21 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     const int wm0 = (wave / WC) * WM, wn0 = (wave % WC) * WN;
 
     // ---- which tile ----
-    const int bid = rn50_xcd_remap(blockIdx.x, gridDim.x);
+    // Workgroups are dealt round-robin to the 8 XCDs.  Normally every XCD takes a contiguous range of row tiles
+    // with all their column tiles (its L2 then holds that range's A rows and all of B); when B is the larger
+    // operand every XCD takes one eighth of the column tiles with all row tiles instead.
     const int n_tiles = a.NO / BN;
-    const int nt = bid % n_tiles;
-    int mt = bid / n_tiles;
+    int nt, mt;
+    if (a.xcd_split_cols) {
+        const int per = n_tiles >> 3, p = blockIdx.x >> 3;
+        nt = (blockIdx.x & 7) * per + p % per;
+        mt = p / per;
+    } else {
+        const int bid = rn50_xcd_remap(blockIdx.x, gridDim.x);
+        nt = bid % n_tiles;
+        mt = bid / n_tiles;
+    }
+    const int tile_row = mt;
     int cls = 0;
     while (cls < a.ncls - 1 && mt >= a.mt_end[cls]) ++cls;
     if (cls > 0) mt -= a.mt_end[cls - 1];
@@ -328,7 +339,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     RN50_WAIT_LGKMCNT0();
     __builtin_amdgcn_s_barrier();             // all waves are done reading the ring before it is reused
 
-    gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, bid / n_tiles, row_pix);
+    gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, tile_row, row_pix);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -642,6 +653,7 @@ int launch_gather(GatherArgs& a, hipStream_t s, int kid, double flops, double by
     }
     if (total == 0) return RN50_OK;
     const int grid = total * (a.NO / BN);
+    a.xcd_split_cols = (a.b_bytes > a.a_bytes && (a.NO / BN) % 8 == 0) ? 1 : 0;
     ProfScope ps(kid, flops, bytes, s);
     gather_gemm_kernel<BM, BN, BK, NST, OCC><<<grid, kThreads, 0, s>>>(a);
     return rn50_check_launch();

@@ -52,6 +52,7 @@ struct GatherArgs {
     float inv_oh[4], inv_ow[4];   // reciprocals of cOHs / cOWs (filled by the launcher)
     unsigned a_bytes, b_bytes;    // sizes of A and B in bytes (buffer range checks)
     int tap[4][9];       // per class and live tap: dh | dw << 8 (signed bytes, A-pixel offset) | filter tap << 16
+    int xcd_split_cols;  // 1: an XCD owns a range of column tiles (all row tiles); 0: a range of row tiles.  Set by the launcher
 };
 
 struct WgradArgs {
