@@ -667,15 +667,19 @@ bool gather_tile_ok(const GatherArgs& a, int tile)
     return (tile != RN50_TILE_128x128 && tile != RN50_TILE_128x128_SHORT) || a.NO % 128 == 0;
 }
 
-// default choice when no tuned tile is given: the large tile while it still yields about two workgroups
-// per compute unit, else smaller ones
+// default choice when no tuned tile is given (what the autotuner picks most often for such shapes): the large
+// tiles while they still yield about two workgroups per compute unit; else 64x64 tiles, with the deepest K-slab
+// the reduction length allows when there are too few workgroups to cover the load latency by numbers
 int gather_tile_heuristic(const GatherArgs& a)
 {
     long long rows = 0;
     for (int c = 0; c < a.ncls; ++c) rows += (long long)a.NB * a.cOHs[c] * a.cOWs[c];
-    if (a.NO % 128 == 0 && (rows / 128) * (a.NO / 128) >= 400) return RN50_TILE_128x128;
-    if ((rows / 128) * (a.NO / 64) >= 400) return RN50_TILE_128x64;
-    return RN50_TILE_64x64_DEEP;
+    if (a.NO % 128 == 0 && (rows / 128) * (a.NO / 128) >= 400) return RN50_TILE_128x128_SHORT;
+    if ((rows / 128) * (a.NO / 64) >= 400) return RN50_TILE_128x64_SHORT;
+    const long long small = ((rows + 63) / 64) * (a.NO / 64);
+    if (small <= 256 && a.CR % 256 == 0) return RN50_TILE_64x64_K256;
+    if (small <= 512 && a.CR % 128 == 0) return RN50_TILE_64x64_K128;
+    return RN50_TILE_64x64_WIDE;
 }
 
 int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, int tile)
@@ -892,8 +896,9 @@ struct WgradPlan { int tile, BM, BN, G, NG, tiles, nsplit, pix_per_split; bool s
 WgradPlan wgrad_plan(const conv_desc& d, int variant)
 {
     WgradPlan p;
-    const int want_blocks = variant < 0 ? 512 : 256 << (variant % 3);
-    p.tile = variant < 0 ? 0 : variant / 3;
+    // without a tuned variant: 64x64 tiles with 128-pixel slabs, 256 workgroups (the autotuner's most frequent pick)
+    const int want_blocks = variant < 0 ? 256 : 256 << (variant % 3);
+    p.tile = variant < 0 ? kWgradFallback128 : variant / 3;
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     const long long npix = (long long)d.n * P * Q;
     p.stem = rn50_conv_is_stem(d);
