@@ -119,13 +119,20 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
             }
     __syncthreads();
     const int oc = tid % OCPR, orl = tid / OCPR;
-    float st[16], mu[8], is[8];
+    float st[16], mu[8], is[8], st2[8], mu2[8], is2[8];
 #pragma unroll
     for (int j = 0; j < 16; ++j) st[j] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) st2[j] = 0.f;
     const bool bwd_stats = a.bn_x != nullptr;
+    const bool second = bwd_stats && a.bn_x2 != nullptr;
     if (bwd_stats) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) { mu[j] = a.bn_mean[nt * BN + oc * 8 + j]; is[j] = a.bn_invstd[nt * BN + oc * 8 + j]; }
+    }
+    if (second) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { mu2[j] = a.bn_mean2[nt * BN + oc * 8 + j]; is2[j] = a.bn_invstd2[nt * BN + oc * 8 + j]; }
     }
 #pragma unroll
     for (int i = 0; i < BM / ORPP; ++i) {
@@ -149,6 +156,11 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
                     st[j] += g;
                     st[8 + j] += g * (((float)xv[j] - mu[j]) * is[j]);
                 }
+                if (second) {
+                    const h16x8 xw = *reinterpret_cast<const h16x8*>(a.bn_x2 + gidx);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) st2[j] += (float)v[j] * (((float)xw[j] - mu2[j]) * is2[j]);
+                }
             } else {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) { const float f = (float)v[j]; st[j] += f; st[8 + j] += f * f; }
@@ -170,6 +182,18 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
             float sum = 0.f;
             for (int r = 0; r < ORPP; ++r) sum += red[(r * 2 + which) * BN + col];
             a.stats_part[((size_t)tile_row * 2 + which) * a.NO + nt * BN + col] = sum;
+            if (second && which == 0) a.stats_part2[((size_t)tile_row * 2) * a.NO + nt * BN + col] = sum;
+        }
+        if (second) {                       // the second BN's sum g*xhat2, through the same scratch
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < 8; ++j) red[orl * BN + oc * 8 + j] = st2[j];
+            __syncthreads();
+            if (tid < BN) {
+                float sum = 0.f;
+                for (int r = 0; r < ORPP; ++r) sum += red[r * BN + tid];
+                a.stats_part2[((size_t)tile_row * 2 + 1) * a.NO + nt * BN + tid] = sum;
+            }
         }
     }
 }
@@ -823,6 +847,9 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
     if (fuse) {
         a.mask_y = fuse->mask_y; a.bn_x = fuse->bn_x; a.bn_mean = fuse->mean; a.bn_invstd = fuse->invstd;
         a.stats_part = fuse->part;
+        if (fuse->bn_x2 && fuse->part2) {
+            a.bn_x2 = fuse->bn_x2; a.bn_mean2 = fuse->mean2; a.bn_invstd2 = fuse->invstd2; a.stats_part2 = fuse->part2;
+        }
     }
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     a.A = dy; a.B = wt; a.out = dx; a.addend = addend;

@@ -35,6 +35,10 @@ struct GatherArgs {
     const h16* bn_x;     // nullable (data gradient): input of the BN that produced mask_y; switches the sums
     const float* bn_mean;    //   to sum g and sum g*xhat with xhat = (bn_x - mean) * invstd
     const float* bn_invstd;
+    const h16* bn_x2;    // nullable: a second BN fed by the same gradient (a projection shortcut's): its input,
+    const float* bn_mean2;   //   statistics, and the place of its sums [tile][2][NO] (sum g again, sum g*xhat2)
+    const float* bn_invstd2;
+    float* stats_part2;
     int NB;              // images
     int IH, IW;          // spatial size of A
     int lda;             // halfs between adjacent pixels of A
@@ -94,6 +98,12 @@ struct DgradBnFuse {
     const float* mean;
     const float* invstd;
     float* part;           // [row tile][sum g | sum g*xhat][channels], rn50_dgrad_stats_floats(d) floats
+    // optional second BN that receives the same (masked) gradient, e.g. the projection shortcut's: its sums go to
+    // part2, same layout and size
+    const h16* bn_x2 = nullptr;
+    const float* mean2 = nullptr;
+    const float* invstd2 = nullptr;
+    float* part2 = nullptr;
 };
 // addend (nullable) has dx's layout, or with addend_even_only its (even row, even column) pixels only,
 // [n][ceil(h/2)][ceil(w/2)][c] (the data gradient of a strided 1x1 convolution is zero elsewhere).

@@ -593,7 +593,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     };
     // BN backward when the data gradient that produced g already applied the ReLU mask and left the
     // per-tile sums (sum g, sum g*xhat) in c.bn_ws: finalize + apply only
-    int fused_tiles = 0;
+    int fused_tiles = 0, proj_tiles = 0;    // row tiles of the sums waiting in c.bn_ws / c.bn_ws_side
     auto bn_bwd_fused = [&](ConvLayer& l, const h16* g) -> int {
         float* sums = c.bn_ws + (size_t)fused_tiles * 2 * l.d.k;
         return rn50_bn_bwd_from_partials_launch((long long)l.d.n * l.P * l.Q, l.d.k, g, l.conv_out,
@@ -604,9 +604,13 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     // data gradient of conv l into l.din.  prev (nullable) = the layer whose BN+ReLU output `in` is l's input:
     // then the result is masked by in > 0 and the BN-backward sums of prev are formed in the epilogue.
     // `compact_addend`: addend holds only the (even, even) pixels (see ConvLayer::din_compact).
-    auto dgrad = [&](ConvLayer& l, const h16* addend, ConvLayer* prev, const h16* in, bool compact_addend = false) -> int {
+    // prev2 (nullable): a second BN that receives the same gradient (the projection shortcut of the block below);
+    // its sums go to c.bn_ws_side, which only the forward pass uses otherwise.
+    auto dgrad = [&](ConvLayer& l, const h16* addend, ConvLayer* prev, const h16* in, bool compact_addend = false,
+                     ConvLayer* prev2 = nullptr) -> int {
         DgradBnFuse f = {in, prev ? prev->conv_out : nullptr, prev ? prev->mean : nullptr,
                          prev ? prev->invstd : nullptr, c.bn_ws};
+        if (prev && prev2) { f.bn_x2 = prev2->conv_out; f.mean2 = prev2->mean; f.invstd2 = prev2->invstd; f.part2 = c.bn_ws_side; }
         // a strided 1x1 convolution only reaches the (even, even) input pixels: its data gradient is the
         // stride-1 data gradient on the output grid, stored compactly
         conv_desc d = l.d;
@@ -623,6 +627,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         const Block& b = L.blocks[bi];
         ConvLayer &l1 = L.layers[b.c1], &l2 = L.layers[b.c2], &l3 = L.layers[b.c3];
         ConvLayer* below = bi > 0 ? &L.layers[L.blocks[bi - 1].c3] : nullptr;   // produced this block's input
+        ConvLayer* below_proj = (bi > 0 && L.blocks[bi - 1].proj >= 0) ? &L.layers[L.blocks[bi - 1].proj] : nullptr;
         const bool need_in = cfg.has_stem || bi > 0;
         const h16* gres;                                              // masked gradient for the shortcut
         if (dY_fused) { RN50_TRY(bn_bwd_fused(l3, dY)); gres = dY; }
@@ -636,15 +641,24 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         RN50_TRY(fork_wgrad(l1, block_in[bi], c.grad32 + l1.w_off));
         if (b.proj >= 0) {
             ConvLayer& lp = L.layers[b.proj];
-            RN50_TRY(bn_bwd_std(lp, gres, false, nullptr));
+            if (dY_fused) {
+                // the data gradient that produced gres also left this BN's sums (in c.bn_ws_side, same tile count)
+                RN50_TRY(rn50_bn_bwd_from_partials_launch((long long)lp.d.n * lp.P * lp.Q, lp.d.k, gres, lp.conv_out,
+                                                          master_w + lp.gamma_off, lp.mean, lp.invstd, lp.dconv,
+                                                          c.grad32 + lp.gamma_off, c.grad32 + lp.beta_off, c.bn_ws_side,
+                                                          proj_tiles, c.bn_ws_side + (size_t)proj_tiles * 2 * lp.d.k, s));
+            } else {
+                RN50_TRY(bn_bwd_std(lp, gres, false, nullptr));
+            }
             RN50_TRY(fork_wgrad(lp, block_in[bi], c.grad32 + lp.w_off));
             if (need_in) {
                 RN50_TRY(dgrad(lp, nullptr, nullptr, nullptr));
-                RN50_TRY(dgrad(l1, lp.din, below, block_in[bi], lp.din_compact));   // main path + projection shortcut
+                RN50_TRY(dgrad(l1, lp.din, below, block_in[bi], lp.din_compact, below_proj));   // main path + projection shortcut
             }
         } else {
-            RN50_TRY(dgrad(l1, gres, below, block_in[bi]));           // main path + identity shortcut
+            RN50_TRY(dgrad(l1, gres, below, block_in[bi], false, below_proj));   // main path + identity shortcut
         }
+        if (below_proj) proj_tiles = fused_tiles;
         dY = l1.din;
         dY_fused = below != nullptr;
     }
