@@ -46,21 +46,33 @@ def measured_traffic(kernel_name):
     return None
 
 
-def cpu_baseline(sample_batch):
-    """The CPU oracle as it stands (FP32 instantiation, storage rounding on), one full ResNet-50
-    training step at a small batch; images/s = batch / seconds."""
+def _cpu_step_seconds(batch):
     import numpy as np
-    import oracle as O
     from oracle import resnet50 as R
     from paper_1811_05233_amd import synth
-    net = R.Net(sample_batch, (224, 224))
+    net = R.Net(batch, (224, 224))
     lay = [(s.kind, s.offset, s.count, s.fan_in) for s in net.segments]
     w = synth.flat_params(200, lay)
-    x = synth.normal_f16(201, (sample_batch, 224, 224, 3))
-    lab = synth.labels(202, sample_batch)
+    x = synth.normal_f16(201, (batch, 224, 224, 3))
+    lab = synth.labels(202, batch)
     t0 = time.perf_counter()
     R.step_ref(net, x, lab, w, np.zeros_like(w), 0.1, 0.9, 1e-4, loss_scale=1024.0, lowp=True, dtype=np.float32)
-    dt = time.perf_counter() - t0
+    return time.perf_counter() - t0
+
+
+def cpu_baseline(sample_batch):
+    """The CPU oracle as it stands (FP32 instantiation, storage rounding on), one full ResNet-50 training step;
+    images/s = batch / seconds.  sample_batch < 0: a batch-4 step first, then the largest batch of 8, 16, 32 (the
+    benchmarked workload) that the batch-4 time predicts to finish within 25 s; its figure is the one reported."""
+    import oracle as O
+    if sample_batch < 0:
+        sample_batch, dt = 4, _cpu_step_seconds(4)
+        bigger = [b for b in (32, 16, 8) if dt * b / 4 <= 25.0]
+        if bigger:
+            sample_batch = bigger[0]
+            dt = _cpu_step_seconds(sample_batch)
+    else:
+        dt = _cpu_step_seconds(sample_batch)
     return {"value": sample_batch / dt, "unit": "images/s", "cores": O.max_threads(), "kind": "oracle",
             "sample": "one full ResNet-50 fwd+bwd+SGD step at batch %d, 224x224, FP32 oracle with binary16 "
                       "storage rounding, %.1f s" % (sample_batch, dt)}
@@ -235,7 +247,8 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=32)
-    ap.add_argument("--cpu-sample-batch", type=int, default=4, help="0 disables the cpu_baseline leg")
+    ap.add_argument("--cpu-sample-batch", type=int, default=-1,
+                    help="batch of the cpu_baseline leg; 0 disables it, negative picks up to 32 within about 25 s")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-autotune", action="store_true", help="use the built-in tile heuristics")
     ap.add_argument("--lars", action="store_true",
@@ -362,7 +375,7 @@ def main():
         "paper_context": "Table 6: 2565 images/s on 4 V100 (641 per GPU, incl. all-reduce and input pipeline)",
         "roofline": roof, "kernels": kernels,
     }
-    if args.cpu_sample_batch > 0:
+    if args.cpu_sample_batch != 0:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_batch)
     print(json.dumps(out))
 
