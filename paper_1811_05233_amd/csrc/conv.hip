@@ -10,9 +10,13 @@
 // For stride 2 the data-gradient rows are split into the four (h%2, w%2) parity classes; each
 // class only visits the filter taps that can reach it, so no multiply hits an inserted zero.
 //
-// The filter gradient reduces over pixels, which is the strided dimension of both operands; its
-// loader transposes 8x8 half blocks in registers on the way into LDS, after which the same MFMA
-// loop applies.  The pixel range is split over workgroups; their partial tiles are added in a fixed order.
+// The filter gradient reduces over pixels, which is the strided dimension of both operands: its
+// tiles go to LDS as they lie in memory and the MFMA operands are read with the transposing LDS
+// read (ds_read_b64_tr_b16).  The pixel range is split over workgroups; their partial tiles are
+// added in a fixed order.
+//
+// Every kernel exists in several variants (tile shape, K-slab depth, ring stages, residency);
+// the whole-step driver times them per layer, the stand-alone entry points use a shape heuristic.
 #include "common.h"
 #include "conv_internal.h"
 #include "prof.h"
