@@ -5,6 +5,8 @@
 //
 // Reductions are two-stage and deterministic: every workgroup writes per-channel partial
 // sums to the workspace, a small second kernel combines them in a fixed order (in double).
+// When the partial sums come from a convolution epilogue and there are at most 400 row tiles,
+// the apply kernels combine them themselves (per 64-channel slice) and no second kernel runs.
 // The forward statistics are accumulated around a per-channel pivot (row 0) so that
 // E[x^2]-E[x]^2 does not cancel when |mean| >> sigma.
 #include "common.h"
