@@ -251,6 +251,10 @@ def main():
                     help="batch of the cpu_baseline leg; 0 disables it, negative picks up to 32 within about 25 s")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-autotune", action="store_true", help="use the built-in tile heuristics")
+    ap.add_argument("--tuning-file", default="",
+                    help="step mode: JSON file with the kernel-variant table; read if it exists (instead of autotuning), "
+                         "written after autotuning otherwise, so that a profiler run executes the same kernels")
+    ap.add_argument("--tune-report", default="", help="step mode: write what the autotune pass measured to this text file")
     ap.add_argument("--lars", action="store_true",
                     help="step mode: update with LARS (eta 0.01, eps 1e-6, the paper's optimizer) instead of momentum SGD")
     ap.add_argument("--cold", action="store_true",
@@ -292,8 +296,14 @@ def main():
     def step():
         ctx.step(x, lab, w, v, w16, g16, hp, loss)
 
-    if not args.no_autotune:
+    if args.tuning_file and os.path.exists(args.tuning_file):
+        ctx.set_tuning(json.load(open(args.tuning_file))["table"])
+    elif not args.no_autotune:
         ctx.autotune(x, lab, w, w16, g16, loss)      # one-off kernel-variant selection, outside the timed region
+        if args.tuning_file:
+            json.dump({"batch": B, "table": ctx.get_tuning()}, open(args.tuning_file, "w"))
+        if args.tune_report:
+            open(args.tune_report, "w").write(ctx.tuning_report())
 
     for _ in range(args.warmup):
         step()

@@ -66,10 +66,11 @@ typedef struct {
 
 enum { RN50_CONV_FWD = 0, RN50_CONV_DGRAD = 1, RN50_CONV_WGRAD = 2 };
 /* The three stand-alone calls below choose among the library's kernel variants (tile shapes, pipeline depths,
- * split counts) by a shape heuristic; all variants compute the same result up to summation order.  For tests the
- * environment may name one: RN50_GATHER_TILE=0..11 (conv_fwd, conv_dgrad), RN50_WGRAD_VARIANT=0..29 (conv_wgrad); a
- * value that does not parse, is out of range or does not fit the shape is ignored. */
+ * split counts) by a shape heuristic; all variants compute the same result up to summation order.  The
+ * *_variant forms (for tests and tuning) name one: 0 .. rn50_conv_variant_count(which)-1; a value that is out
+ * of range or does not fit the shape leaves the heuristic in charge. */
 size_t conv_workspace_bytes(const conv_desc* d, int which);
+int rn50_conv_variant_count(int which);
 
 /* y[n,p,q,k] = sum_{r,s,c} x[n,p*stride+r-pad,q*stride+s-pad,c] * w[k,r,s,c]  (zero padding) */
 int conv_fwd(const conv_desc* d, const void* x, const void* w, void* y,
@@ -78,11 +79,17 @@ int conv_fwd(const conv_desc* d, const void* x, const void* w, void* y,
  *               dy[n,p,q,k] * w[k,r,s,c].  Every element of dx is written. */
 int conv_dgrad(const conv_desc* d, const void* dy, const void* w, void* dx,
                void* ws, size_t ws_bytes, void* stream);
+int conv_fwd_variant(const conv_desc* d, const void* x, const void* w, void* y,
+                     void* ws, size_t ws_bytes, int variant, void* stream);
+int conv_dgrad_variant(const conv_desc* d, const void* dy, const void* w, void* dx,
+                       void* ws, size_t ws_bytes, int variant, void* stream);
 /* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n,p*stride+r-pad,q*stride+s-pad,c], stored as
  * half.  FP32 partial sums of different pixel ranges are added in a fixed order, so the
  * result is deterministic. */
 int conv_wgrad(const conv_desc* d, const void* x, const void* dy, void* dw,
                void* ws, size_t ws_bytes, void* stream);
+int conv_wgrad_variant(const conv_desc* d, const void* x, const void* dy, void* dw,
+                       void* ws, size_t ws_bytes, int variant, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Batch normalisation over m = N*H*W rows of c channels with batch statistics only
@@ -90,7 +97,9 @@ int conv_wgrad(const conv_desc* d, const void* x, const void* dy, void* dw,
  * mean in FP32 => biased variance), optional residual add, optional ReLU.
  *   mean_c = E[x], var_c = E[x^2]-mean^2 (clamped at 0), invstd = 1/sqrt(var+eps)
  *   y = gamma*(x-mean)*invstd + beta (+ residual);  y = max(y,0) if relu
- * c must be a multiple of 8.  x, y, residual, dy, dx, dresidual: half [m,c].
+ * c: a power of two from 8 to 2048, or a multiple of 2048 (a thread owns 8 channels and a 256-thread
+ * workgroup covers whole rows or a whole number of 2048-channel passes); anything else: RN50_ERR_SHAPE.
+ * x, y, residual, dy, dx, dresidual: half [m,c].
  * gamma, beta, save_mean, save_invstd: float [c].  dgamma, dbeta: half [c] (slices of
  * the flat FP16 gradient).
  * ---------------------------------------------------------------------------------------- */
@@ -278,6 +287,17 @@ int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* labels,
  * documented tolerances but may differ in the last bits from an untuned context (summation order). */
 int rn50_autotune(rn50_ctx* ctx, const void* images, const int32_t* labels, float* master_w, void* w_lowp,
                   void* grad_lowp, float* loss_out, void* stream);
+
+/* The variants in use on a context, three ints per convolution in network order (forward, data gradient, filter
+ * gradient; -1 = shape heuristic), so that a tuning can be stored and a later context (another process, a
+ * profiler run) executes exactly the same kernels.  rn50_get_tuning(ctx, NULL, 0) returns the table length; with
+ * a table it fills it and returns the length (RN50_ERR_SHAPE if capacity is too small).  rn50_set_tuning checks
+ * the length and every entry's range.  rn50_tuning_report copies the text of what the last rn50_autotune measured
+ * (one line per launch site and candidate, microseconds) into buf (host, at most cap-1 characters, NUL-terminated)
+ * and returns its full length. */
+int rn50_get_tuning(rn50_ctx* ctx, int* table /* host */, int capacity);
+int rn50_set_tuning(rn50_ctx* ctx, const int* table /* host */, int n);
+size_t rn50_tuning_report(rn50_ctx* ctx, char* buf /* host */, size_t cap);
 
 /* Device address of a tensor the last rn50_step left in the workspace, for parity checks.
  * name: "<conv>.conv" (conv output), "<conv>.out" (BN output), "<conv>.mean",

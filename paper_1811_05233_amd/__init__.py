@@ -65,6 +65,10 @@ _SIGNATURES = {
     "conv_fwd": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv_dgrad": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv_wgrad": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _vp]),
+    "rn50_conv_variant_count": (_i, [_i]),
+    "conv_fwd_variant": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _i, _vp]),
+    "conv_dgrad_variant": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _i, _vp]),
+    "conv_wgrad_variant": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _i, _vp]),
     "bn_workspace_bytes": (_sz, [ctypes.POINTER(bn_desc)]),
     "bn_relu_fwd": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_relu_bwd": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -94,6 +98,9 @@ _SIGNATURES = {
     "rn50_profile_begin": (_i, []),
     "rn50_profile_end": (_i, [ctypes.POINTER(rn50_profile_entry), _i, ctypes.POINTER(_i)]),
     "rn50_autotune": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "rn50_get_tuning": (_i, [_vp, ctypes.POINTER(_i), _i]),
+    "rn50_set_tuning": (_i, [_vp, ctypes.POINTER(_i), _i]),
+    "rn50_tuning_report": (_sz, [_vp, ctypes.c_char_p, _sz]),
     "rn50_tensor": (_i, [_vp, ctypes.c_char_p, ctypes.POINTER(_vp), ctypes.POINTER(_sz), ctypes.POINTER(_i)]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -114,7 +121,7 @@ def lib():
                 missing.append(name)
                 continue
             fn.restype, fn.argtypes = res, args
-        if missing and not os.environ.get("RN50_ALLOW_PARTIAL_LIB"):
+        if missing:
             raise Rn50Error("librn50.so lacks %s: rebuild it" % ", ".join(missing))
         _lib = l
     return _lib
@@ -152,23 +159,37 @@ def conv_workspace_bytes(d, which):
     return int(lib().conv_workspace_bytes(ctypes.byref(d), which))
 
 
-def conv_fwd(d, x, w, y, ws=None):
+def conv_variant_count(which):
+    return int(lib().rn50_conv_variant_count(which))
+
+
+def conv_fwd(d, x, w, y, ws=None, variant=None):
     ws = ws if ws is not None else _ws(conv_workspace_bytes(d, CONV_FWD), x)
-    _check(lib().conv_fwd(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), _ptr(ws), ws.numel(), _stream()), "conv_fwd")
+    if variant is None:
+        rc = lib().conv_fwd(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), _ptr(ws), ws.numel(), _stream())
+    else:
+        rc = lib().conv_fwd_variant(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(y), _ptr(ws), ws.numel(), int(variant), _stream())
+    _check(rc, "conv_fwd")
     return y
 
 
-def conv_dgrad(d, dy, w, dx, ws=None):
+def conv_dgrad(d, dy, w, dx, ws=None, variant=None):
     ws = ws if ws is not None else _ws(conv_workspace_bytes(d, CONV_DGRAD), dy)
-    _check(lib().conv_dgrad(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(dx), _ptr(ws), ws.numel(), _stream()),
-           "conv_dgrad")
+    if variant is None:
+        rc = lib().conv_dgrad(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(dx), _ptr(ws), ws.numel(), _stream())
+    else:
+        rc = lib().conv_dgrad_variant(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(dx), _ptr(ws), ws.numel(), int(variant), _stream())
+    _check(rc, "conv_dgrad")
     return dx
 
 
-def conv_wgrad(d, x, dy, dw, ws=None):
+def conv_wgrad(d, x, dy, dw, ws=None, variant=None):
     ws = ws if ws is not None else _ws(conv_workspace_bytes(d, CONV_WGRAD), x)
-    _check(lib().conv_wgrad(ctypes.byref(d), _ptr(x), _ptr(dy), _ptr(dw), _ptr(ws), ws.numel(), _stream()),
-           "conv_wgrad")
+    if variant is None:
+        rc = lib().conv_wgrad(ctypes.byref(d), _ptr(x), _ptr(dy), _ptr(dw), _ptr(ws), ws.numel(), _stream())
+    else:
+        rc = lib().conv_wgrad_variant(ctypes.byref(d), _ptr(x), _ptr(dy), _ptr(dw), _ptr(ws), ws.numel(), int(variant), _stream())
+    _check(rc, "conv_wgrad")
     return dw
 
 
@@ -346,6 +367,24 @@ class Rn50Context:
         """Time the kernel variants of every convolution on one forward+backward pass (synchronises)."""
         _check(lib().rn50_autotune(self.handle, _ptr(images), _ptr(labels), _ptr(master_w), _ptr(w_lowp),
                                    _ptr(grad_lowp), _ptr(loss_out), _stream()), "rn50_autotune")
+
+    def get_tuning(self):
+        """Kernel variants in use: [fwd, dgrad, wgrad] per convolution in network order (-1 = heuristic)."""
+        n = lib().rn50_get_tuning(self.handle, None, 0)
+        buf = (_i * n)()
+        if lib().rn50_get_tuning(self.handle, buf, n) != n:
+            raise Rn50Error("rn50_get_tuning failed")
+        return list(buf)
+
+    def set_tuning(self, table):
+        buf = (_i * len(table))(*[int(v) for v in table])
+        _check(lib().rn50_set_tuning(self.handle, buf, len(table)), "rn50_set_tuning")
+
+    def tuning_report(self):
+        n = int(lib().rn50_tuning_report(self.handle, None, 0))
+        buf = ctypes.create_string_buffer(n + 1)
+        lib().rn50_tuning_report(self.handle, buf, n + 1)
+        return buf.value.decode()
 
     def tensor(self, name):
         """Copy of a workspace tensor left by the last step, as a flat torch tensor (half or float)."""

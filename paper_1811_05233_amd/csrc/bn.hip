@@ -113,15 +113,14 @@ __global__ __launch_bounds__(kThreads) void bn_stats_kernel(long long m, int c, 
 //   kMode 0 (forward): partials are sum (x - pivot), sum (x - pivot)^2 -> mean, 1/sqrt(var + eps);
 //                      pivot_row: first row of x, or nullptr for pivot 0
 //   kMode 1 (backward): partials are sum g, sum g*xhat -> sums[0..c) = d beta, sums[c..2c) = d gamma, plus the
-//                      optional half / float copies
+//                      optional half copies (slices of the flat FP16 gradient)
 //   kMode 2 (moments):  as kMode 0 but out0[0..c) = mean, out0[c..2c) = mean of squares (what GPUs exchange)
 template <int kMode, int kNT>
 __global__ __launch_bounds__(kNT) void bn_finalize_kernel(long long m, int c, float eps, int nblk,
                                                           const h16* __restrict__ pivot_row,
                                                           const float* __restrict__ part, float* __restrict__ out0,
                                                           float* __restrict__ out1, h16* __restrict__ dgamma,
-                                                          h16* __restrict__ dbeta, float* __restrict__ dgamma32,
-                                                          float* __restrict__ dbeta32)
+                                                          h16* __restrict__ dbeta)
 {
     constexpr int kRowLanes = kNT / 8, kWaves = kNT / 64, kBatch = 8;
     __shared__ float red[kWaves][32];
@@ -181,8 +180,6 @@ __global__ __launch_bounds__(kNT) void bn_finalize_kernel(long long m, int c, fl
             out0[c + ch] = (float)sb;
             if (dbeta) dbeta[ch] = (h16)(float)sa;
             if (dgamma) dgamma[ch] = (h16)(float)sb;
-            if (dbeta32) dbeta32[ch] = (float)sa;
-            if (dgamma32) dgamma32[ch] = (float)sb;
         }
     }
 }
@@ -190,15 +187,13 @@ __global__ __launch_bounds__(kNT) void bn_finalize_kernel(long long m, int c, fl
 // many partial rows: 1024 threads (128 row lanes), else 256
 template <int kMode>
 void launch_bn_finalize(long long m, int c, float eps, int nblk, const h16* pivot_row, const float* part, float* out0,
-                        float* out1, h16* dgamma, h16* dbeta, float* dgamma32, float* dbeta32, hipStream_t s)
+                        float* out1, h16* dgamma, h16* dbeta, hipStream_t s)
 {
     const int grid = rn50_cdiv(c, 16);
     if (nblk > 256)
-        bn_finalize_kernel<kMode, 1024><<<grid, 1024, 0, s>>>(m, c, eps, nblk, pivot_row, part, out0, out1, dgamma, dbeta,
-                                                             dgamma32, dbeta32);
+        bn_finalize_kernel<kMode, 1024><<<grid, 1024, 0, s>>>(m, c, eps, nblk, pivot_row, part, out0, out1, dgamma, dbeta);
     else
-        bn_finalize_kernel<kMode, 256><<<grid, 256, 0, s>>>(m, c, eps, nblk, pivot_row, part, out0, out1, dgamma, dbeta,
-                                                           dgamma32, dbeta32);
+        bn_finalize_kernel<kMode, 256><<<grid, 256, 0, s>>>(m, c, eps, nblk, pivot_row, part, out0, out1, dgamma, dbeta);
 }
 
 // ------------------------------------------------------------------ forward apply
@@ -490,8 +485,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_fused_apply_kernel(long long 
                                                                       const float* __restrict__ gamma,
                                                                       const float* __restrict__ mean,
                                                                       const float* __restrict__ invstd,
-                                                                      h16* __restrict__ dx, float* __restrict__ dgamma32,
-                                                                      float* __restrict__ dbeta32)
+                                                                      h16* __restrict__ dx, h16* __restrict__ dgamma,
+                                                                      h16* __restrict__ dbeta)
 {
     __shared__ double sums[128];
     const int tid = threadIdx.x;
@@ -508,8 +503,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_fused_apply_kernel(long long 
     }
     slice_partial_sums(part, c, ntiles, ch0, sums);
     if (blockIdx.x == 0 && tid < 64) {
-        if (dbeta32) dbeta32[ch0 + tid] = (float)sums[tid];
-        if (dgamma32) dgamma32[ch0 + tid] = (float)sums[64 + tid];
+        if (dbeta) dbeta[ch0 + tid] = (h16)(float)sums[tid];
+        if (dgamma) dgamma[ch0 + tid] = (h16)(float)sums[64 + tid];
     }
     const float inv_m = 1.f / (float)m;
     float mu[8], is[8], sc[8], mb[8], mg[8];
@@ -613,7 +608,7 @@ int rn50_bn_fwd_launch(long long m, int c, float eps, bool relu, const h16* x, c
     }
     {
         ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * p.nblk * c, s);
-        launch_bn_finalize<0>(m, c, eps, p.nblk, x, ws, save_mean, save_invstd, nullptr, nullptr, nullptr, nullptr, s);
+        launch_bn_finalize<0>(m, c, eps, p.nblk, x, ws, save_mean, save_invstd, nullptr, nullptr, s);
     }
     ProfScope ps(RN50_K_BN_APPLY, 0.0, (res ? 6.0 : 4.0) * elems, s);
     const BnPlan pa = plan_rows_apply(m, c);
@@ -644,7 +639,7 @@ int rn50_bn_fwd_from_partials_launch(long long m, int c, float eps, bool relu, c
     }
     {
         ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * ntiles * c, s);
-        launch_bn_finalize<0>(m, c, eps, ntiles, nullptr, part, save_mean, save_invstd, nullptr, nullptr, nullptr, nullptr, s);
+        launch_bn_finalize<0>(m, c, eps, ntiles, nullptr, part, save_mean, save_invstd, nullptr, nullptr, s);
     }
     ProfScope ps(RN50_K_BN_APPLY, 0.0, (res ? 6.0 : 4.0) * elems, s);
     const BnPlan pa = plan_rows_apply(m, c);
@@ -658,7 +653,7 @@ int rn50_bn_fwd_from_partials_launch(long long m, int c, float eps, bool relu, c
 
 int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* x, const h16* y, const float* gamma,
                        const float* save_mean, const float* save_invstd, h16* dx, h16* dres,
-                       h16* dgamma, h16* dbeta, float* dgamma32, float* dbeta32, float* ws, hipStream_t s)
+                       h16* dgamma, h16* dbeta, float* ws, hipStream_t s)
 {
     const BnPlan p = plan_rows(m, c);
     float* sums = ws + (size_t)kMaxBlocks * 2 * c;
@@ -670,7 +665,7 @@ int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* 
     }
     {
         ProfScope ps(RN50_K_BN_BWD_FINALIZE, 0.0, 8.0 * p.nblk * c, s);
-        launch_bn_finalize<1>(m, c, 0.f, p.nblk, nullptr, ws, sums, nullptr, dgamma, dbeta, dgamma32, dbeta32, s);
+        launch_bn_finalize<1>(m, c, 0.f, p.nblk, nullptr, ws, sums, nullptr, dgamma, dbeta, s);
     }
     ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, ((relu ? 6.0 : 4.0) + 2.0 + (dres ? 2.0 : 0.0)) * elems, s);
     const BnPlan pa = plan_rows_apply(m, c);
@@ -686,7 +681,7 @@ int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* 
 // were already produced by the data gradient that wrote g: combine the partials, then dx.  sums: 2c floats.
 int rn50_bn_bwd_from_partials_launch(long long m, int c, const h16* g, const h16* x, const float* gamma,
                                      const float* save_mean, const float* save_invstd, h16* dx,
-                                     float* dgamma32, float* dbeta32, const float* part, int ntiles, float* sums,
+                                     h16* dgamma, h16* dbeta, const float* part, int ntiles, float* sums,
                                      hipStream_t s)
 {
     const double elems = (double)m * c;
@@ -694,12 +689,12 @@ int rn50_bn_bwd_from_partials_launch(long long m, int c, const h16* g, const h16
         ProfScope ps(RN50_K_BN_BWD_FUSED_APPLY, 0.0, 6.0 * elems, s);
         const dim3 grid((unsigned)rn50_cdiv(m, kSliceRows), (unsigned)(c / 64));
         bn_bwd_fused_apply_kernel<<<grid, kThreads, 0, s>>>(m, c, ntiles, part, g, x, gamma, save_mean, save_invstd, dx,
-                                                            dgamma32, dbeta32);
+                                                            dgamma, dbeta);
         return rn50_check_launch();
     }
     {
         ProfScope ps(RN50_K_BN_BWD_FINALIZE, 0.0, 8.0 * ntiles * c, s);
-        launch_bn_finalize<1>(m, c, 0.f, ntiles, nullptr, part, sums, nullptr, nullptr, nullptr, dgamma32, dbeta32, s);
+        launch_bn_finalize<1>(m, c, 0.f, ntiles, nullptr, part, sums, nullptr, dgamma, dbeta, s);
     }
     ProfScope ps(RN50_K_BN_BWD_APPLY, 0.0, 6.0 * elems, s);
     const BnPlan pa = plan_rows_apply(m, c);
@@ -738,8 +733,7 @@ extern "C" int bn_relu_bwd(const bn_desc* d, const void* dy, const void* x, cons
     return rn50_bn_bwd_launch(d->m, d->c, d->relu != 0, static_cast<const h16*>(dy), static_cast<const h16*>(x),
                               static_cast<const h16*>(y), gamma, save_mean, save_invstd, static_cast<h16*>(dx),
                               d->has_residual ? static_cast<h16*>(dresidual) : nullptr, static_cast<h16*>(dgamma),
-                              static_cast<h16*>(dbeta), nullptr, nullptr, static_cast<float*>(ws),
-                              static_cast<hipStream_t>(stream));
+                              static_cast<h16*>(dbeta), static_cast<float*>(ws), static_cast<hipStream_t>(stream));
 }
 
 
@@ -759,7 +753,7 @@ extern "C" int bn_batch_moments(const bn_desc* d, const void* x, float* moments,
         bn_stats_kernel<<<p.nblk, kThreads, 0, s>>>(d->m, d->c, xh, part, p.rows_per_block);
     }
     ProfScope ps(RN50_K_BN_STATS_FINALIZE, 0.0, 8.0 * p.nblk * d->c, s);
-    launch_bn_finalize<2>(d->m, d->c, 0.f, p.nblk, xh, part, moments, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    launch_bn_finalize<2>(d->m, d->c, 0.f, p.nblk, xh, part, moments, nullptr, nullptr, nullptr, s);
     return rn50_check_launch();
 }
 
@@ -809,7 +803,7 @@ extern "C" int bn_relu_bwd_sums(const bn_desc* d, const void* dy, const void* x,
         else         bn_bwd_reduce_kernel<false><<<p.nblk, kThreads, 0, s>>>(m, c, dyh, xh, yh, save_mean, save_invstd, part, p.rows_per_block);
     }
     ProfScope ps(RN50_K_BN_BWD_FINALIZE, 0.0, 8.0 * p.nblk * c, s);
-    launch_bn_finalize<1>(m, c, 0.f, p.nblk, nullptr, part, sums, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    launch_bn_finalize<1>(m, c, 0.f, p.nblk, nullptr, part, sums, nullptr, nullptr, nullptr, s);
     return rn50_check_launch();
 }
 

@@ -553,9 +553,11 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradArgs a)
         }
 }
 
-// out[i] = sum over splits of part[s][i].  A workgroup owns 16 consecutive float4 elements; 16 split
-// lanes each add every 16th split in order, and their sums are combined in a fixed order through LDS.
-__global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const f32x4* __restrict__ part, f32x4* __restrict__ out,
+// out[i] = sum over splits of part[s][i], stored as FP32 or rounded to half (the flat FP16 gradient).  A workgroup
+// owns 16 consecutive float4 elements; 16 split lanes each add every 16th split in order, and their sums are
+// combined in a fixed order through LDS.
+template <bool kHalfOut>
+__global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const f32x4* __restrict__ part, void* __restrict__ out,
                                                                 size_t n4, int nsplit, size_t stride4)
 {
     __shared__ f32x4 red[16][16];
@@ -568,7 +570,14 @@ __global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const f32x4* __r
     __syncthreads();
     if (sl == 0 && i < n4) {
         for (int k = 1; k < 16; ++k) s += red[k][il];
-        out[i] = s;
+        if (kHalfOut) {
+            h16x4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j] = (h16)s[j];
+            static_cast<h16x4*>(out)[i] = o;
+        } else {
+            static_cast<f32x4*>(out)[i] = s;
+        }
     }
 }
 
@@ -649,13 +658,13 @@ __global__ __launch_bounds__(kThreads) void stem_pack_filter_kernel(const h16* _
     dst[i] = (s < 7 && c < 3) ? w[(((size_t)k * 7 + r) * 7 + s) * 3 + c] : (h16)0.f;
 }
 
-// stem filter gradient: acc [K][8][32] (row r, column s*4+c) -> out [K][7][7][3] (FP32)
-__global__ __launch_bounds__(kThreads) void stem_unpack_wgrad_kernel(const float* __restrict__ acc, float* __restrict__ out, int K)
+// stem filter gradient: acc [K][8][32] (row r, column s*4+c, FP32) -> out [K][7][7][3] (half)
+__global__ __launch_bounds__(kThreads) void stem_unpack_wgrad_kernel(const float* __restrict__ acc, h16* __restrict__ out, int K)
 {
     const int i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= K * 147) return;
     const int c = i % 3, s = (i / 3) % 7, r = (i / 21) % 7, k = i / 147;
-    out[i] = acc[((size_t)k * 8 + r) * 32 + s * 4 + c];
+    out[i] = (h16)acc[((size_t)k * 8 + r) * 32 + s * 4 + c];
 }
 
 int grid_for(size_t work_items)
@@ -960,29 +969,31 @@ void launch_wgrad_tile(const WgradArgs& a, int grid, hipStream_t s)
 }
 }  // namespace
 
-// floats of scratch rn50_conv_wgrad_launch needs for its per-split partial tiles (0 if it does not split)
+// floats of scratch rn50_conv_wgrad_launch needs for its per-split partial tiles
 size_t rn50_wgrad_partial_floats(const conv_desc& d)
 {
     size_t most = 0;
     for (int v = RN50_TILE_AUTO; v < RN50_NUM_WGRAD_VARIANTS; ++v) {
         const WgradPlan p = wgrad_plan(d, v);
-        const size_t f = p.nsplit > 1 ? (size_t)p.nsplit * rn50_wgrad_acc_floats(d) : 0;
+        const size_t f = (size_t)p.nsplit * rn50_wgrad_acc_floats(d);
         if (f > most) most = f;
     }
     return most;
 }
 
-// bytes of partial tiles that variant `variant` writes (and the sum kernel reads back); 0 without a pixel split
+// bytes of partial tiles that variant `variant` writes (and the sum kernel reads back)
 size_t rn50_wgrad_variant_partial_bytes(const conv_desc& d, int variant)
 {
     const WgradPlan p = wgrad_plan(d, variant);
-    return p.nsplit > 1 ? (size_t)p.nsplit * rn50_wgrad_acc_floats(d) * sizeof(float) : 0;
+    return (size_t)p.nsplit * rn50_wgrad_acc_floats(d) * sizeof(float);
 }
 
-// Filter gradient in FP32 into out (layout [K][R][S][C]; stem: [K][8][32]); every element is written.
-// partials: scratch of rn50_wgrad_partial_floats(d) floats.  For the stem, x is the padded 4-channel image.
-int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, float* out, float* partials, hipStream_t s,
-                           int variant)
+// Filter gradient: every pixel split leaves an FP32 partial tile in `partials` (rn50_wgrad_partial_floats(d) floats);
+// their sum goes to out16 as half (layout [K][R][S][C], a slice of the flat FP16 gradient) or, for the stem, to
+// out32 in FP32 (layout [K][8][32], unpacked afterwards).  Exactly one of out16 / out32 is given; every element is
+// written.  For the stem, x is the padded 4-channel image.
+int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, h16* out16, float* out32, float* partials,
+                           hipStream_t s, int variant)
 {
     WgradArgs a = {};
     const WgradPlan p = wgrad_plan(d, variant);
@@ -1001,7 +1012,7 @@ int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, floa
     }
     a.pix_per_split = p.pix_per_split;
     a.split_stride = rn50_wgrad_acc_floats(d);
-    a.out = p.nsplit > 1 ? partials : out;
+    a.out = partials;
     const int grid = p.tiles * p.nsplit;
     {
         const double bytes = 2.0 * ((double)d.n * d.h * d.w * d.c + (double)d.n * P * Q * d.k) + 4.0 * d.k * d.r * d.s * d.c;
@@ -1022,19 +1033,22 @@ int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, floa
         }
         RN50_TRY(rn50_check_launch());
     }
-    if (p.nsplit > 1) {
+    {
         const size_t n4 = a.split_stride / 4;
-        ProfScope ps(RN50_K_WGRAD_REDUCE, 0.0, 4.0 * a.split_stride * (p.nsplit + 1.0), s);
-        wgrad_reduce_kernel<<<(unsigned)((n4 + 15) / 16), kThreads, 0, s>>>(reinterpret_cast<const f32x4*>(partials),
-                                                              reinterpret_cast<f32x4*>(out), n4, p.nsplit, n4);
+        const unsigned rgrid = (unsigned)((n4 + 15) / 16);
+        ProfScope ps(RN50_K_WGRAD_REDUCE, 0.0, a.split_stride * (4.0 * p.nsplit + (out16 ? 2.0 : 4.0)), s);
+        if (out16)
+            wgrad_reduce_kernel<true><<<rgrid, kThreads, 0, s>>>(reinterpret_cast<const f32x4*>(partials), out16, n4, p.nsplit, n4);
+        else
+            wgrad_reduce_kernel<false><<<rgrid, kThreads, 0, s>>>(reinterpret_cast<const f32x4*>(partials), out32, n4, p.nsplit, n4);
         RN50_TRY(rn50_check_launch());
     }
     return RN50_OK;
 }
 
-int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, float* out, hipStream_t s)
+int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, h16* out, hipStream_t s)
 {
-    ProfScope ps(RN50_K_STEM_MISC, 0.0, (double)d.k * (147 + 256) * 4, s);
+    ProfScope ps(RN50_K_STEM_MISC, 0.0, (double)d.k * (147 * 2 + 256 * 4), s);
     stem_unpack_wgrad_kernel<<<rn50_cdiv(d.k * 147, kThreads), kThreads, 0, s>>>(acc, out, d.k);
     return rn50_check_launch();
 }
@@ -1042,22 +1056,6 @@ int rn50_stem_unpack_wgrad(const conv_desc& d, const float* acc, float* out, hip
 // ------------------------------------------------------------------------------------------------
 // C ABI
 // ------------------------------------------------------------------------------------------------
-namespace {
-// The stand-alone entry points pick a kernel variant by a shape heuristic.  For tests and experiments the
-// environment can name one instead: RN50_GATHER_TILE (forward and data gradient, an RN50_TILE_* value) and
-// RN50_WGRAD_VARIANT (0 .. RN50_NUM_WGRAD_VARIANTS-1).  A value that is absent, malformed, out of range or not
-// applicable to the shape leaves the heuristic in charge.
-int variant_from_env(const char* name, int count)
-{
-    const char* v = getenv(name);
-    if (!v || !*v) return RN50_TILE_AUTO;
-    char* end = nullptr;
-    const long x = strtol(v, &end, 10);
-    if (*end != 0 || x < 0 || x >= count) return RN50_TILE_AUTO;
-    return (int)x;
-}
-}  // namespace
-
 extern "C" size_t conv_workspace_bytes(const conv_desc* d, int which)
 {
     if (rn50_conv_validate(d) != RN50_OK) return 0;
@@ -1068,9 +1066,8 @@ extern "C" size_t conv_workspace_bytes(const conv_desc* d, int which)
         case RN50_CONV_DGRAD:
             return stem ? 0 : rn50_round_up((size_t)d->k * d->r * d->s * d->c * sizeof(h16), 256);
         case RN50_CONV_WGRAD: {
-            size_t b = rn50_round_up(rn50_wgrad_acc_floats(*d) * sizeof(float), 256) +
-                       rn50_round_up(rn50_wgrad_partial_floats(*d) * sizeof(float), 256);
-            if (stem) b += rn50_stem_padded_bytes(*d) + rn50_round_up((size_t)d->k * 147 * sizeof(float), 256);
+            size_t b = rn50_round_up(rn50_wgrad_partial_floats(*d) * sizeof(float), 256);
+            if (stem) b += rn50_round_up(rn50_wgrad_acc_floats(*d) * sizeof(float), 256) + rn50_stem_padded_bytes(*d);
             return b;
         }
         default: return 0;
@@ -1087,7 +1084,16 @@ static int check_common(const conv_desc* d, const void* p0, const void* p1, cons
     return RN50_OK;
 }
 
-extern "C" int conv_fwd(const conv_desc* d, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, void* stream)
+extern "C" int rn50_conv_variant_count(int which)
+{
+    if (which == RN50_CONV_FWD || which == RN50_CONV_DGRAD) return RN50_NUM_GATHER_TILES;
+    return which == RN50_CONV_WGRAD ? RN50_NUM_WGRAD_VARIANTS : 0;
+}
+
+// The stand-alone entry points pick a kernel variant by a shape heuristic; the *_variant forms name one
+// (a value that is out of range or does not fit the shape leaves the heuristic in charge).
+extern "C" int conv_fwd_variant(const conv_desc* d, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, int variant,
+                                void* stream)
 {
     RN50_TRY(check_common(d, x, w, y, ws, ws_bytes, RN50_CONV_FWD));
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1099,10 +1105,16 @@ extern "C" int conv_fwd(const conv_desc* d, const void* x, const void* w, void* 
         return rn50_conv_fwd_launch(*d, padded, packed, static_cast<h16*>(y), s, nullptr, nullptr, RN50_TILE_AUTO);
     }
     return rn50_conv_fwd_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(w), static_cast<h16*>(y), s, nullptr,
-                                nullptr, variant_from_env("RN50_GATHER_TILE", RN50_NUM_GATHER_TILES));
+                                nullptr, variant);
 }
 
-extern "C" int conv_dgrad(const conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, void* stream)
+extern "C" int conv_fwd(const conv_desc* d, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, void* stream)
+{
+    return conv_fwd_variant(d, x, w, y, ws, ws_bytes, RN50_TILE_AUTO, stream);
+}
+
+extern "C" int conv_dgrad_variant(const conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes,
+                                  int variant, void* stream)
 {
     RN50_TRY(rn50_conv_validate(d));
     if (rn50_conv_is_stem(*d)) return RN50_ERR_SHAPE;   // the images need no gradient
@@ -1111,27 +1123,33 @@ extern "C" int conv_dgrad(const conv_desc* d, const void* dy, const void* w, voi
     h16* wt = static_cast<h16*>(ws);
     RN50_TRY(rn50_transpose_filter(*d, static_cast<const h16*>(w), wt, s));
     return rn50_conv_dgrad_launch(*d, static_cast<const h16*>(dy), wt, nullptr, static_cast<h16*>(dx), s, nullptr, nullptr,
-                                  variant_from_env("RN50_GATHER_TILE", RN50_NUM_GATHER_TILES));
+                                  variant);
+}
+
+extern "C" int conv_dgrad(const conv_desc* d, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes, void* stream)
+{
+    return conv_dgrad_variant(d, dy, w, dx, ws, ws_bytes, RN50_TILE_AUTO, stream);
+}
+
+extern "C" int conv_wgrad_variant(const conv_desc* d, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes,
+                                  int variant, void* stream)
+{
+    RN50_TRY(check_common(d, x, dy, dw, ws, ws_bytes, RN50_CONV_WGRAD));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* partials = static_cast<float*>(ws);
+    char* p = static_cast<char*>(ws) + rn50_round_up(rn50_wgrad_partial_floats(*d) * sizeof(float), 256);
+    if (rn50_conv_is_stem(*d)) {
+        float* acc = reinterpret_cast<float*>(p);
+        h16* padded = reinterpret_cast<h16*>(p + rn50_round_up(rn50_wgrad_acc_floats(*d) * sizeof(float), 256));
+        RN50_TRY(rn50_stem_pad_image(*d, static_cast<const h16*>(x), padded, s));
+        RN50_TRY(rn50_conv_wgrad_launch(*d, padded, static_cast<const h16*>(dy), nullptr, acc, partials, s, RN50_TILE_AUTO));
+        return rn50_stem_unpack_wgrad(*d, acc, static_cast<h16*>(dw), s);
+    }
+    return rn50_conv_wgrad_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(dy), static_cast<h16*>(dw), nullptr,
+                                  partials, s, (variant >= 0 && variant < RN50_NUM_WGRAD_VARIANTS) ? variant : RN50_TILE_AUTO);
 }
 
 extern "C" int conv_wgrad(const conv_desc* d, const void* x, const void* dy, void* dw, void* ws, size_t ws_bytes, void* stream)
 {
-    RN50_TRY(check_common(d, x, dy, dw, ws, ws_bytes, RN50_CONV_WGRAD));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    float* acc = static_cast<float*>(ws);
-    const size_t acc_floats = rn50_wgrad_acc_floats(*d);
-    char* p = static_cast<char*>(ws) + rn50_round_up(acc_floats * sizeof(float), 256);
-    float* partials = reinterpret_cast<float*>(p);
-    p += rn50_round_up(rn50_wgrad_partial_floats(*d) * sizeof(float), 256);
-    if (rn50_conv_is_stem(*d)) {
-        h16* padded = reinterpret_cast<h16*>(p);
-        float* unpacked = reinterpret_cast<float*>(p + rn50_stem_padded_bytes(*d));
-        RN50_TRY(rn50_stem_pad_image(*d, static_cast<const h16*>(x), padded, s));
-        RN50_TRY(rn50_conv_wgrad_launch(*d, padded, static_cast<const h16*>(dy), acc, partials, s, RN50_TILE_AUTO));
-        RN50_TRY(rn50_stem_unpack_wgrad(*d, acc, unpacked, s));
-        return rn50_cast_f32_to_h16(unpacked, static_cast<h16*>(dw), (size_t)d->k * 147, s);
-    }
-    RN50_TRY(rn50_conv_wgrad_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(dy), acc, partials, s,
-                                    variant_from_env("RN50_WGRAD_VARIANT", RN50_NUM_WGRAD_VARIANTS)));
-    return rn50_cast_f32_to_h16(acc, static_cast<h16*>(dw), acc_floats, s);
+    return conv_wgrad_variant(d, x, dy, dw, ws, ws_bytes, RN50_TILE_AUTO, stream);
 }

@@ -62,32 +62,15 @@ bool lars_layout(const rn50_lars_segment* segs, int nseg, Layout& L)
     return true;
 }
 
-// gradient element as the optimizer sees it: the FP16 value (an FP32 accumulator is rounded to half first)
-template <bool kF32Grad>
-__device__ __forceinline__ void load8(const void* g, size_t i, float (&out)[8], h16x8& gh)
+__device__ __forceinline__ void load8(const h16* g, size_t i, float (&out)[8])
 {
-    if (kF32Grad) {
-        const f32x4 a = *reinterpret_cast<const f32x4*>(static_cast<const float*>(g) + i);
-        const f32x4 b = *reinterpret_cast<const f32x4*>(static_cast<const float*>(g) + i + 4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { gh[j] = (h16)a[j]; gh[4 + j] = (h16)b[j]; }
-    } else {
-        gh = *reinterpret_cast<const h16x8*>(static_cast<const h16*>(g) + i);
-    }
+    const h16x8 gh = *reinterpret_cast<const h16x8*>(g + i);
 #pragma unroll
     for (int j = 0; j < 8; ++j) out[j] = (float)gh[j];
 }
 
-template <bool kF32Grad>
-__device__ __forceinline__ float load1(const void* g, size_t i, h16& gh)
-{
-    gh = kF32Grad ? (h16) static_cast<const float*>(g)[i] : static_cast<const h16*>(g)[i];
-    return (float)gh;
-}
-
-template <bool kF32Grad>
 __global__ __launch_bounds__(kThreads) void lars_norm_kernel(const LarsBlock* __restrict__ blocks,
-                                                             const int* __restrict__ seg_use, const void* __restrict__ g,
+                                                             const int* __restrict__ seg_use, const h16* __restrict__ g,
                                                              float grad_scale, const float* __restrict__ w,
                                                              float* __restrict__ partial)
 {
@@ -99,8 +82,7 @@ __global__ __launch_bounds__(kThreads) void lars_norm_kernel(const LarsBlock* __
     if (e0 + 8 <= b.count) {
         const size_t i = (size_t)b.begin + e0;
         float gv[8];
-        h16x8 gh;
-        load8<kF32Grad>(g, i, gv, gh);
+        load8(g, i, gv);
         const f32x4 w0 = *reinterpret_cast<const f32x4*>(w + i), w1 = *reinterpret_cast<const f32x4*>(w + i + 4);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -110,8 +92,7 @@ __global__ __launch_bounds__(kThreads) void lars_norm_kernel(const LarsBlock* __
         }
     } else {
         for (unsigned e = e0; e < b.count; ++e) {
-            h16 gh;
-            const float a = load1<kF32Grad>(g, (size_t)b.begin + e, gh) * grad_scale;
+            const float a = (float)g[(size_t)b.begin + e] * grad_scale;
             const float x = w[(size_t)b.begin + e];
             sw += x * x; sg += a * a;
         }
@@ -161,10 +142,10 @@ __global__ __launch_bounds__(64) void lars_rate_kernel(int nseg, const int* __re
     }
 }
 
-template <bool kF32Grad, bool kWriteLowp>
+template <bool kWriteLowp>
 __global__ __launch_bounds__(kThreads) void lars_update_kernel(const LarsBlock* __restrict__ blocks,
-                                                               const float* __restrict__ scale, const void* __restrict__ g,
-                                                               h16* __restrict__ g16, float grad_scale, float* __restrict__ w,
+                                                               const float* __restrict__ scale, const h16* __restrict__ g,
+                                                               float grad_scale, float* __restrict__ w,
                                                                float* __restrict__ v, h16* __restrict__ w16, float mu)
 {
     const LarsBlock b = blocks[blockIdx.x];
@@ -173,8 +154,8 @@ __global__ __launch_bounds__(kThreads) void lars_update_kernel(const LarsBlock* 
     if (e0 + 8 <= b.count) {
         const size_t i = (size_t)b.begin + e0;
         float gv[8];
-        h16x8 gh, lo;
-        load8<kF32Grad>(g, i, gv, gh);
+        h16x8 lo;
+        load8(g, i, gv);
         f32x4 w0 = *reinterpret_cast<const f32x4*>(w + i), w1 = *reinterpret_cast<const f32x4*>(w + i + 4);
         f32x4 v0 = *reinterpret_cast<const f32x4*>(v + i), v1 = *reinterpret_cast<const f32x4*>(v + i + 4);
 #pragma unroll
@@ -190,17 +171,14 @@ __global__ __launch_bounds__(kThreads) void lars_update_kernel(const LarsBlock* 
         }
         *reinterpret_cast<f32x4*>(w + i) = w0; *reinterpret_cast<f32x4*>(w + i + 4) = w1;
         *reinterpret_cast<f32x4*>(v + i) = v0; *reinterpret_cast<f32x4*>(v + i + 4) = v1;
-        if (kF32Grad) *reinterpret_cast<h16x8*>(g16 + i) = gh;
         if (kWriteLowp) *reinterpret_cast<h16x8*>(w16 + i) = lo;
     } else {
         for (unsigned e = e0; e < b.count; ++e) {
             const size_t i = (size_t)b.begin + e;
-            h16 gh;
-            const float gp = load1<kF32Grad>(g, i, gh) * grad_scale + decay * w[i];
+            const float gp = (float)g[i] * grad_scale + decay * w[i];
             const float vn = mu * v[i] + step * gp;
             const float wn = w[i] - vn;
             v[i] = vn; w[i] = wn;
-            if (kF32Grad) g16[i] = gh;
             if (kWriteLowp) w16[i] = (h16)wn;
         }
     }
@@ -265,15 +243,13 @@ extern "C" int lars_plan_create(lars_plan** out, const rn50_lars_segment* segs, 
 
 extern "C" void lars_plan_destroy(lars_plan* plan) { delete plan; }
 
-// grad: FP16 gradient, or (internal, f32_grad) FP32 accumulators whose half-rounded values are also written to g16
-int rn50_lars_launch(const lars_plan* p, const void* grad, bool f32_grad, h16* g16, float grad_scale, float* w, float* v,
-                     h16* w16, float lr, float mu, float wd, float eta, float eps, float* rates_out, hipStream_t s)
+int rn50_lars_launch(const lars_plan* p, const h16* grad, float grad_scale, float* w, float* v, h16* w16, float lr, float mu,
+                     float wd, float eta, float eps, float* rates_out, hipStream_t s)
 {
     if (p->nblocks == 0) return RN50_OK;
     {
-        ProfScope ps(RN50_K_LARS_NORM, 0.0, (f32_grad ? 8.0 : 6.0) * p->covered, s);
-        if (f32_grad) lars_norm_kernel<true><<<p->nblocks, kThreads, 0, s>>>(p->blocks, p->seg_use, grad, grad_scale, w, p->partial);
-        else lars_norm_kernel<false><<<p->nblocks, kThreads, 0, s>>>(p->blocks, p->seg_use, grad, grad_scale, w, p->partial);
+        ProfScope ps(RN50_K_LARS_NORM, 0.0, 6.0 * p->covered, s);
+        lars_norm_kernel<<<p->nblocks, kThreads, 0, s>>>(p->blocks, p->seg_use, grad, grad_scale, w, p->partial);
         RN50_TRY(rn50_check_launch());
     }
     {
@@ -281,14 +257,9 @@ int rn50_lars_launch(const lars_plan* p, const void* grad, bool f32_grad, h16* g
         lars_rate_kernel<<<p->nseg, 64, 0, s>>>(p->nseg, p->seg_first, p->seg_use, p->partial, lr, wd, eta, eps, p->scale, rates_out);
         RN50_TRY(rn50_check_launch());
     }
-    ProfScope ps(RN50_K_LARS_UPDATE, 0.0, ((f32_grad ? 22.0 : 18.0) + (w16 ? 2.0 : 0.0)) * p->covered, s);
-    if (f32_grad) {
-        if (w16) lars_update_kernel<true, true><<<p->nblocks, kThreads, 0, s>>>(p->blocks, p->scale, grad, g16, grad_scale, w, v, w16, mu);
-        else lars_update_kernel<true, false><<<p->nblocks, kThreads, 0, s>>>(p->blocks, p->scale, grad, g16, grad_scale, w, v, nullptr, mu);
-    } else {
-        if (w16) lars_update_kernel<false, true><<<p->nblocks, kThreads, 0, s>>>(p->blocks, p->scale, grad, nullptr, grad_scale, w, v, w16, mu);
-        else lars_update_kernel<false, false><<<p->nblocks, kThreads, 0, s>>>(p->blocks, p->scale, grad, nullptr, grad_scale, w, v, nullptr, mu);
-    }
+    ProfScope ps(RN50_K_LARS_UPDATE, 0.0, (18.0 + (w16 ? 2.0 : 0.0)) * p->covered, s);
+    if (w16) lars_update_kernel<true><<<p->nblocks, kThreads, 0, s>>>(p->blocks, p->scale, grad, grad_scale, w, v, w16, mu);
+    else lars_update_kernel<false><<<p->nblocks, kThreads, 0, s>>>(p->blocks, p->scale, grad, grad_scale, w, v, nullptr, mu);
     return rn50_check_launch();
 }
 
@@ -303,6 +274,6 @@ extern "C" int lars_momentum_flat(const lars_plan* plan, const void* grad, int g
     RN50_REQUIRE_ALIGNED(grad); RN50_REQUIRE_ALIGNED(master_w); RN50_REQUIRE_ALIGNED(momentum);
     RN50_REQUIRE_ALIGNED(w_lowp_out);
     if (!(eta > 0.f) || eps < 0.f) return RN50_ERR_SHAPE;
-    return rn50_lars_launch(plan, grad, false, nullptr, grad_scale, master_w, momentum, static_cast<h16*>(w_lowp_out), lr, mu,
-                            wd, eta, eps, rates_out, static_cast<hipStream_t>(stream));
+    return rn50_lars_launch(plan, static_cast<const h16*>(grad), grad_scale, master_w, momentum, static_cast<h16*>(w_lowp_out),
+                            lr, mu, wd, eta, eps, rates_out, static_cast<hipStream_t>(stream));
 }

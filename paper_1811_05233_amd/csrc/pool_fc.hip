@@ -157,10 +157,10 @@ __global__ __launch_bounds__(kThreads) void fc_fwd_kernel(int B, int Cin, int Co
     }
 }
 
-// dWt[j,c] = sum_i dz[i,j]*a[i,c]  (FP32 out);  db[j] = sum_i dz[i,j]
+// dWt[j,c] = sum_i dz[i,j]*a[i,c];  db[j] = sum_i dz[i,j]  (FP32 sums, stored as half)
 __global__ __launch_bounds__(kThreads) void fc_bwd_w_kernel(int B, int Cin, int Cout, const h16* __restrict__ a,
-                                                            const h16* __restrict__ dz, float* __restrict__ dWt,
-                                                            float* __restrict__ db)
+                                                            const h16* __restrict__ dz, h16* __restrict__ dWt,
+                                                            h16* __restrict__ db)
 {
     const int G = Cin / 8;
     const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
@@ -175,10 +175,11 @@ __global__ __launch_bounds__(kThreads) void fc_bwd_w_kernel(int B, int Cin, int 
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] += d * (float)av[e];
     }
-    float* o = dWt + (size_t)j * Cin + g * 8;
+    h16x8 o;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = acc[e];
-    if (g == 0) db[j] = sb;
+    for (int e = 0; e < 8; ++e) o[e] = (h16)acc[e];
+    *reinterpret_cast<h16x8*>(dWt + (size_t)j * Cin + g * 8) = o;
+    if (g == 0) db[j] = (h16)sb;
 }
 
 // da[i,c] = sum_j dz[i,j]*Wt[j,c] rounded to half, then spread over the HW positions of the
@@ -274,7 +275,7 @@ int rn50_fc_fwd(int B, int Cin, int Cout, const h16* a, const h16* Wt, const flo
     return rn50_check_launch();
 }
 
-int rn50_fc_bwd(int B, int Cin, int Cout, int HW, const h16* a, const h16* Wt, const h16* dz, float* dWt, float* db,
+int rn50_fc_bwd(int B, int Cin, int Cout, int HW, const h16* a, const h16* Wt, const h16* dz, h16* dWt, h16* db,
                 h16* dx, hipStream_t s)
 {
     ProfScope ps(RN50_K_FC, 4.0 * B * Cin * Cout, 2.0 * Cin * (B + Cout) + 4.0 * Cin * Cout + 2.0 * B * Cin * HW, s);

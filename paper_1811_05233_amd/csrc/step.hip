@@ -175,7 +175,6 @@ struct rn50_ctx {
     float* logits = nullptr;
     h16* dlogits = nullptr;
     h16* wt_all = nullptr;        // transposed filters
-    float* grad32 = nullptr;      // flat FP32 gradient accumulators
     float* bn_ws = nullptr;
     float* bn_ws_side = nullptr;  // BN partial sums of the projection branch (forward, side stream)
     float* wgrad_part = nullptr;  // per-split partial tiles of the filter gradient
@@ -192,6 +191,7 @@ struct rn50_ctx {
     hipEvent_t join_event = nullptr;
     hipEvent_t transpose_fork = nullptr, transpose_done = nullptr;
     bool tuning = false;                   // rn50_autotune: every conv launch site times its variants
+    std::string tune_report;               // what the last rn50_autotune measured, one line per launch site and candidate
     hipEvent_t tune_e0 = nullptr, tune_e1 = nullptr;
     size_t max_act = 0, wt_elems = 0;
 };
@@ -246,7 +246,6 @@ size_t carve(rn50_ctx& c, char* base)
     c.logits = reinterpret_cast<float*>(take((size_t)cfg.batch * cfg.classes * sizeof(float)));
     c.dlogits = reinterpret_cast<h16*>(take((size_t)cfg.batch * cfg.classes * sizeof(h16)));
     c.wt_all = reinterpret_cast<h16*>(take(wt_elems * sizeof(h16)));
-    c.grad32 = reinterpret_cast<float*>(take(rn50_round_up(L.param_count, 8) * sizeof(float)));
     size_t bn_ws_floats = rn50_bn_ws_floats(max_c);
     for (const ConvLayer& l : L.layers) {
         if (rn50_conv_stats_floats(l.d) > bn_ws_floats) bn_ws_floats = rn50_conv_stats_floats(l.d);
@@ -449,7 +448,7 @@ int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch,
                    G penalty_ms = no_penalty)
 {
     if (!c.tuning) return launch(*choice);
-    static const bool log = getenv("RN50_TUNE_LOG") != nullptr;     // per-candidate times on stderr
+    char line[160];
     float best_ms = 1e30f;
     int best = RN50_TILE_AUTO;
     for (int cand = 0; cand < ncand; ++cand) {
@@ -465,9 +464,11 @@ int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch,
         if (e != hipSuccess) return rn50_hip_fail(e);
         ms = ms * 0.5f + penalty_ms(cand);
         if (ms < best_ms) { best_ms = ms; best = cand; }
-        if (log) fprintf(stderr, "tune %s %s cand %d: %.1f us\n", layer, what, cand, ms * 1000.f);
+        snprintf(line, sizeof line, "tune %s %s cand %d: %.1f us\n", layer, what, cand, ms * 1000.f);
+        c.tune_report += line;
     }
-    if (log) fprintf(stderr, "tune %s %s -> %d (%.1f us)\n", layer, what, best, best_ms * 1000.f);
+    snprintf(line, sizeof line, "tune %s %s -> %d (%.1f us)\n", layer, what, best, best_ms * 1000.f);
+    c.tune_report += line;
     *choice = best;
     return launch(best);
 }
@@ -486,6 +487,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     const rn50_config& cfg = c.cfg;
     Layout& L = c.L;
     const h16* w16 = static_cast<const h16*>(w_lowp);
+    h16* g16 = static_cast<h16*>(grad_lowp);      // every gradient kernel stores its slice of the flat FP16 gradient itself
     const int B = cfg.batch;
 
     // ---- per-step preparation: re-lay the filters for the data gradient.  Only the backward pass needs
@@ -565,18 +567,18 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         hipError_t e = hipStreamWaitEvent(s, c.transpose_done, 0);
         if (e != hipSuccess) return rn50_hip_fail(e);
     }
-    RN50_TRY(rn50_fc_bwd(B, L.feat, cfg.classes, HW, c.feat, w16 + L.fcw_off, c.dlogits, c.grad32 + L.fcw_off,
-                         c.grad32 + L.fcb_off, c.head_din, s));
+    RN50_TRY(rn50_fc_bwd(B, L.feat, cfg.classes, HW, c.feat, w16 + L.fcw_off, c.dlogits, g16 + L.fcw_off, g16 + L.fcb_off,
+                         c.head_din, s));
 
     // The filter gradient of a conv is queued on the side stream as soon as d(conv output) exists (it only
     // needs that and forward activations), so that it overlaps with the data-gradient / BN-backward chain.
-    auto fork_wgrad = [&](ConvLayer& l, const h16* in, float* out) -> int {
+    auto fork_wgrad = [&](ConvLayer& l, const h16* in, h16* out16, float* out32) -> int {
         hipEvent_t ev = c.fork_events[&l - &L.layers[0]];
         hipError_t e = hipEventRecord(ev, s);
         if (e == hipSuccess) e = hipStreamWaitEvent(c.side, ev, 0);
         if (e != hipSuccess) return rn50_hip_fail(e);
         return launch_or_tune(c, c.side, l.d.c == 3 ? 3 : RN50_NUM_WGRAD_VARIANTS, &l.wgrad_variant, [&](int variant) {
-            return rn50_conv_wgrad_launch(l.d, in, l.dconv, out, c.wgrad_part, c.side, variant);
+            return rn50_conv_wgrad_launch(l.d, in, l.dconv, out16, out32, c.wgrad_part, c.side, variant);
         }, "wgrad", l.name.c_str(), [&](int variant) {
             // the partial tiles of a pixel split are written and read back through HBM, which the rest of the
             // step competes for; timing the variant on its own does not show that, so the traffic is charged at
@@ -588,8 +590,8 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     // BN backward, stand-alone form (reduce, finalize, apply): dy -> l.dconv (and dres)
     auto bn_bwd_std = [&](ConvLayer& l, const h16* dy, bool relu, h16* dres) -> int {
         return rn50_bn_bwd_launch((long long)l.d.n * l.P * l.Q, l.d.k, relu, dy, l.conv_out, l.bn_out,
-                                  master_w + l.gamma_off, l.mean, l.invstd, l.dconv, dres, nullptr, nullptr,
-                                  c.grad32 + l.gamma_off, c.grad32 + l.beta_off, c.bn_ws, s);
+                                  master_w + l.gamma_off, l.mean, l.invstd, l.dconv, dres, g16 + l.gamma_off,
+                                  g16 + l.beta_off, c.bn_ws, s);
     };
     // BN backward when the data gradient that produced g already applied the ReLU mask and left the
     // per-tile sums (sum g, sum g*xhat) in c.bn_ws: finalize + apply only
@@ -598,8 +600,7 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         float* sums = c.bn_ws + (size_t)fused_tiles * 2 * l.d.k;
         return rn50_bn_bwd_from_partials_launch((long long)l.d.n * l.P * l.Q, l.d.k, g, l.conv_out,
                                                 master_w + l.gamma_off, l.mean, l.invstd, l.dconv,
-                                                c.grad32 + l.gamma_off, c.grad32 + l.beta_off, c.bn_ws, fused_tiles,
-                                                sums, s);
+                                                g16 + l.gamma_off, g16 + l.beta_off, c.bn_ws, fused_tiles, sums, s);
     };
     // data gradient of conv l into l.din.  prev (nullable) = the layer whose BN+ReLU output `in` is l's input:
     // then the result is masked by in > 0 and the BN-backward sums of prev are formed in the epilogue.
@@ -632,25 +633,25 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         const h16* gres;                                              // masked gradient for the shortcut
         if (dY_fused) { RN50_TRY(bn_bwd_fused(l3, dY)); gres = dY; }
         else { RN50_TRY(bn_bwd_std(l3, dY, true, l3.dres)); gres = l3.dres; }
-        RN50_TRY(fork_wgrad(l3, l2.bn_out, c.grad32 + l3.w_off));
+        RN50_TRY(fork_wgrad(l3, l2.bn_out, g16 + l3.w_off, nullptr));
         RN50_TRY(dgrad(l3, nullptr, &l2, l2.bn_out));
         RN50_TRY(bn_bwd_fused(l2, l3.din));
-        RN50_TRY(fork_wgrad(l2, l1.bn_out, c.grad32 + l2.w_off));
+        RN50_TRY(fork_wgrad(l2, l1.bn_out, g16 + l2.w_off, nullptr));
         RN50_TRY(dgrad(l2, nullptr, &l1, l1.bn_out));
         RN50_TRY(bn_bwd_fused(l1, l2.din));
-        RN50_TRY(fork_wgrad(l1, block_in[bi], c.grad32 + l1.w_off));
+        RN50_TRY(fork_wgrad(l1, block_in[bi], g16 + l1.w_off, nullptr));
         if (b.proj >= 0) {
             ConvLayer& lp = L.layers[b.proj];
             if (dY_fused) {
                 // the data gradient that produced gres also left this BN's sums (in c.bn_ws_side, same tile count)
                 RN50_TRY(rn50_bn_bwd_from_partials_launch((long long)lp.d.n * lp.P * lp.Q, lp.d.k, gres, lp.conv_out,
                                                           master_w + lp.gamma_off, lp.mean, lp.invstd, lp.dconv,
-                                                          c.grad32 + lp.gamma_off, c.grad32 + lp.beta_off, c.bn_ws_side,
+                                                          g16 + lp.gamma_off, g16 + lp.beta_off, c.bn_ws_side,
                                                           proj_tiles, c.bn_ws_side + (size_t)proj_tiles * 2 * lp.d.k, s));
             } else {
                 RN50_TRY(bn_bwd_std(lp, gres, false, nullptr));
             }
-            RN50_TRY(fork_wgrad(lp, block_in[bi], c.grad32 + lp.w_off));
+            RN50_TRY(fork_wgrad(lp, block_in[bi], g16 + lp.w_off, nullptr));
             if (need_in) {
                 RN50_TRY(dgrad(lp, nullptr, nullptr, nullptr));
                 RN50_TRY(dgrad(l1, lp.din, below, block_in[bi], lp.din_compact, below_proj));   // main path + projection shortcut
@@ -666,26 +667,24 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         ConvLayer& st = L.layers[0];
         RN50_TRY(rn50_maxpool_bwd(B, st.P, st.Q, st.d.k, dY, c.pool_arg, c.pool_din, s));
         RN50_TRY(rn50_bn_bwd_launch((long long)B * st.P * st.Q, st.d.k, true, c.pool_din, st.conv_out, st.bn_out,
-                                    master_w + st.gamma_off, st.mean, st.invstd, st.dconv, nullptr, nullptr, nullptr,
-                                    c.grad32 + st.gamma_off, c.grad32 + st.beta_off, c.bn_ws, s));
-        RN50_TRY(fork_wgrad(st, c.stem_padded, c.stem_wacc));
-        RN50_TRY(rn50_stem_unpack_wgrad(st.d, c.stem_wacc, c.grad32 + st.w_off, c.side));
+                                    master_w + st.gamma_off, st.mean, st.invstd, st.dconv, nullptr, g16 + st.gamma_off,
+                                    g16 + st.beta_off, c.bn_ws, s));
+        RN50_TRY(fork_wgrad(st, c.stem_padded, nullptr, c.stem_wacc));
+        RN50_TRY(rn50_stem_unpack_wgrad(st.d, c.stem_wacc, g16 + st.w_off, c.side));
     }
-    {   // join: everything queued on the side stream precedes the gradient cast and the update
+    {   // join: everything queued on the side stream precedes the update
         hipError_t e = hipEventRecord(c.join_event, c.side);
         if (e == hipSuccess) e = hipStreamWaitEvent(s, c.join_event, 0);
         if (e != hipSuccess) return rn50_hip_fail(e);
     }
 
-    // ================= flat FP16 gradient, update =================
+    // ================= update (the flat FP16 gradient is complete) =================
     if (hp && hp->lars_eta > 0.f)
-        return rn50_lars_launch(c.lars, c.grad32, true, static_cast<h16*>(grad_lowp), hp->grad_scale, master_w, momentum,
-                                static_cast<h16*>(w_lowp), hp->lr, hp->momentum, hp->wd, hp->lars_eta, hp->lars_eps,
-                                nullptr, s);
+        return rn50_lars_launch(c.lars, g16, hp->grad_scale, master_w, momentum, static_cast<h16*>(w_lowp), hp->lr,
+                                hp->momentum, hp->wd, hp->lars_eta, hp->lars_eps, nullptr, s);
     if (hp)
-        return rn50_sgd_from_f32_launch(L.param_count, c.grad32, static_cast<h16*>(grad_lowp), hp->grad_scale, master_w,
-                                        momentum, static_cast<h16*>(w_lowp), hp->lr, hp->momentum, hp->wd, s);
-    RN50_TRY(rn50_cast_f32_to_h16(c.grad32, static_cast<h16*>(grad_lowp), L.param_count, s));
+        return sgd_momentum_flat(L.param_count, g16, RN50_F16, hp->grad_scale, master_w, momentum, w_lowp, hp->lr, hp->momentum,
+                                 hp->wd, stream);
     return RN50_OK;
 }
 
@@ -693,10 +692,54 @@ extern "C" int rn50_autotune(rn50_ctx* ctx, const void* images, const int32_t* l
                              void* grad_lowp, float* loss_out, void* stream)
 {
     RN50_REQUIRE_PTR(ctx);
+    ctx->tune_report.clear();
     ctx->tuning = true;
     const int rc = rn50_step(ctx, images, labels, master_w, nullptr, w_lowp, grad_lowp, nullptr, loss_out, stream);
     ctx->tuning = false;
     if (rc != RN50_OK) return rc;
     hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RN50_OK : rn50_hip_fail(e);
+}
+
+// Kernel variants in use, three numbers per convolution in network order: forward tile, data-gradient tile,
+// filter-gradient variant (RN50_TILE_AUTO = the launcher's heuristic).
+extern "C" int rn50_get_tuning(rn50_ctx* ctx, int* table, int capacity)
+{
+    RN50_REQUIRE_PTR(ctx);
+    const int n = 3 * (int)ctx->L.layers.size();
+    if (!table) return n;
+    if (capacity < n) return RN50_ERR_SHAPE;
+    for (size_t i = 0; i < ctx->L.layers.size(); ++i) {
+        const ConvLayer& l = ctx->L.layers[i];
+        table[3 * i] = l.fwd_tile; table[3 * i + 1] = l.dgrad_tile; table[3 * i + 2] = l.wgrad_variant;
+    }
+    return n;
+}
+
+extern "C" int rn50_set_tuning(rn50_ctx* ctx, const int* table, int n)
+{
+    RN50_REQUIRE_PTR(ctx); RN50_REQUIRE_PTR(table);
+    if (n != 3 * (int)ctx->L.layers.size()) return RN50_ERR_SHAPE;
+    for (int i = 0; i < n; ++i) {
+        const int limit = (i % 3 == 2) ? RN50_NUM_WGRAD_VARIANTS : RN50_NUM_GATHER_TILES;
+        if (table[i] < RN50_TILE_AUTO || table[i] >= limit) return RN50_ERR_SHAPE;
+    }
+    for (size_t i = 0; i < ctx->L.layers.size(); ++i) {
+        ConvLayer& l = ctx->L.layers[i];
+        l.fwd_tile = table[3 * i]; l.dgrad_tile = table[3 * i + 1]; l.wgrad_variant = table[3 * i + 2];
+    }
+    return RN50_OK;
+}
+
+// Text of what the last rn50_autotune on this context measured.  Copies at most cap-1 characters (NUL-terminated)
+// and returns the full length.
+extern "C" size_t rn50_tuning_report(rn50_ctx* ctx, char* buf, size_t cap)
+{
+    if (!ctx) return 0;
+    if (buf && cap > 0) {
+        const size_t n = ctx->tune_report.size() < cap - 1 ? ctx->tune_report.size() : cap - 1;
+        memcpy(buf, ctx->tune_report.data(), n);
+        buf[n] = 0;
+    }
+    return ctx->tune_report.size();
 }

@@ -73,55 +73,6 @@ __global__ __launch_bounds__(kThreads) void sgd_momentum_kernel(
     }
 }
 
-// Same update, fed by the FP32 gradient buffer of the whole-step driver: the gradient is first rounded
-// to half (that rounded value is the flat FP16 gradient, written to g16), then used exactly as above.
-__global__ __launch_bounds__(kThreads) void sgd_momentum_f32grad_kernel(
-    size_t n, const float* __restrict__ g32, h16* __restrict__ g16, float grad_scale, float* __restrict__ w,
-    float* __restrict__ v, h16* __restrict__ w16, float lr, float mu, float wd)
-{
-    const size_t nvec = n / 8;
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
-        const f32x4 g0 = reinterpret_cast<const f32x4*>(g32)[2 * i];
-        const f32x4 g1 = reinterpret_cast<const f32x4*>(g32)[2 * i + 1];
-        f32x4 w0 = reinterpret_cast<const f32x4*>(w)[2 * i];
-        f32x4 w1 = reinterpret_cast<const f32x4*>(w)[2 * i + 1];
-        f32x4 v0 = reinterpret_cast<const f32x4*>(v)[2 * i];
-        f32x4 v1 = reinterpret_cast<const f32x4*>(v)[2 * i + 1];
-        h16x8 gh, lo;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            gh[j] = (h16)g0[j];
-            float gp = (float)gh[j] * grad_scale + wd * w0[j];
-            v0[j] = mu * v0[j] + gp;
-            w0[j] = w0[j] - lr * v0[j];
-            lo[j] = (h16)w0[j];
-            gh[4 + j] = (h16)g1[j];
-            gp = (float)gh[4 + j] * grad_scale + wd * w1[j];
-            v1[j] = mu * v1[j] + gp;
-            w1[j] = w1[j] - lr * v1[j];
-            lo[4 + j] = (h16)w1[j];
-        }
-        reinterpret_cast<h16x8*>(g16)[i] = gh;
-        reinterpret_cast<f32x4*>(w)[2 * i] = w0;
-        reinterpret_cast<f32x4*>(w)[2 * i + 1] = w1;
-        reinterpret_cast<f32x4*>(v)[2 * i] = v0;
-        reinterpret_cast<f32x4*>(v)[2 * i + 1] = v1;
-        reinterpret_cast<h16x8*>(w16)[i] = lo;
-    }
-    const size_t t = nvec * 8 + (size_t)blockIdx.x * kThreads + threadIdx.x;
-    if (t < n) {
-        const h16 gh = (h16)g32[t];
-        const float gp = (float)gh * grad_scale + wd * w[t];
-        const float vn = mu * v[t] + gp;
-        const float wn = w[t] - lr * vn;
-        g16[t] = gh;
-        v[t] = vn;
-        w[t] = wn;
-        w16[t] = (h16)wn;
-    }
-}
-
 __global__ __launch_bounds__(kThreads) void cast_params_kernel(size_t n, const float* __restrict__ w,
                                                                h16* __restrict__ w16)
 {
@@ -171,15 +122,6 @@ extern "C" int sgd_momentum_flat(size_t n, const void* grad, int grad_dt, float 
     else
         sgd_momentum_kernel<false><<<grid, kThreads, 0, s>>>(n, static_cast<const h16*>(grad), grad_scale, master_w,
                                                              momentum, nullptr, lr, mu, wd);
-    return rn50_check_launch();
-}
-
-// Internal: cast of the FP32 gradient buffer fused with the update (24 bytes per parameter).
-int rn50_sgd_from_f32_launch(size_t n, const float* g32, h16* g16, float grad_scale, float* w, float* v, h16* w16,
-                             float lr, float mu, float wd, hipStream_t s)
-{
-    ProfScope ps(RN50_K_SGD, 0.0, 24.0 * (double)n, s);
-    sgd_momentum_f32grad_kernel<<<stream_grid(n), kThreads, 0, s>>>(n, g32, g16, grad_scale, w, v, w16, lr, mu, wd);
     return rn50_check_launch();
 }
 

@@ -73,18 +73,19 @@ def test_conv_edge_shapes(shape):
     run_case(n, h, w, cin, cout, r, stride, pad, 300 + EDGE_SHAPES.index(shape) * 3, do_dgrad=cin != 3)
 
 
-# every kernel variant, forced through the environment, on shapes where each applies: (n, h, w, cin, cout, r, stride, pad).
+# every kernel variant, named through the *_variant entry points, on shapes where each applies: (n, h, w, cin, cout, r, stride, pad).
 # Small images make one tile span several of them, and most shapes end in a ragged tile.
 VARIANT_SHAPES = [
     (3, 14, 14, 128, 128, 3, 1, 1), (5, 7, 7, 64, 256, 3, 1, 1), (2, 28, 28, 96 + 32, 64, 3, 1, 1),
     (2, 56, 56, 64, 64, 3, 1, 1), (7, 5, 3, 64, 128, 3, 1, 1), (1, 6, 70, 64, 64, 3, 1, 1), (40, 2, 2, 64, 64, 3, 1, 1),
     (2, 14, 14, 256, 256, 1, 1, 0), (2, 15, 13, 128, 128, 3, 2, 1)]
-N_GATHER_TILES, N_WGRAD_VARIANTS = 12, 30
+MAX_GATHER_TILES, MAX_WGRAD_VARIANTS = 24, 60     # parametrisation bounds; the library reports the real counts
 
 
-@pytest.mark.parametrize("tile", range(N_GATHER_TILES))
-def test_conv_every_gather_tile(tile, monkeypatch):
-    monkeypatch.setenv("RN50_GATHER_TILE", str(tile))
+@pytest.mark.parametrize("tile", range(MAX_GATHER_TILES))
+def test_conv_every_gather_tile(tile):
+    if tile >= P.conv_variant_count(P.CONV_FWD):
+        pytest.skip("the library has fewer gather-GEMM tiles")
     for i, (n, h, w, cin, cout, r, stride, pad) in enumerate(VARIANT_SHAPES):
         print("[case] tile=%d n=%d h=%d w=%d c=%d k=%d r=%d stride=%d" % (tile, n, h, w, cin, cout, r, stride), flush=True)
         x = synth.normal_f16(700 + i, (n, h, w, cin))
@@ -93,18 +94,19 @@ def test_conv_every_gather_tile(tile, monkeypatch):
         dy = synth.normal_f16(740 + i, (n, p, q, cout))
         d = P.make_conv_desc(n, h, w, cin, cout, r, r, stride, pad)
         y = torch.full((n, p, q, cout), float("nan"), dtype=torch.float16, device=DEV)
-        P.conv_fwd(d, dev_h(x), dev_h(wt), y)
+        P.conv_fwd(d, dev_h(x), dev_h(wt), y, variant=tile)
         e = rel_err(host(y), O.conv_fwd(x.astype(np.float64), wt.astype(np.float64), stride, pad))
         assert e <= TOL16, "fwd err %g (tile %d, shape %d)" % (e, tile, i)
         dx = torch.full((n, h, w, cin), float("nan"), dtype=torch.float16, device=DEV)
-        P.conv_dgrad(d, dev_h(dy), dev_h(wt), dx)
+        P.conv_dgrad(d, dev_h(dy), dev_h(wt), dx, variant=tile)
         e = rel_err(host(dx), O.conv_dgrad(dy.astype(np.float64), wt.astype(np.float64), x.shape, stride, pad))
         assert e <= TOL16, "dgrad err %g (tile %d, shape %d)" % (e, tile, i)
 
 
-@pytest.mark.parametrize("variant", range(N_WGRAD_VARIANTS))
-def test_conv_every_wgrad_variant(variant, monkeypatch):
-    monkeypatch.setenv("RN50_WGRAD_VARIANT", str(variant))
+@pytest.mark.parametrize("variant", range(MAX_WGRAD_VARIANTS))
+def test_conv_every_wgrad_variant(variant):
+    if variant >= P.conv_variant_count(P.CONV_WGRAD):
+        pytest.skip("the library has fewer filter-gradient variants")
     for i, (n, h, w, cin, cout, r, stride, pad) in enumerate(VARIANT_SHAPES):
         print("[case] wgrad variant=%d shape %d" % (variant, i), flush=True)
         x = synth.normal_f16(760 + i, (n, h, w, cin))
@@ -112,7 +114,7 @@ def test_conv_every_wgrad_variant(variant, monkeypatch):
         dy = synth.normal_f16(780 + i, (n, p, q, cout))
         d = P.make_conv_desc(n, h, w, cin, cout, r, r, stride, pad)
         dw = torch.full((cout, r, r, cin), float("nan"), dtype=torch.float16, device=DEV)
-        P.conv_wgrad(d, dev_h(x), dev_h(dy), dw)
+        P.conv_wgrad(d, dev_h(x), dev_h(dy), dw, variant=variant)
         e = rel_err(host(dw), O.conv_wgrad(x.astype(np.float64), dy.astype(np.float64), (cout, r, r, cin), stride, pad))
         assert e <= TOL16, "wgrad err %g (variant %d, shape %d)" % (e, variant, i)
 

@@ -84,6 +84,18 @@ def test_bad_configs_and_null_arguments():
     assert l.sgd_momentum_flat(0, None, 0, 1.0, None, None, None, 0.1, 0.9, 0.0, None) == 0
 
 
+def test_bn_channel_counts_the_header_states():
+    """bn_*: c a power of two from 8 to 2048 or a multiple of 2048."""
+    l = P.lib()
+    for c, ok in [(8, True), (64, True), (2048, True), (4096, True), (6144, True), (24, False), (192, False), (320, False),
+                  (3072, False), (4, False), (0, False)]:
+        b = P.make_bn_desc(10, c)
+        assert (P.bn_workspace_bytes(b) > 0) == ok, c
+        rc = l.bn_relu_fwd(ctypes.byref(b), None, None, None, None, None, None, None, None, 0, None)
+        assert rc == (-1 if ok else -2), (c, rc)                     # shape is judged before the pointers
+    assert P.conv_variant_count(P.CONV_FWD) >= 12 and P.conv_variant_count(P.CONV_WGRAD) >= 30 and P.conv_variant_count(7) == 0
+
+
 def test_lars_table_validation_without_a_gpu():
     """lars_workspace_bytes / lars_plan_create reject bad segment tables before anything touches the device."""
     l = P.lib()
