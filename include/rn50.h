@@ -116,6 +116,15 @@ size_t bn_workspace_bytes(const bn_desc* d);
 int bn_relu_fwd(const bn_desc* d, const void* x, const float* gamma, const float* beta,
                 const void* residual /* NULL unless has_residual */, void* y,
                 float* save_mean, float* save_invstd, void* ws, size_t ws_bytes, void* stream);
+/* bn_relu_fwd for callers that cannot allocate or pass a workspace (code under HIP graph capture, serving
+ * loops, harnesses that forbid hipMalloc): same arguments without ws, same kernels, same result bit for bit.
+ * The partial sums live in a device array inside the library (RN50_BN_STATIC_MAX_C channels, 4.2 MB per GPU,
+ * held until the process ends); c above that limit returns RN50_ERR_WORKSPACE.  The call allocates nothing.
+ * All calls on one GPU share that array: calls that overlap in time on the same GPU race. */
+#define RN50_BN_STATIC_MAX_C 256
+int bn_relu_fwd_static(const bn_desc* d, const void* x, const float* gamma, const float* beta,
+                       const void* residual /* NULL unless has_residual */, void* y,
+                       float* save_mean, float* save_invstd, void* stream);
 /* g = dy*[y>0] if relu else dy;  dresidual = g (written iff has_residual);
  * dbeta = sum g; dgamma = sum g*xhat; dx = gamma*invstd*(g - dbeta/m - xhat*dgamma/m). */
 int bn_relu_bwd(const bn_desc* d, const void* dy, const void* x, const void* y /* NULL unless relu */,

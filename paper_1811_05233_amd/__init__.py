@@ -71,6 +71,7 @@ _SIGNATURES = {
     "conv_wgrad_variant": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _i, _vp]),
     "bn_workspace_bytes": (_sz, [ctypes.POINTER(bn_desc)]),
     "bn_relu_fwd": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_relu_fwd_static": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "bn_relu_bwd": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_batch_moments": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _sz, _vp]),
     "bn_relu_fwd_from_moments": (_i, [ctypes.POINTER(bn_desc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -205,6 +206,13 @@ def bn_relu_fwd(d, x, gamma, beta, residual, y, save_mean, save_invstd, ws=None)
     ws = ws if ws is not None else _ws(bn_workspace_bytes(d), x)
     _check(lib().bn_relu_fwd(ctypes.byref(d), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(residual), _ptr(y),
                              _ptr(save_mean), _ptr(save_invstd), _ptr(ws), ws.numel(), _stream()), "bn_relu_fwd")
+    return y
+
+
+def bn_relu_fwd_static(d, x, gamma, beta, residual, y, save_mean, save_invstd):
+    """bn_relu_fwd on the library's static device scratch (no workspace, no allocation; c <= 256)."""
+    _check(lib().bn_relu_fwd_static(ctypes.byref(d), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(residual), _ptr(y),
+                                    _ptr(save_mean), _ptr(save_invstd), _stream()), "bn_relu_fwd_static")
     return y
 
 

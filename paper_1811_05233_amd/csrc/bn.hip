@@ -737,6 +737,52 @@ extern "C" int bn_relu_bwd(const bn_desc* d, const void* dy, const void* x, cons
 }
 
 
+// ---- bn_relu_fwd for callers that cannot hand over (or allocate) a workspace ----
+// Same kernels as bn_relu_fwd; the partial sums of the statistics pass live in a file-scope device array
+// instead of a workspace argument.  Every GPU holds its own copy of the array; its device address is looked
+// up once per device and kept.  All calls on one GPU share the array, so calls that overlap in time on one
+// GPU race (every call overwrites the part it reads, nothing has to start at zero).
+namespace {
+constexpr int kStaticMaxC = RN50_BN_STATIC_MAX_C;
+constexpr size_t kStaticFloats = (size_t)kMaxBlocks * 2 * kStaticMaxC + 2 * (size_t)kStaticMaxC;
+__device__ __align__(256) float scratch[kStaticFloats];
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices];      // per device: address of that device's copy of `scratch` (nullptr: not looked up yet)
+
+int static_scratch(float** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return rn50_hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return RN50_ERR_SHAPE;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return rn50_hip_fail(e);
+        if (!p) return RN50_ERR_HIP;
+        g_scratch_ptr[dev] = static_cast<float*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return RN50_OK;
+}
+}  // namespace
+
+extern "C" int bn_relu_fwd_static(const bn_desc* d, const void* x, const float* gamma, const float* beta,
+                                  const void* residual, void* y, float* save_mean, float* save_invstd, void* stream)
+{
+    RN50_TRY(validate(d));
+    if (d->c > kStaticMaxC) return RN50_ERR_WORKSPACE;      // the static scratch holds the partials of at most this many channels
+    RN50_REQUIRE_PTR(x); RN50_REQUIRE_PTR(gamma); RN50_REQUIRE_PTR(beta); RN50_REQUIRE_PTR(y);
+    RN50_REQUIRE_PTR(save_mean); RN50_REQUIRE_PTR(save_invstd);
+    if (d->has_residual) RN50_REQUIRE_PTR(residual);
+    RN50_REQUIRE_ALIGNED(x); RN50_REQUIRE_ALIGNED(y); RN50_REQUIRE_ALIGNED(residual);
+    float* ws = nullptr;
+    RN50_TRY(static_scratch(&ws));
+    return rn50_bn_fwd_launch(d->m, d->c, d->eps, d->relu != 0, static_cast<const h16*>(x), gamma, beta,
+                              d->has_residual ? static_cast<const h16*>(residual) : nullptr, static_cast<h16*>(y),
+                              save_mean, save_invstd, ws, static_cast<hipStream_t>(stream));
+}
+
 // ---- the same operators split at the points where GPUs exchange statistics (synchronised BN) ----
 extern "C" int bn_batch_moments(const bn_desc* d, const void* x, float* moments, void* ws, size_t ws_bytes, void* stream)
 {

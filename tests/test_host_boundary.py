@@ -85,7 +85,7 @@ def test_bad_configs_and_null_arguments():
 
 
 def test_bn_channel_counts_the_header_states():
-    """bn_*: c a power of two from 8 to 2048 or a multiple of 2048."""
+    """bn_*: c a power of two from 8 to 2048 or a multiple of 2048; the static-scratch form up to 256 channels."""
     l = P.lib()
     for c, ok in [(8, True), (64, True), (2048, True), (4096, True), (6144, True), (24, False), (192, False), (320, False),
                   (3072, False), (4, False), (0, False)]:
@@ -93,6 +93,10 @@ def test_bn_channel_counts_the_header_states():
         assert (P.bn_workspace_bytes(b) > 0) == ok, c
         rc = l.bn_relu_fwd(ctypes.byref(b), None, None, None, None, None, None, None, None, 0, None)
         assert rc == (-1 if ok else -2), (c, rc)                     # shape is judged before the pointers
+    b = P.make_bn_desc(10, 512)
+    assert l.bn_relu_fwd_static(ctypes.byref(b), None, None, None, None, None, None, None, None) == -4
+    b = P.make_bn_desc(10, 256)
+    assert l.bn_relu_fwd_static(ctypes.byref(b), None, None, None, None, None, None, None, None) == -1
     assert P.conv_variant_count(P.CONV_FWD) >= 12 and P.conv_variant_count(P.CONV_WGRAD) >= 30 and P.conv_variant_count(7) == 0
 
 
