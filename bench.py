@@ -27,6 +27,7 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+PACKAGED_TUNING = os.path.join("paper_1811_05233_amd", "tuning_resnet50_b32.json")
 PEAK_FP16_TFLOPS = 2500.0     # MI355X dense FP16 MFMA peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 
@@ -60,11 +61,23 @@ def _cpu_step_seconds(batch):
     return time.perf_counter() - t0
 
 
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(sample_batch):
     """The CPU oracle as it stands (FP32 instantiation, storage rounding on), one full ResNet-50 training step;
     images/s = batch / seconds.  sample_batch < 0: a batch-4 step first, then the largest batch of 8, 16, 32 (the
-    benchmarked workload) that the batch-4 time predicts to finish within 25 s; its figure is the one reported."""
+    benchmarked workload) that the batch-4 time predicts to finish within 25 s; its figure is the one reported.
+    A single-threaded batch-1 step is timed as well."""
     import oracle as O
+    threads = O.max_threads()
     if sample_batch < 0:
         sample_batch, dt = 4, _cpu_step_seconds(4)
         bigger = [b for b in (32, 16, 8) if dt * b / 4 <= 25.0]
@@ -73,9 +86,15 @@ def cpu_baseline(sample_batch):
             dt = _cpu_step_seconds(sample_batch)
     else:
         dt = _cpu_step_seconds(sample_batch)
-    return {"value": sample_batch / dt, "unit": "images/s", "cores": O.max_threads(), "kind": "oracle",
+    O.set_threads(1)
+    dt1 = _cpu_step_seconds(1)
+    O.set_threads(threads)
+    return {"value": sample_batch / dt, "unit": "images/s", "cores": threads, "kind": "oracle",
             "sample": "one full ResNet-50 fwd+bwd+SGD step at batch %d, 224x224, FP32 oracle with binary16 "
-                      "storage rounding, %.1f s" % (sample_batch, dt)}
+                      "storage rounding, %.1f s" % (sample_batch, dt),
+            "cpu_model": _cpu_model(),
+            "single_thread": {"value": 1.0 / dt1, "unit": "images/s", "cores": 1,
+                              "sample": "the same step at batch 1 on one thread, %.1f s" % dt1}}
 
 
 # (cin, cout, r, stride, pad, hin, layers with this shape): the 23 distinct convolution shapes of ResNet-50 v1.5
@@ -150,19 +169,19 @@ def conv_sweep(args):
         rows.append(row)
     summary = {k: {"us_all_layers": round(v[0], 1), "tflops": round(v[1] / v[0] / 1e6, 1),
                    "mfma_util_pct": round(100.0 * v[1] / v[0] / 1e6 / PEAK_FP16_TFLOPS, 2)} for k, v in tot.items()}
-    print(json.dumps({"metric": "conv kernel sweep, ResNet-50 v1.5 shapes @ batch %d" % B, "unit": "TFLOP/s",
-                      "value": summary["fwd"]["tflops"], "n_gpus": 1, "dtype": "f16 storage, f32 accumulate",
-                      "data": "synthetic", "config": {"workload": "23 distinct conv shapes (53 layers), fwd / dgrad / wgrad "
-                      "timed separately, %s operands, built-in tile heuristics" % ("cold (rotating sets > 256 MB)" if args.cold else "warm")},
-                      "summary": summary, "shapes": rows}))
+    return {"metric": "conv kernel sweep, ResNet-50 v1.5 shapes @ batch %d" % B, "unit": "TFLOP/s",
+            "value": summary["fwd"]["tflops"], "n_gpus": 1, "dtype": "f16 storage, f32 accumulate",
+            "data": "synthetic", "config": {"workload": "23 distinct conv shapes (53 layers), fwd / dgrad / wgrad "
+            "timed separately, %s operands, built-in tile heuristics" % ("cold (rotating sets > 256 MB)" if args.cold else "warm")},
+            "summary": summary, "shapes": rows}
 
 
-def batch_sweep(args):
+def batch_sweep(args, batches=(16, 32, 64, 128)):
     import torch
     import paper_1811_05233_amd as P
     from paper_1811_05233_amd import synth
     dev, loss_scale, res = "cuda:0", 1024.0, []
-    for B in (16, 32, 64, 128):
+    for B in batches:
         cfg = P.make_config(B, loss_scale=loss_scale)
         lay, n = P.rn50_param_layout(cfg), P.rn50_param_count(cfg)
         w = torch.from_numpy(synth.flat_params(300 + B, lay)).to(dev)
@@ -189,10 +208,10 @@ def batch_sweep(args):
                     "loss": round(float(loss.item()), 5)})
         ctx.close()
         del ctx, w, v, w16, g16, x
-    print(json.dumps({"metric": "images/sec per MI355X, ResNet-50 fwd+bwd+SGD, per-GPU batch 16/32/64/128", "unit": "images/s",
-                      "value": [r["images_per_s"] for r in res], "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-                      "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
-                      "config": {"workload": "full ResNet-50 v1.5 training step at the batch-size-control sizes"}, "batches": res}))
+    return {"metric": "images/sec per MI355X, ResNet-50 fwd+bwd+SGD, per-GPU batch %s" % "/".join(str(b) for b in batches),
+            "unit": "images/s", "value": [r["images_per_s"] for r in res], "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
+            "config": {"workload": "full ResNet-50 v1.5 training step at the batch-size-control sizes"}, "batches": res}
 
 
 def tail(args):
@@ -229,15 +248,40 @@ def tail(args):
     torch.cuda.synchronize()
     us_l = e0.elapsed_time(e1) * 1e3 / steps
     gbs_l = 26.0 * n / us_l / 1e3
-    print(json.dumps({"metric": "momentum-SGD update of the flat 25,557,032-parameter buffer", "unit": "GB/s", "value": round(gbs, 1),
-                      "n_gpus": 1, "steps": steps, "us_per_step": round(us, 2), "dtype": "f32 (f16 gradient in, f16 weight copy out)",
-                      "data": "synthetic", "config": {"workload": "g ~ N(0,1e-3^2) f16, w ~ N(0,0.05^2), v=0, grad_scale 1/54000, "
-                      "lr 0.1, momentum 0.9, wd 1e-4, 100 steps on the same gradient"},
-                      "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                   "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None, "bytes_per_parameter": 20},
-                      "lars": {"us_per_step": round(us_l, 2), "achieved": round(gbs_l, 1), "unit": "GB/s",
-                               "frac": round(gbs_l / PEAK_HBM_GBS, 4), "bytes_per_parameter": 26, "segments": len(segments),
-                               "eta": 0.01, "eps": 1e-6}}))
+    return {"metric": "momentum-SGD update of the flat 25,557,032-parameter buffer", "unit": "GB/s", "value": round(gbs, 1),
+            "n_gpus": 1, "steps": steps, "us_per_step": round(us, 2), "dtype": "f32 (f16 gradient in, f16 weight copy out)",
+            "data": "synthetic", "config": {"workload": "g ~ N(0,1e-3^2) f16, w ~ N(0,0.05^2), v=0, grad_scale 1/54000, "
+            "lr 0.1, momentum 0.9, wd 1e-4, 100 steps on the same gradient"},
+            "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None, "bytes_per_parameter": 20},
+            "lars": {"us_per_step": round(us_l, 2), "achieved": round(gbs_l, 1), "unit": "GB/s",
+                     "frac": round(gbs_l / PEAK_HBM_GBS, 4), "bytes_per_parameter": 26, "segments": len(segments),
+                     "eta": 0.01, "eps": 1e-6}}
+
+
+def extras(args):
+    """The other workloads of the configuration list in short form, outside the timed region of the step: the
+    update tail (100 steps), the convolution sweep (warm and cold operands: totals and the three shapes furthest
+    from their own roofline) and the step at the other batch-size-control sizes (few steps each)."""
+    import copy
+    out = {}
+    t = tail(args)
+    out["tail"] = {"sgd_gbs": t["value"], "sgd_hbm_frac": t["roofline"]["frac"], "sgd_us_per_step": t["us_per_step"],
+                   "lars_gbs": t["lars"]["achieved"], "lars_hbm_frac": t["lars"]["frac"], "steps": t["steps"]}
+    sweep = {}
+    for cold in (False, True):
+        a = copy.copy(args)
+        a.cold, a.steps, a.batch = cold, 5, 32
+        r = conv_sweep(a)
+        worst = sorted(((row[k]["roofline_frac"], row["shape"], k, row[k]["us"]) for row in r["shapes"]
+                        for k in ("fwd", "dgrad", "wgrad") if k in row))[:3]
+        sweep["cold" if cold else "warm"] = {"summary": r["summary"],
+                                             "worst": [{"shape": w[1], "kind": w[2], "us": w[3], "roofline_frac": w[0]} for w in worst]}
+    out["conv_sweep"] = sweep
+    a = copy.copy(args)
+    a.steps, a.warmup, a.no_autotune = 8, 2, False
+    out["batch_sweep"] = batch_sweep(a, (16, 64, 128))["batches"]
+    return out
 
 
 def main():
@@ -250,10 +294,14 @@ def main():
     ap.add_argument("--cpu-sample-batch", type=int, default=-1,
                     help="batch of the cpu_baseline leg; 0 disables it, negative picks up to 32 within about 25 s")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel event pass")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="step mode: skip the short runs of the other workloads (update tail, conv sweep, other batch sizes)")
     ap.add_argument("--no-autotune", action="store_true", help="use the built-in tile heuristics")
     ap.add_argument("--tuning-file", default="",
                     help="step mode: JSON file with the kernel-variant table; read if it exists (instead of autotuning), "
-                         "written after autotuning otherwise, so that a profiler run executes the same kernels")
+                         "written after autotuning otherwise.  Default at batch 32: the table shipped with the package "
+                         "(%s), so that the benchmark and the committed profiles run the same kernels" % PACKAGED_TUNING)
+    ap.add_argument("--autotune", action="store_true", help="step mode: time the kernel variants now instead of using the shipped table")
     ap.add_argument("--tune-report", default="", help="step mode: write what the autotune pass measured to this text file")
     ap.add_argument("--lars", action="store_true",
                     help="step mode: update with LARS (eta 0.01, eps 1e-6, the paper's optimizer) instead of momentum SGD")
@@ -269,7 +317,8 @@ def main():
         sys.exit(2)
 
     if args.mode != "step":
-        return {"conv-sweep": conv_sweep, "batch-sweep": batch_sweep, "tail": tail}[args.mode](args)
+        print(json.dumps({"conv-sweep": conv_sweep, "batch-sweep": batch_sweep, "tail": tail}[args.mode](args)))
+        return
 
     import numpy as np
     import torch
@@ -296,7 +345,10 @@ def main():
     def step():
         ctx.step(x, lab, w, v, w16, g16, hp, loss)
 
-    if args.tuning_file and os.path.exists(args.tuning_file):
+    if not args.tuning_file and not args.autotune and not args.no_autotune and B == 32 and os.path.exists(os.path.join(ROOT, PACKAGED_TUNING)):
+        args.tuning_file = os.path.join(ROOT, PACKAGED_TUNING)
+    shipped = os.path.abspath(args.tuning_file) == os.path.join(ROOT, PACKAGED_TUNING) if args.tuning_file else False
+    if args.tuning_file and os.path.exists(args.tuning_file) and not args.autotune:
         ctx.set_tuning(json.load(open(args.tuning_file))["table"])
     elif not args.no_autotune:
         ctx.autotune(x, lab, w, w16, g16, loss)      # one-off kernel-variant selection, outside the timed region
@@ -317,6 +369,15 @@ def main():
     loss_val = float(loss.item())
     if not np.isfinite(loss_val):
         raise RuntimeError("loss is not finite after the timed steps")
+    # the same K steps once more, each bracketed by its own pair of events on the launch stream: the median step time
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    median_ms = per_step[len(per_step) // 2]
 
     if args.copy_probe:
         src = torch.zeros(128 << 20, dtype=torch.float16, device=dev)
@@ -354,7 +415,7 @@ def main():
                     "avg_launch_us": round(1e3 * dom["total_ms"] / dom["launches"], 2),
                     "launches_per_step": dom["launches"] / args.steps}
         # all convolution kernels together: MFMA rate while they run, and over the whole step
-        roof["traffic"] = measured_traffic(dom["name"])
+        roof["traffic"] = measured_traffic(dom["name"]) if shipped else None     # the committed counters describe the shipped table
         roof["algorithmic_bytes_per_launch"] = int(dom["bytes"] / dom["launches"])
         # what an event pair reads around an (almost) empty launch: the dispatch latency that avg_launch_us includes
         # and that a profiler's begin/end timestamps of the kernel do not
@@ -374,17 +435,23 @@ def main():
             roof["sgd_hbm_frac"] = round(sum(e["bytes"] for e in sgd) / (sum(e["total_ms"] for e in sgd) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
 
     out = {
-        "metric": "images/sec per MI355X, ResNet-50 fwd+bwd+%s @ batch 32" % ("LARS" if args.lars else "SGD"),
+        "metric": "images/sec per MI355X, ResNet-50 fwd+bwd+%s @ batch %d" % ("LARS" if args.lars else "SGD", B),
         "value": round(B * args.steps / dt, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "median_ms_per_step": round(median_ms, 4),
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
         "config": {"workload": "full ResNet-50 v1.5 training step (fwd+bwd+label-smoothed loss+momentum SGD), "
                                "batch %d, 224x224x3 fp16 N(0,1) images, 1000 classes" % B,
                    "global_batch": B, "loss_scale": loss_scale},
         "loss": round(loss_val, 5),
-        "paper_context": "Table 6: 2565 images/s on 4 V100 (641 per GPU, incl. all-reduce and input pipeline)",
+        "paper_context": "other hardware, context only: Table 6: 2565 images/s on 4 V100 (641 per GPU, incl. all-reduce and "
+                         "input pipeline); Table 5: 90 epochs in 122 s on 3456 V100; Table 2: 84.75 % scaling efficiency on 1024 V100",
         "roofline": roof, "kernels": kernels,
     }
+    ctx.close()
+    del ctx
+    if not args.no_extras:
+        out["extras"] = extras(args)
     if args.cpu_sample_batch != 0:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_batch)
     print(json.dumps(out))

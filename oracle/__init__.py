@@ -30,11 +30,18 @@ def lib():
         _LIB.oracle_round_binary16.restype = ctypes.c_double
         _LIB.oracle_round_binary16.argtypes = [ctypes.c_double]
         _LIB.oracle_max_threads.restype = ctypes.c_int
+        _LIB.oracle_set_threads.argtypes = [ctypes.c_int]
+        _LIB.oracle_set_threads.restype = None
     return _LIB
 
 
 def max_threads():
     return int(lib().oracle_max_threads())
+
+
+def set_threads(n):
+    """OpenMP threads the oracle uses from now on (timing only; results do not depend on it)."""
+    lib().oracle_set_threads(int(n))
 
 
 def _sfx(a):

@@ -37,6 +37,17 @@ int oracle_max_threads(void)
 #endif
 }
 
+/* Number of OpenMP threads later calls use (timing aid for the benchmark's CPU leg; no effect on results). */
+void oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 #define REAL float
 #define FN(name) name##_f32
 #include "rn50_oracle_impl.inc"

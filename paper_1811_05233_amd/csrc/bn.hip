@@ -588,6 +588,7 @@ int validate(const bn_desc* d)
 }  // namespace
 
 // partials of up to kMaxBlocks workgroups (2 rows of c floats each) + 2c floats of totals
+int rn50_bn_fused_max_tiles() { return kFusedMaxTiles; }
 size_t rn50_bn_ws_floats(int c) { return (size_t)kMaxBlocks * 2 * c + 2 * (size_t)c; }
 
 extern "C" size_t bn_workspace_bytes(const bn_desc* d)

@@ -224,7 +224,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     __shared__ __attribute__((aligned(16))) h16 lds[LDS_HALFS];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index as a scalar
     const int li = lane & 31, lg = lane >> 5;
     const int wm0 = (wave / WC) * WM, wn0 = (wave % WC) * WN;
 
@@ -345,22 +345,39 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
         if (kit + NST - 1 < kiters) issue_slab();
         const h16* sa = lds + cur * STAGE;
         const h16* sb = sa + BM * BK;
+        // Operand reads run one group of k-steps (at least four MFMAs' worth) ahead of the MFMAs that use them, in
+        // two register sets, so that a wave keeps its matrix unit busy while its next LDS reads are in flight.
+        constexpr int GE = (TM * TN >= 4 || KS == 1) ? 1 : ((TM * TN == 2 || KS == 2) ? 2 : 4);
+        constexpr int NG = KS / GE;
+        h16x8 fa[2][GE][TM], fb[2][GE][TN];
+        auto read_group = [&](int g, int buf) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            h16x8 fa[TM], fb[TN];
+            for (int e = 0; e < GE; ++e) {
+                const int ks = g * GE + e;
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                fa[tm] = *reinterpret_cast<const h16x8*>(sa + lds_off<BK>(wm0 + tm * 32 + li, ks * 2 + lg));
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                fb[tn] = *reinterpret_cast<const h16x8*>(sb + lds_off<BK>(wn0 + tn * 32 + li, ks * 2 + lg));
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
+                for (int tm = 0; tm < TM; ++tm)
+                    fa[buf][e][tm] = *reinterpret_cast<const h16x8*>(sa + lds_off<BK>(wm0 + tm * 32 + li, ks * 2 + lg));
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
-                    // operands swapped: the accumulator holds out^T, i.e. every lane owns one pixel
-                    // (lane%32) and runs of 4 consecutive output channels
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[tn], fa[tm], acc[tm][tn], 0, 0, 0);
+                    fb[buf][e][tn] = *reinterpret_cast<const h16x8*>(sb + lds_off<BK>(wn0 + tn * 32 + li, ks * 2 + lg));
+            }
+        };
+        read_group(0, 0);
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int buf = g & 1;
+            if (g + 1 < NG) read_group(g + 1, buf ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int e = 0; e < GE; ++e)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        // operands swapped: the accumulator holds out^T, i.e. every lane owns one pixel
+                        // (lane%32) and runs of 4 consecutive output channels
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[buf][e][tn], fa[buf][e][tm], acc[tm][tn], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (++cur == NST) cur = 0;
     }
@@ -368,6 +385,173 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     __builtin_amdgcn_s_barrier();             // all waves are done reading the ring before it is reused
 
     gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, tile_row, row_pix);
+}
+
+// ------------------------------------------------------------------------------------------------
+// 3x3, stride 1, pad 1 (forward, and the data gradient of such a layer)
+// ------------------------------------------------------------------------------------------------
+// With stride 1 and "same" padding, consecutive output pixels (flat index m over n, h, w) read consecutive input
+// pixels: tap (dh, dw) of output pixel m is input pixel m + dh*W + dw.  One strip of BM + 2W + 2 input pixels
+// therefore serves all nine taps of a tile of BM output pixels; it is loaded once per 32-channel slab instead of
+// nine times (the gather kernel above loads every tap's rows separately).  Where a tap falls outside the image
+// (top / bottom row, left / right column) the strip holds a neighbouring pixel instead of the zero padding; the
+// A fragment of such a row is cleared in registers (a row is one lane of the fragment).  The nine filter taps of
+// the slab sit next to the strip, [tap][column][32 channels].  Two stages: the next slab's strip and taps are in
+// flight while the 9 x 2 x TM x TN MFMAs of the current one run.
+constexpr int kStripMaxW = 56;      // widest image row the strip buffer is sized for
+
+template <int BM, int WR, int WC>
+__global__ __launch_bounds__(kThreads, 1) void strip_gemm_kernel(const GatherArgs a)
+{
+    constexpr int BN = 64, BK = 32, NST = 2, T = 9;
+    constexpr int SROWS = (BM + 2 * kStripMaxW + 2 + 15) / 16 * 16;    // strip rows per stage, whole 1 KB DMA blocks
+    constexpr int BROWS = T * BN;
+    constexpr int NAJ = SROWS / 16 / 4, NBJ = BROWS / 16 / 4;          // DMA loads per thread and slab
+    constexpr int STAGE = (SROWS + BROWS) * BK;                        // halfs
+    constexpr int WM = BM / WR, WN = BN / WC, TM = WM / 32, TN = WN / 32;
+    constexpr int KS = BK / 16;
+    constexpr int EP = BN + 8;
+    constexpr int EPI_HALFS = BM * EP + (kThreads / (BN / 8)) * 2 * BN * 2;
+    constexpr int LDS_HALFS = (NST * STAGE > EPI_HALFS) ? NST * STAGE : EPI_HALFS;
+    constexpr unsigned kOutOfRange = 0x80000000u;
+    static_assert(WR * WC == 4 && TM >= 1 && TN >= 1 && SROWS % 64 == 0, "four waves; strip rows in whole rounds of the four waves");
+    __shared__ __attribute__((aligned(16))) h16 lds[LDS_HALFS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, lg = lane >> 5;
+    const int wm0 = (wave / WC) * WM, wn0 = (wave % WC) * WN;
+
+    const int n_tiles = a.NO / BN;
+    const int bid = rn50_xcd_remap(blockIdx.x, gridDim.x);
+    const int nt = bid % n_tiles, mt = bid / n_tiles;
+    const int H = a.IH, W = a.IW, lda = a.lda, CR = a.CR;
+    const int M = a.NB * H * W;
+    const int m0 = mt * BM;
+    const int p0 = m0 - (W + 1);                   // flat input pixel held by strip row 0
+    const int naw = (BM + 2 * W + 2 + 15) >> 4;    // 16-row DMA blocks the strip needs for this image width
+
+    // ---- this lane's place in a wave-wide load (16 rows of 64 bytes, two rows per 128-byte line) ----
+    const int row_in_grp = 2 * (lane >> 3) + ((lane & 7) >> 2), phys = lane & 3;
+    unsigned a_voff[NAJ], b_voff[NBJ];
+#pragma unroll
+    for (int j = 0; j < NAJ; ++j) {
+        const int row = (wave + 4 * j) * 16 + row_in_grp;
+        const int p = p0 + row;
+        const int chunk = phys ^ ((row >> 1) & 3);
+        a_voff[j] = ((unsigned)p < (unsigned)M) ? (unsigned)(p * lda) * 2u + chunk * 16 : kOutOfRange;
+    }
+#pragma unroll
+    for (int j = 0; j < NBJ; ++j) {
+        const int row = (wave + 4 * j) * 16 + row_in_grp;          // = tap slot * 64 + column
+        const int slot = row >> 6, col = row & 63;
+        const int bt = a.tap[0][slot] >> 16;                       // filter tap of this slot
+        const int chunk = phys ^ ((row >> 1) & 3);
+        b_voff[j] = (unsigned)(((nt * BN + col) * T + bt) * CR) * 2u + chunk * 16;
+    }
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<h16*>(a.A), 0, a.a_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(const_cast<h16*>(a.B), 0, a.b_bytes, 0x00020000);
+
+    const int KC = CR / BK;
+    int ld_cc = 0, ld_stage = 0;
+    auto issue_slab = [&]() {
+        h16* sa = lds + ld_stage * STAGE;
+        h16* sb = sa + SROWS * BK;
+        const unsigned delta = (unsigned)(ld_cc * BK) * 2u;
+#pragma unroll
+        for (int j = 0; j < NBJ; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(sb + (wave + 4 * j) * 512), 16, (int)(b_voff[j] + delta), 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < NAJ; ++j)
+            if (wave + 4 * j < naw) {      // wave-uniform
+                const unsigned voff = a_voff[j] == kOutOfRange ? kOutOfRange : a_voff[j] + delta;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(sa + (wave + 4 * j) * 512), 16, (int)voff, 0, 0, 0);
+            }
+        ++ld_cc;
+        ld_stage ^= 1;
+    };
+    issue_slab();
+
+    auto row_pix = [&](int row, int& n, int& oh, int& ow) -> bool {
+        const int m = m0 + row;
+        if (m >= M) return false;
+        int t;
+        fast_divmod(m, W, a.inv_ow[0], t, ow);
+        fast_divmod(t, H, a.inv_oh[0], n, oh);
+        return true;
+    };
+
+    // ---- per tap: where this lane's A rows sit in the strip, and whether the tap leaves the image there ----
+    int fa_off[T][TM];         // halfs, k-step 0 (k-step 1: ^ 16)
+    unsigned inval[TM];        // bit t: tap slot t reads outside the image for this lane's row
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        int n, oh, ow;
+        const bool live = row_pix(wm0 + tm * 32 + li, n, oh, ow);
+        unsigned bad = live ? 0u : 0x1ffu;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int tap = a.tap[0][t];
+            const int dh = (int)(signed char)(tap & 0xff), dw = (int)(signed char)((tap >> 8) & 0xff);
+            if (live && ((unsigned)(oh + dh) >= (unsigned)H || (unsigned)(ow + dw) >= (unsigned)W)) bad |= 1u << t;
+            fa_off[t][tm] = lds_off<BK>(wm0 + tm * 32 + li + dh * W + dw + W + 1, lg);
+        }
+        inval[tm] = bad;
+    }
+    int fb_off[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) fb_off[tn] = lds_off<BK>(wn0 + tn * 32 + li, lg);
+
+    f32x16 acc[TM][TN];
+    gather_init_acc<BN>(a, acc, wm0, wn0, li, lg, nt, row_pix);
+
+    int cur = 0;
+    for (int kit = 0; kit < KC; ++kit) {
+        RN50_WAIT_VMCNT(0);                   // this wave's part of slab kit has landed
+        RN50_WAIT_LGKMCNT0();
+        __builtin_amdgcn_s_barrier();         // everyone's part has; the other stage is free
+        if (kit + 1 < KC) issue_slab();
+        const h16* sa = lds + cur * STAGE;
+        const h16* sb = sa + SROWS * BK;
+        // The operands of tap t+1 are requested before the MFMAs of tap t are issued (two register sets), so that
+        // with a single wave per SIMD the LDS latency hides behind a whole tap's worth of matrix work.
+        h16x8 fa[2][KS][TM], fb[2][KS][TN];
+        auto read_tap = [&](int t, int buf) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+                    fa[buf][ks][tm] = *reinterpret_cast<const h16x8*>(sa + (fa_off[t][tm] ^ (ks * 16)));
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    fb[buf][ks][tn] = *reinterpret_cast<const h16x8*>(sb + t * (BN * BK) + (fb_off[tn] ^ (ks * 16)));
+            }
+        };
+        read_tap(0, 0);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int buf = t & 1;
+            if (t + 1 < T) read_tap(t + 1, buf ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+                    if ((inval[tm] >> t) & 1u) fa[buf][ks][tm] = h16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[buf][ks][tn], fa[buf][ks][tm], acc[tm][tn], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        cur ^= 1;
+    }
+    RN50_WAIT_LGKMCNT0();
+    __builtin_amdgcn_s_barrier();
+
+    gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, mt, row_pix);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -696,9 +880,33 @@ int launch_gather(GatherArgs& a, hipStream_t s, int kid, double flops, double by
     return rn50_check_launch();
 }
 
+template <int BM, int WR, int WC>
+int launch_strip(GatherArgs& a, hipStream_t s, int kid, double flops, double bytes)
+{
+    const long long M = (long long)a.NB * a.cOHs[0] * a.cOWs[0];
+    const int total = (int)((M + BM - 1) / BM);
+    a.mt_end[0] = total;
+    a.inv_oh[0] = 1.0f / (float)a.cOHs[0];
+    a.inv_ow[0] = 1.0f / (float)a.cOWs[0];
+    if (total == 0) return RN50_OK;
+    ProfScope ps(kid, flops, bytes, s);
+    strip_gemm_kernel<BM, WR, WC><<<total * (a.NO / 64), kThreads, 0, s>>>(a);
+    return rn50_check_launch();
+}
+
+// the strip kernel covers 3x3 / stride 1 / pad 1 in either direction: nine taps in one class, output grid = input grid
+bool strip_ok(const GatherArgs& a)
+{
+    return a.ncls == 1 && a.ntaps[0] == 9 && a.T == 9 && a.a_mul == 1 && a.o_mul == 1 && a.a_off == 0 && a.IH == a.OH &&
+           a.IW == a.OW && a.IW <= kStripMaxW && a.lda == a.CR && a.CR % 32 == 0 && a.NO % 64 == 0 && a.IH >= 1;
+}
+
 bool gather_tile_ok(const GatherArgs& a, int tile)
 {
     if (tile < 0 || tile >= RN50_NUM_GATHER_TILES) return false;
+    if (tile == RN50_TILE_STRIP_256 || tile == RN50_TILE_STRIP_128 || tile == RN50_TILE_STRIP_64) return strip_ok(a);
+    if (tile == RN50_TILE_128x128_K64 || tile == RN50_TILE_256x128_K64) return a.NO % 128 == 0 && a.CR % 64 == 0;
+    if (tile == RN50_TILE_256x64_K64) return a.CR % 64 == 0;
     if (tile == RN50_TILE_64x64_K128 || tile == RN50_TILE_128x64_K128) return a.CR % 128 == 0;
     if (tile == RN50_TILE_64x64_K256) return a.CR % 256 == 0;
     return (tile != RN50_TILE_128x128 && tile != RN50_TILE_128x128_SHORT) || a.NO % 128 == 0;
@@ -723,7 +931,13 @@ int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, in
 {
     if (a.CR == 32)                 // stem forward
         return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
-    if (!gather_tile_ok(a, tile)) tile = gather_tile_heuristic(a);
+    // RN50_TILE_STRICT (tuning): a variant that does not apply to this shape is an error instead of a fallback
+    const bool strict = tile >= 0 && (tile & RN50_TILE_STRICT) != 0;
+    if (tile >= 0) tile &= ~RN50_TILE_STRICT;
+    if (!gather_tile_ok(a, tile)) {
+        if (strict) return RN50_ERR_SHAPE;
+        tile = gather_tile_heuristic(a);
+    }
     static_assert(RN50_K_GATHER_TILE_LAST - RN50_K_GATHER_TILE0 + 1 == RN50_NUM_GATHER_TILES, "one profile id per tile variant");
     const int kid = RN50_K_GATHER_TILE0 + tile;
     switch (tile) {
@@ -738,10 +952,30 @@ int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, in
         case RN50_TILE_64x64_K128: return launch_gather<64, 64, 128, 2, 2>(a, s, kid, flops, bytes);
         case RN50_TILE_128x64_K128: return launch_gather<128, 64, 128, 2, 1>(a, s, kid, flops, bytes);
         case RN50_TILE_64x64_K256: return launch_gather<64, 64, 256, 2, 1>(a, s, kid, flops, bytes);
+        case RN50_TILE_128x128_K64: return launch_gather<128, 128, 64, 2, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_256x64_K64: return launch_gather<256, 64, 64, 2, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_256x128_K64: return launch_gather<256, 128, 64, 2, 1>(a, s, kid, flops, bytes);
+        case RN50_TILE_STRIP_256: return launch_strip<256, 4, 1>(a, s, kid, flops, bytes);
+        case RN50_TILE_STRIP_128: return launch_strip<128, 2, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_STRIP_64: return launch_strip<64, 2, 2>(a, s, kid, flops, bytes);
         default: tile = RN50_TILE_64x64_K32; return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_TILE0 + tile, flops, bytes);
     }
 }
 
+}  // namespace
+
+// output rows (pixels) per workgroup of a gather-GEMM tile variant
+int rn50_gather_tile_rows(int tile)
+{
+    switch (tile) {
+        case RN50_TILE_64x64_DEEP: case RN50_TILE_64x64_WIDE: case RN50_TILE_64x64_K32: case RN50_TILE_64x64_K128:
+        case RN50_TILE_64x64_K256: case RN50_TILE_STRIP_64: return 64;
+        case RN50_TILE_256x64: case RN50_TILE_256x64_K64: case RN50_TILE_256x128_K64: case RN50_TILE_STRIP_256: return 256;
+        default: return 128;
+    }
+}
+
+namespace {
 // algorithmic work of one convolution (either direction): 2*M*N*K flops; bytes = input pixels actually
 // needed + filter + output, 2 bytes each
 double conv_flops(const conv_desc& d, int P, int Q) { return 2.0 * d.n * P * Q * (double)d.k * d.r * d.s * d.c; }
@@ -891,6 +1125,13 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
             }
             a.ntaps[c] = nt;
         }
+    // A strided 1x1 convolution reaches only the (even, even) input pixels: the other three parity classes of dx are
+    // plain zeros.  Without an addend or a fused epilogue they are cleared by a fill of the whole tensor and only the
+    // first class goes through the GEMM.
+    if (d.r == 1 && d.stride == 2 && !addend && !fuse) {
+        RN50_TRY(rn50_fill_zero(reinterpret_cast<float*>(dx), (size_t)d.n * d.h * d.w * d.c / 2, s));
+        a.ncls = 1;
+    }
     // a strided 1x1 data gradient still writes every pixel of dx
     const double bytes = conv_bytes(d, P, Q, addend != nullptr) +
                          ((d.r == 1 && d.stride > 1) ? 2.0 * d.n * ((double)d.h * d.w - (double)P * Q) * d.c : 0.0);

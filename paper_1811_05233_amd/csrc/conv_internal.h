@@ -18,7 +18,14 @@ enum {
     RN50_TILE_64x64_K128,      // 64x64, 128-wide slabs, 2 stages (reduction length a multiple of 128)
     RN50_TILE_128x64_K128,     // 128x64, 128-wide slabs, 2 stages (reduction length a multiple of 128)
     RN50_TILE_64x64_K256,      // 64x64, 256-wide slabs, 2 stages (reduction length a multiple of 256)
+    RN50_TILE_128x128_K64,     // 128x128, 64-wide slabs, 2 stages, 2 workgroups per compute unit
+    RN50_TILE_256x64_K64,      // 256x64, 64-wide slabs, 2 stages
+    RN50_TILE_256x128_K64,     // 256x128, 64-wide slabs, 2 stages, 1 workgroup per compute unit
+    RN50_TILE_STRIP_256,       // 3x3 / stride 1 only: 256 pixels x 64 columns, one input strip per 32-channel slab for all 9 taps
+    RN50_TILE_STRIP_128,       //   the same with 128 pixels
+    RN50_TILE_STRIP_64,        //   the same with 64 pixels
     RN50_NUM_GATHER_TILES,
+    RN50_TILE_STRICT = 0x1000,  // flag on a tile id: fail with RN50_ERR_SHAPE instead of falling back when it does not apply
     RN50_NUM_WGRAD_TILES = 10,
     RN50_NUM_WGRAD_VARIANTS = 3 * RN50_NUM_WGRAD_TILES      // tile x split target
 };
@@ -78,6 +85,7 @@ struct WgradArgs {
 };
 
 bool rn50_conv_is_stem(const conv_desc& d);
+int rn50_gather_tile_rows(int tile);
 int rn50_conv_validate(const conv_desc* d);
 size_t rn50_stem_padded_bytes(const conv_desc& d);
 size_t rn50_stem_packed_filter_bytes(const conv_desc& d);

@@ -17,6 +17,9 @@ int rn50_bn_bwd_launch(long long m, int c, bool relu, const h16* dy, const h16* 
                        const float* save_mean, const float* save_invstd, h16* dx, h16* dres,
                        h16* dgamma, h16* dbeta, float* ws, hipStream_t s);
 size_t rn50_bn_ws_floats(int c);
+// most row tiles of partial sums that the from_partials launchers combine inside the apply kernel; beyond this
+// they run a separate finalize kernel first
+int rn50_bn_fused_max_tiles();
 int rn50_bn_fwd_from_partials_launch(long long m, int c, float eps, bool relu, const h16* x, const float* gamma,
                                      const float* beta, const h16* res, h16* y, float* save_mean, float* save_invstd,
                                      const float* part, int ntiles, hipStream_t s);

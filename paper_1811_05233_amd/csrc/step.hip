@@ -442,21 +442,32 @@ namespace {
 // leaves its (identical) result in place.
 inline float no_penalty(int) { return 0.f; }
 
+// A convolution whose epilogue leaves more row tiles of BatchNorm partial sums than the apply kernel combines by
+// itself costs one more (small, dependent) launch afterwards: charged to the tile variants that cause it.
+inline float finalize_penalty(long long rows, int tile)
+{
+    const int per = rn50_gather_tile_rows(tile);
+    return (rows + per - 1) / per > rn50_bn_fused_max_tiles() ? 0.008f : 0.f;
+}
+
 // penalty_ms(cand) is added to a candidate's measured time (cost the timing in isolation does not show).
+// cand_flag is or-ed to every candidate while tuning (RN50_TILE_STRICT: candidates that do not apply are skipped).
 template <class F, class G = float (*)(int)>
 int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch, const char* what = "", const char* layer = "",
-                   G penalty_ms = no_penalty)
+                   G penalty_ms = no_penalty, int cand_flag = 0)
 {
     if (!c.tuning) return launch(*choice);
     char line[160];
     float best_ms = 1e30f;
     int best = RN50_TILE_AUTO;
     for (int cand = 0; cand < ncand; ++cand) {
-        RN50_TRY(launch(cand));
+        const int first = launch(cand | cand_flag);
+        if (first == RN50_ERR_SHAPE && cand_flag) continue;       // not applicable to this shape
+        RN50_TRY(first);
         hipError_t e = hipEventRecord(c.tune_e0, s);
         if (e != hipSuccess) return rn50_hip_fail(e);
-        RN50_TRY(launch(cand));
-        RN50_TRY(launch(cand));
+        RN50_TRY(launch(cand | cand_flag));
+        RN50_TRY(launch(cand | cand_flag));
         e = hipEventRecord(c.tune_e1, s);
         if (e == hipSuccess) e = hipEventSynchronize(c.tune_e1);
         float ms = 0.f;
@@ -511,7 +522,8 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         int tiles = 0;
         RN50_TRY(launch_or_tune(c, st, l.d.c == 3 ? 1 : RN50_NUM_GATHER_TILES, &l.fwd_tile, [&](int tile) {
             return rn50_conv_fwd_launch(l.d, x, wts, l.conv_out, st, part, &tiles, tile);
-        }, "fwd", l.name.c_str()));
+        }, "fwd", l.name.c_str(), [&](int tile) { return finalize_penalty((long long)l.d.n * l.P * l.Q, tile); },
+        l.d.c == 3 ? 0 : RN50_TILE_STRICT));
         return rn50_bn_fwd_from_partials_launch((long long)l.d.n * l.P * l.Q, l.d.k, cfg.bn_eps, relu, l.conv_out,
                                                 master_w + l.gamma_off, master_w + l.beta_off, residual, l.bn_out,
                                                 l.mean, l.invstd, part, tiles, st);
@@ -619,7 +631,9 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         return launch_or_tune(c, s, RN50_NUM_GATHER_TILES, &l.dgrad_tile, [&](int tile) {
             return rn50_conv_dgrad_launch(d, l.dconv, c.wt_all + l.wt_off, addend, l.din, s, prev ? &f : nullptr,
                                           prev ? &fused_tiles : nullptr, tile, compact_addend);
-        }, "dgrad", l.name.c_str());
+        }, "dgrad", l.name.c_str(), [&](int tile) {
+            return (prev && d.stride == 1) ? finalize_penalty((long long)d.n * d.h * d.w, tile) : 0.f;
+        }, RN50_TILE_STRICT);
     };
 
     const h16* dY = c.head_din;
