@@ -3,12 +3,18 @@
 // (one 16-byte chunk per row) and walks rows, so every access is a coalesced 16-byte
 // load/store and per-channel parameters stay in registers.
 //
-// Reductions are two-stage and deterministic: every workgroup writes per-channel partial
-// sums to the workspace, a small second kernel combines them in a fixed order (in double).
+// Reductions are two-stage and deterministic: every workgroup writes per-channel FP32 partial
+// sums to the workspace, a second stage combines them in a fixed order: FP32 within a row
+// lane, double across lanes, waves and for everything that follows (mean, variance).
 // When the partial sums come from a convolution epilogue and there are at most 400 row tiles,
-// the apply kernels combine them themselves (per 64-channel slice) and no second kernel runs.
-// The forward statistics are accumulated around a per-channel pivot (row 0) so that
-// E[x^2]-E[x]^2 does not cancel when |mean| >> sigma.
+// the apply kernels combine them themselves (per 64-channel slice, in double) and no second
+// kernel runs.
+// The stand-alone forward statistics (bn_relu_fwd, bn_batch_moments) are accumulated around a
+// per-channel pivot (row 0) so that E[x^2]-E[x]^2 does not cancel when |mean| >> sigma.  The
+// partial sums a convolution epilogue leaves (whole-step path) are plain sum x / sum x^2 of
+// at most 256 rows per tile in FP32 (pivot 0): with |mean| = r*sigma the variance carries a
+// relative error of about r^2 * 2^-24 per tile, i.e. 1/sqrt(var+eps) is good to 1e-4 up to
+// r of about 40 and degrades as r^2 beyond; BN inputs here are zero-mean-ish conv outputs.
 #include "common.h"
 #include "misc_internal.h"
 #include "prof.h"
@@ -393,12 +399,12 @@ constexpr int kFusedMaxTiles = 400;      // beyond this the redundant summing co
 // Column sums of part[ntiles][2][c] for channels [ch0, ch0 + 64): s[0..63] = first sums, s[64..127] = second sums.
 __device__ __forceinline__ void slice_partial_sums(const float* __restrict__ part, int c, int ntiles, int ch0, double* s)
 {
-    __shared__ float red[4][128];
+    __shared__ double red[4][128];
     const int tid = threadIdx.x;
     const int cl = tid & 31, rl = tid >> 5;                       // 32 x 16-byte columns, 8 row lanes
     const float* p = part + (size_t)(cl >> 4) * c + ch0 + (cl & 15) * 4;
     const size_t pitch = 2 * (size_t)c;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
     for (int r0 = rl; r0 < ntiles; r0 += 64) {
         f32x4 v[8];
 #pragma unroll
@@ -407,7 +413,9 @@ __device__ __forceinline__ void slice_partial_sums(const float* __restrict__ par
             v[u] = r < ntiles ? *reinterpret_cast<const f32x4*>(p + (size_t)r * pitch) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc += v[u];
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] += (double)v[u][j];
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[j] += __shfl_xor(acc[j], 32, 64);
@@ -416,7 +424,7 @@ __device__ __forceinline__ void slice_partial_sums(const float* __restrict__ par
         for (int j = 0; j < 4; ++j) red[tid >> 6][cl * 4 + j] = acc[j];
     }
     __syncthreads();
-    if (tid < 128) s[tid] = (double)red[0][tid] + (double)red[1][tid] + (double)red[2][tid] + (double)red[3][tid];
+    if (tid < 128) s[tid] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
     __syncthreads();
 }
 

@@ -25,18 +25,29 @@ namespace {
 
 constexpr int kThreads = 256;
 
-// LDS tile of ROWS rows x KW halfs (KW = 32, 64 or 128), addressed in 16-byte chunks with an XOR
-// swizzle that keeps both the row-wise MFMA operand reads and the transposing writes conflict-free.
+// LDS tile of ROWS rows x KW halfs (KW = 32, 64, 128 or 256), addressed in 16-byte chunks.  A ds_read_b128 is served
+// 16 lanes at a time (16 lanes x 16 bytes = the 64 banks), and the 16 lanes of such a group read 16 consecutive rows
+// at one chunk index; the chunk index is therefore XOR-ed with a function of the row that gives those 16 rows 16
+// different 16-byte slots of the 256-byte bank space:
+//   KW = 32  (64-byte rows, four rows per bank space): rows r, r+4, r+8, r+12 share a quarter -> chunk ^ ((r >> 2) & 3)
+//   KW = 64  (128-byte rows, two per bank space):       even / odd rows share a half           -> chunk ^ ((r ^ (r >> 3)) & 7)
+//   KW >= 128 (every row spans the whole bank space):                                           -> chunk ^ (r & 15)
+// (the first holds for any 16 consecutive rows, which the strip kernel's shifted reads need).
+template <int KW>
+__device__ __forceinline__ int lds_swz(int row) {
+    if (KW == 32) return (row >> 2) & 3;
+    if (KW == 64) return (row ^ (row >> 3)) & 7;
+    return row & 15;
+}
 template <int KW>
 __device__ __forceinline__ int lds_off(int row, int chunk) {
-    const int sw = (row ^ (row >> 3)) & 7;
     if (KW == 32) {
         // two rows share a 128-byte line
         const int line = row >> 1;
-        const int slot = ((row & 1) << 2) | ((chunk ^ (line & 3)) & 3);
+        const int slot = ((row & 1) << 2) | ((chunk ^ lds_swz<32>(row)) & 3);
         return line * 64 + slot * 8;
     }
-    return row * KW + ((chunk ^ sw)) * 8;   // XOR touches only the low 3 bits of the chunk index
+    return row * KW + (chunk ^ lds_swz<KW>(row)) * 8;   // XOR touches only the low bits of the chunk index
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -257,10 +268,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     int row_in_grp, phys;
     if (BK >= 64) { row_in_grp = lane / CPR; phys = lane % CPR; }
     else { row_in_grp = 2 * (lane >> 3) + ((lane & 7) >> 2); phys = lane & 3; }
-    auto logical_chunk = [&](int row) {
-        if (BK >= 64) return phys ^ ((row ^ (row >> 3)) & 7);
-        return phys ^ ((row >> 1) & 3);
-    };
+    auto logical_chunk = [&](int row) { return phys ^ lds_swz<BK>(row); };
 
     int a_h0[NA], a_w0[NA];
     unsigned a_voff[NA], b_voff[NB];
@@ -438,7 +446,7 @@ __global__ __launch_bounds__(kThreads, 1) void strip_gemm_kernel(const GatherArg
     for (int j = 0; j < NAJ; ++j) {
         const int row = (wave + 4 * j) * 16 + row_in_grp;
         const int p = p0 + row;
-        const int chunk = phys ^ ((row >> 1) & 3);
+        const int chunk = phys ^ lds_swz<BK>(row);
         a_voff[j] = ((unsigned)p < (unsigned)M) ? (unsigned)(p * lda) * 2u + chunk * 16 : kOutOfRange;
     }
 #pragma unroll
@@ -446,7 +454,7 @@ __global__ __launch_bounds__(kThreads, 1) void strip_gemm_kernel(const GatherArg
         const int row = (wave + 4 * j) * 16 + row_in_grp;          // = tap slot * 64 + column
         const int slot = row >> 6, col = row & 63;
         const int bt = a.tap[0][slot] >> 16;                       // filter tap of this slot
-        const int chunk = phys ^ ((row >> 1) & 3);
+        const int chunk = phys ^ lds_swz<BK>(row);
         b_voff[j] = (unsigned)(((nt * BN + col) * T + bt) * CR) * 2u + chunk * 16;
     }
     const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<h16*>(a.A), 0, a.a_bytes, 0x00020000);

@@ -180,7 +180,7 @@ def test_step_two_blocks_per_stage_ragged_batch():
 
 
 def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, loss_scale=1024.0, classes=1000,
-                       autotune=False, lars=None, plan_check=False):
+                       autotune=False, lars=None, plan_check=False, mutate=None):
     """Every kernel launch inside one rn50_step call, checked where it ran: the oracle recomputes
     each layer's result from the GPU's OWN input tensors of that layer (read back from the workspace,
     keep_grads=1), so rounding differences cannot pile up over the depth of the network and the
@@ -191,6 +191,8 @@ def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, 
           flush=True)
     f64 = np.float64
     cfg, net, w, x, lab = make_problem(batch, image_hw, has_stem, blocks, classes, loss_scale)
+    if mutate:
+        mutate(net, w, x)
     cfg.keep_grads = 1
     lr, mu, wd_ = 0.1, 0.9, 1e-4
     hp = P.rn50_hparams(lr, mu, wd_, 1.0 / loss_scale, *(lars or (0.0, 0.0)))
@@ -353,6 +355,18 @@ def test_step_resnet50_batch32_in_situ_sampled():
 
 def test_step_small_in_situ_ragged():
     check_step_in_situ(3, (32, 48), True, (2, 2), plan_check=True)
+
+
+def test_step_large_mean_channel_through_the_conv_epilogue_statistics():
+    """Inside rn50_step the BN statistics come from the convolution epilogue as plain FP32 sum x / sum x^2 per row
+    tile (no pivot).  One output channel of conv1 is given mean = 32 sigma (inputs shifted to mean 4, its filter
+    constant 1/8): mean and 1/sqrt(var+eps) of every channel must still pass the in-situ bounds (1e-5 / 1e-4)."""
+    def mutate(net, w, x):
+        x += 4.0
+        x[...] = x.astype(np.float16).astype(np.float32)            # keep the inputs binary16-representable
+        sg = net.seg["s1b0c1.w"]
+        w[sg.offset:sg.offset + sg.count].reshape(sg.shape)[0] = 0.125
+    check_step_in_situ(4, (56, 56), False, (1,), mutate=mutate)
 
 
 def test_step_small_in_situ_lars_update():
