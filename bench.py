@@ -345,9 +345,9 @@ def main():
     def step():
         ctx.step(x, lab, w, v, w16, g16, hp, loss)
 
-    if not args.tuning_file and not args.autotune and not args.no_autotune and B == 32 and os.path.exists(os.path.join(ROOT, PACKAGED_TUNING)):
-        args.tuning_file = os.path.join(ROOT, PACKAGED_TUNING)
-    shipped = os.path.abspath(args.tuning_file) == os.path.join(ROOT, PACKAGED_TUNING) if args.tuning_file else False
+    if not args.tuning_file and not args.autotune and not args.no_autotune and P.shipped_tuning_path(B):
+        args.tuning_file = P.shipped_tuning_path(B)
+    shipped = os.path.abspath(args.tuning_file) == P.shipped_tuning_path(B) if args.tuning_file else False
     if args.tuning_file and os.path.exists(args.tuning_file) and not args.autotune:
         ctx.set_tuning(json.load(open(args.tuning_file))["table"])
     elif not args.no_autotune:

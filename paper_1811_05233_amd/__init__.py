@@ -352,6 +352,23 @@ def rn50_workspace_bytes(cfg):
     return int(lib().rn50_workspace_bytes(ctypes.byref(cfg)))
 
 
+def shipped_tuning_path(batch):
+    """File of the kernel-variant table shipped for full ResNet-50 at this per-GPU batch size (written by
+    tune_in_situ on an MI355X), or None if none is shipped for it."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "tuning_resnet50_b%d.json" % int(batch))
+    return path if os.path.exists(path) else None
+
+
+def shipped_tuning(batch):
+    """The shipped variant table ([fwd, dgrad, wgrad] per convolution, for Rn50Context.set_tuning) or None."""
+    path = shipped_tuning_path(batch)
+    if path is None:
+        return None
+    import json
+    with open(path) as f:
+        return json.load(f)["table"]
+
+
 class Rn50Context:
     """Owns the workspace tensor and the rn50_ctx handle."""
 

@@ -408,10 +408,10 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
 // flight while the 9 x 2 x TM x TN MFMAs of the current one run.
 constexpr int kStripMaxW = 56;      // widest image row the strip buffer is sized for
 
-template <int BM, int WR, int WC>
-__global__ __launch_bounds__(kThreads, 1) void strip_gemm_kernel(const GatherArgs a)
+template <int BM, int WR, int WC, int NST, int OCC>
+__global__ __launch_bounds__(kThreads, OCC) void strip_gemm_kernel(const GatherArgs a)
 {
-    constexpr int BN = 64, BK = 32, NST = 2, T = 9;
+    constexpr int BN = 64, BK = 32, T = 9;
     constexpr int SROWS = (BM + 2 * kStripMaxW + 2 + 15) / 16 * 16;    // strip rows per stage, whole 1 KB DMA blocks
     constexpr int BROWS = T * BN;
     constexpr int NAJ = SROWS / 16 / 4, NBJ = BROWS / 16 / 4;          // DMA loads per thread and slab
@@ -476,7 +476,7 @@ __global__ __launch_bounds__(kThreads, 1) void strip_gemm_kernel(const GatherArg
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(sa + (wave + 4 * j) * 512), 16, (int)voff, 0, 0, 0);
             }
         ++ld_cc;
-        ld_stage ^= 1;
+        if (NST == 2) ld_stage ^= 1;
     };
     issue_slab();
 
@@ -518,7 +518,7 @@ __global__ __launch_bounds__(kThreads, 1) void strip_gemm_kernel(const GatherArg
         RN50_WAIT_VMCNT(0);                   // this wave's part of slab kit has landed
         RN50_WAIT_LGKMCNT0();
         __builtin_amdgcn_s_barrier();         // everyone's part has; the other stage is free
-        if (kit + 1 < KC) issue_slab();
+        if (NST == 2 && kit + 1 < KC) issue_slab();
         const h16* sa = lds + cur * STAGE;
         const h16* sb = sa + SROWS * BK;
         // The operands of tap t+1 are requested before the MFMAs of tap t are issued (two register sets), so that
@@ -554,7 +554,14 @@ __global__ __launch_bounds__(kThreads, 1) void strip_gemm_kernel(const GatherArg
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        cur ^= 1;
+        if (NST == 2) cur ^= 1;
+        else if (kit + 1 < KC) {
+            // single stage (several workgroups per compute unit overlap each other's loads and MFMAs instead):
+            // the next slab overwrites this one once every wave is done reading it
+            RN50_WAIT_LGKMCNT0();
+            __builtin_amdgcn_s_barrier();
+            issue_slab();
+        }
     }
     RN50_WAIT_LGKMCNT0();
     __builtin_amdgcn_s_barrier();
@@ -745,6 +752,153 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_kernel(const WgradArgs a)
         }
 }
 
+// Filter gradient of a 3x3 / stride 1 / pad 1 convolution with operand reuse across the nine taps.
+// Pixels are enumerated in PADDED coordinates (h+1, w+1) of an (H+2) x (W+2) frame per image; positions on the
+// frame's border hold zeros (the DMA leaves them to the out-of-range zero fill, nothing is padded in memory).  In
+// these coordinates tap (r, s) of output position pp is input position pp + (r-1)*(W+2) + (s-1) for every pp,
+// border included (there dy is zero), so one slab of dy positions and ONE strip of x positions (the slab's range
+// widened by W+3 on either side) serve all nine taps: a workgroup owns 64 output channels x 9 taps x 64 input
+// channels, reads each dy fragment once per k-step for nine MFMAs, and moves 4-6 times fewer bytes from L2 into
+// LDS per MFMA than the tile-per-tap kernel above.  No masks are needed.
+// A K-slab is RPS = floor(64 / (W+2)) whole frame rows of one image (padded with zero rows to 64 positions), so
+// that a lane's place inside a slab (frame row, frame column) never changes and the per-slab address arithmetic is
+// scalar; the reduction gets up to 30 % longer for it (frame border + slab padding).  Slab ranges are split over
+// workgroups as above (partial tiles, fixed-order sum).
+constexpr int kWStripMaxW = 56, kWStripMinW = 10;                 // narrower images waste most of a 64-position slab
+constexpr int kWStripPix = 64;                                    // positions per K-slab
+constexpr int kWStripRows = 192;                                  // x strip rows per stage: 64 + 2*(56+2) + 2 = 182, in whole rounds of 32
+
+__global__ __launch_bounds__(kThreads, 2) void wgrad_strip_kernel(const WgradArgs a)
+{
+    constexpr int BKP = kWStripPix, SROWS = kWStripRows, NST = 2, T = 9;
+    constexpr int NA = BKP / 8 / 4, NB = SROWS / 8 / 4;            // wave-wide loads (8 rows of 128 bytes) per thread and slab
+    constexpr int STAGE = (BKP + SROWS) * 64;                      // halfs
+    constexpr unsigned kOutOfRange = 0x80000000u;
+    __shared__ __attribute__((aligned(16))) h16 lds[NST * STAGE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, lg = lane >> 5;
+    const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+
+    const int K = a.K, C = a.C, H = a.H, W = a.W;
+    const int WP = W + 2;
+    const int rps = a.P, spi = a.Q;                                // frame rows per slab, slabs per image (set by the launcher)
+    const int m_tiles = K / 64, n_tiles = C / 64;
+    int bid = rn50_xcd_remap(blockIdx.x, gridDim.x);               // the tiles of one slab range share its dy / x rows: same L2
+    const int nt = bid % n_tiles; bid /= n_tiles;
+    const int mt = bid % m_tiles;
+    const int split = bid / m_tiles;
+    const int slab_begin = split * a.pix_per_split;                // in slabs
+    int slab_end = slab_begin + a.pix_per_split;
+    if (slab_end > a.npix) slab_end = a.npix;                      // npix: slabs in all
+    const int kiters = slab_end - slab_begin;
+    const int nbw = (BKP + 2 * WP + 2 + 7) >> 3;                   // wave-wide loads the strip needs
+
+    // ---- this lane's fixed place in every slab: frame row (relative to the slab's first) and frame column ----
+    const int pl = lane >> 3, chunk = (lane & 7) ^ ((pl & 3) << 1);       // row inside a wave-wide load, swizzled 16-byte chunk
+    int a_row[NA], b_row[NB];
+    unsigned a_off[NA], b_off[NB];
+    bool a_ok[NA], b_ok[NB];
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        const int i = (wave + 4 * j) * 8 + pl;                     // slab position
+        const int rr = i / WP, wp = i - rr * WP;
+        a_row[j] = rr;
+        a_ok[j] = rr < rps && wp >= 1 && wp <= W;
+        a_off[j] = (unsigned)((rr * W + wp) * K + mt * 64 + chunk * 8) * 2u;
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int sr = (wave + 4 * j) * 8 + pl;                    // strip row: slab position sr - (WP + 1)
+        const int t = sr + WP - 1, q = t / WP, wp = t - q * WP;
+        b_row[j] = q - 2;
+        b_ok[j] = wp >= 1 && wp <= W;
+        b_off[j] = (unsigned)(((q - 2) * W + wp) * C + nt * 64 + chunk * 8) * 2u;
+    }
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<h16*>(a.dy), 0, a.dy_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(const_cast<h16*>(a.x), 0, a.x_bytes, 0x00020000);
+
+    int ld_n = slab_begin / spi, ld_si = slab_begin - ld_n * spi, ld_stage = 0;     // image and slab-in-image of the next slab to load
+    auto issue_slab = [&]() {
+        h16* sa = lds + ld_stage * STAGE;
+        h16* sb = sa + BKP * 64;
+        const int hp0 = ld_si * rps;                                                // frame row of slab position 0
+        const int pix0 = (ld_n * H + hp0 - 1) * W - 1;                              // pixel index of frame position (hp0, 0), may be negative
+        const unsigned base_a = (unsigned)(pix0 * K) * 2u, base_b = (unsigned)(pix0 * C) * 2u;
+#pragma unroll
+        for (int j = 0; j < NA; ++j) {
+            const bool ok = a_ok[j] && (unsigned)(hp0 + a_row[j] - 1) < (unsigned)H;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(sa + (wave + 4 * j) * 512), 16,
+                                                     (int)(ok ? base_a + a_off[j] : kOutOfRange), 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            if (wave + 4 * j < nbw) {          // wave-uniform
+                const bool ok = b_ok[j] && (unsigned)(hp0 + b_row[j] - 1) < (unsigned)H;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(sb + (wave + 4 * j) * 512), 16,
+                                                         (int)(ok ? base_b + b_off[j] : kOutOfRange), 0, 0, 0);
+            }
+        if (++ld_si == spi) { ld_si = 0; ++ld_n; }
+        ld_stage ^= 1;
+    };
+    if (kiters > 0) issue_slab();
+
+    f32x16 acc[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+    // transposing-read addresses (see wgrad_kernel): lane 4*jj+r of a 16-lane group reads channels 4r..4r+3 of pixel jj
+    const int g4 = lane >> 4, jj = (lane >> 2) & 3, rr = lane & 3;
+    const int cha = wm0 + 16 * (g4 & 1) + 4 * rr, chb = wn0 + 16 * (g4 & 1) + 4 * rr;
+    const int fa_off = (8 * (g4 >> 1) + jj) * 64 + ((((cha >> 3) ^ (jj << 1)) << 3) | (cha & 7));
+    int fb_off[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int row = 8 * (g4 >> 1) + jj + (t / 3) * WP + (t % 3);        // strip row 0 is slab position - (W+2) - 1
+        fb_off[t] = row * 64 + ((((chb >> 3) ^ ((row & 3) << 1)) << 3) | (chb & 7));
+    }
+
+    int cur = 0;
+    for (int kit = 0; kit < kiters; ++kit) {
+        RN50_WAIT_VMCNT(0);
+        RN50_WAIT_LGKMCNT0();
+        __builtin_amdgcn_s_barrier();
+        if (kit + 1 < kiters) issue_slab();
+        h16* sa = lds + cur * STAGE;
+        h16* sb = sa + BKP * 64;
+#pragma unroll
+        for (int ks = 0; ks < BKP / 16; ++ks) {
+            const h16x4 alo = lds_read_tr(sa + fa_off + (ks * 16) * 64);
+            const h16x4 ahi = lds_read_tr(sa + fa_off + (ks * 16 + 4) * 64);
+            const h16x8 fa = __builtin_shufflevector(alo, ahi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const h16x4 lo = lds_read_tr(sb + fb_off[t] + (ks * 16) * 64);
+                const h16x4 hi = lds_read_tr(sb + fb_off[t] + (ks * 16 + 4) * 64);
+                const h16x8 fb = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, acc[t], 0, 0, 0);
+            }
+        }
+        cur ^= 1;
+    }
+
+    // ---- FP32 partial tile [K][9][C]: lane owns column li, rows 8*(v/4) + 4*lg + v%4 ----
+    const int row_len = T * C;
+    float* out = a.out + (size_t)split * a.split_stride;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int col = t * C + nt * 64 + wn0 + li;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = mt * 64 + wm0 + (v / 4) * 8 + lg * 4 + (v % 4);
+            out[(size_t)row * row_len + col] = acc[t][v];
+        }
+    }
+}
+
 // out[i] = sum over splits of part[s][i], stored as FP32 or rounded to half (the flat FP16 gradient).  A workgroup
 // owns 16 consecutive float4 elements; 16 split lanes each add every 16th split in order, and their sums are
 // combined in a fixed order through LDS.
@@ -888,7 +1042,7 @@ int launch_gather(GatherArgs& a, hipStream_t s, int kid, double flops, double by
     return rn50_check_launch();
 }
 
-template <int BM, int WR, int WC>
+template <int BM, int WR, int WC, int NST, int OCC>
 int launch_strip(GatherArgs& a, hipStream_t s, int kid, double flops, double bytes)
 {
     const long long M = (long long)a.NB * a.cOHs[0] * a.cOWs[0];
@@ -898,7 +1052,7 @@ int launch_strip(GatherArgs& a, hipStream_t s, int kid, double flops, double byt
     a.inv_ow[0] = 1.0f / (float)a.cOWs[0];
     if (total == 0) return RN50_OK;
     ProfScope ps(kid, flops, bytes, s);
-    strip_gemm_kernel<BM, WR, WC><<<total * (a.NO / 64), kThreads, 0, s>>>(a);
+    strip_gemm_kernel<BM, WR, WC, NST, OCC><<<total * (a.NO / 64), kThreads, 0, s>>>(a);
     return rn50_check_launch();
 }
 
@@ -912,7 +1066,7 @@ bool strip_ok(const GatherArgs& a)
 bool gather_tile_ok(const GatherArgs& a, int tile)
 {
     if (tile < 0 || tile >= RN50_NUM_GATHER_TILES) return false;
-    if (tile == RN50_TILE_STRIP_256 || tile == RN50_TILE_STRIP_128 || tile == RN50_TILE_STRIP_64) return strip_ok(a);
+    if (tile >= RN50_TILE_STRIP_256 && tile <= RN50_TILE_STRIP_64_S1) return strip_ok(a);
     if (tile == RN50_TILE_128x128_K64 || tile == RN50_TILE_256x128_K64) return a.NO % 128 == 0 && a.CR % 64 == 0;
     if (tile == RN50_TILE_256x64_K64) return a.CR % 64 == 0;
     if (tile == RN50_TILE_64x64_K128 || tile == RN50_TILE_128x64_K128) return a.CR % 128 == 0;
@@ -963,9 +1117,12 @@ int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, in
         case RN50_TILE_128x128_K64: return launch_gather<128, 128, 64, 2, 2>(a, s, kid, flops, bytes);
         case RN50_TILE_256x64_K64: return launch_gather<256, 64, 64, 2, 2>(a, s, kid, flops, bytes);
         case RN50_TILE_256x128_K64: return launch_gather<256, 128, 64, 2, 1>(a, s, kid, flops, bytes);
-        case RN50_TILE_STRIP_256: return launch_strip<256, 4, 1>(a, s, kid, flops, bytes);
-        case RN50_TILE_STRIP_128: return launch_strip<128, 2, 2>(a, s, kid, flops, bytes);
-        case RN50_TILE_STRIP_64: return launch_strip<64, 2, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_STRIP_256: return launch_strip<256, 4, 1, 2, 1>(a, s, kid, flops, bytes);
+        case RN50_TILE_STRIP_128: return launch_strip<128, 2, 2, 2, 1>(a, s, kid, flops, bytes);
+        case RN50_TILE_STRIP_64: return launch_strip<64, 2, 2, 2, 1>(a, s, kid, flops, bytes);
+        case RN50_TILE_STRIP_256_S1: return launch_strip<256, 4, 1, 1, 2>(a, s, kid, flops, bytes);
+        case RN50_TILE_STRIP_128_S1: return launch_strip<128, 2, 2, 1, 3>(a, s, kid, flops, bytes);
+        case RN50_TILE_STRIP_64_S1: return launch_strip<64, 2, 2, 1, 3>(a, s, kid, flops, bytes);
         default: tile = RN50_TILE_64x64_K32; return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_TILE0 + tile, flops, bytes);
     }
 }
@@ -977,8 +1134,9 @@ int rn50_gather_tile_rows(int tile)
 {
     switch (tile) {
         case RN50_TILE_64x64_DEEP: case RN50_TILE_64x64_WIDE: case RN50_TILE_64x64_K32: case RN50_TILE_64x64_K128:
-        case RN50_TILE_64x64_K256: case RN50_TILE_STRIP_64: return 64;
-        case RN50_TILE_256x64: case RN50_TILE_256x64_K64: case RN50_TILE_256x128_K64: case RN50_TILE_STRIP_256: return 256;
+        case RN50_TILE_64x64_K256: case RN50_TILE_STRIP_64: case RN50_TILE_STRIP_64_S1: return 64;
+        case RN50_TILE_256x64: case RN50_TILE_256x64_K64: case RN50_TILE_256x128_K64: case RN50_TILE_STRIP_256:
+        case RN50_TILE_STRIP_256_S1: return 256;
         default: return 128;
     }
 }
@@ -1173,12 +1331,22 @@ namespace {
 // Tile variants of the filter gradient: (filters) x (filter-element columns), ring stages, pixels per K-slab.
 // A shape that does not allow a 128-wide side runs the 64x64 tile of the same slab depth instead.
 struct WgradTile { int BM, BN, NST, BKP; };
-constexpr WgradTile kWgradTiles[RN50_NUM_WGRAD_TILES] = {
+constexpr WgradTile kWgradTiles[RN50_WGRAD_TILE_STRIP] = {
     {128, 128, 4, 32}, {64, 64, 4, 32}, {64, 128, 4, 32}, {128, 64, 4, 32},
     {64, 64, 3, 64}, {64, 64, 2, 64}, {64, 64, 2, 128}, {64, 128, 3, 64}, {128, 64, 3, 64}, {128, 128, 2, 64}};
 constexpr int kWgradFallback32 = 1, kWgradFallback64 = 4, kWgradFallback128 = 6;   // the 64x64 tile per slab depth
 
-struct WgradPlan { int tile, BM, BN, G, NG, tiles, nsplit, pix_per_split; bool stem; };
+struct WgradPlan { int tile, BM, BN, G, NG, tiles, nsplit, pix_per_split; bool stem, strip; };
+
+// the strip kernel covers 3x3 / stride 1 / pad 1 with image rows of at most kWStripMaxW pixels
+bool wgrad_strip_ok(const conv_desc& d)
+{
+    return d.r == 3 && d.s == 3 && d.stride == 1 && d.pad == 1 && d.w <= kWStripMaxW && d.w >= kWStripMinW && d.c % 64 == 0 &&
+           d.k % 64 == 0;
+}
+// frame rows per 64-position slab, slabs per image
+inline int wstrip_rps(const conv_desc& d) { return kWStripPix / (d.w + 2); }
+inline int wstrip_spi(const conv_desc& d) { return (d.h + 2 + wstrip_rps(d) - 1) / wstrip_rps(d); }
 
 // variant: RN50_TILE_AUTO, or tile_index * 3 + split_index: a kWgradTiles entry and a split target of 256, 512 or
 // 1024 workgroups
@@ -1191,6 +1359,23 @@ WgradPlan wgrad_plan(const conv_desc& d, int variant)
     const int P = out_dim(d.h, d.pad, d.r, d.stride), Q = out_dim(d.w, d.pad, d.s, d.stride);
     const long long npix = (long long)d.n * P * Q;
     p.stem = rn50_conv_is_stem(d);
+    p.strip = false;
+    if (!p.stem && p.tile == RN50_WGRAD_TILE_STRIP) {
+        if (wgrad_strip_ok(d)) {
+            // 64 filters x 9 taps x 64 channels per workgroup; 128, 256 or 512 workgroups; ranges of padded positions
+            p.strip = true;
+            p.BM = 64; p.BN = 64; p.G = 64; p.NG = 9 * d.c / 64;
+            p.tiles = (d.k / 64) * (d.c / 64);
+            const long long slabs_s = (long long)d.n * wstrip_spi(d);
+            long long want_s = ((128 << (variant % 3)) + p.tiles - 1) / p.tiles;
+            long long per = (slabs_s + want_s - 1) / want_s;
+            if (per < 4) per = slabs_s < 4 ? slabs_s : 4;
+            p.pix_per_split = (int)per;                    // in slabs
+            p.nsplit = (int)((slabs_s + per - 1) / per);
+            return p;
+        }
+        p.tile = kWgradFallback128;
+    }
     if (p.stem) { p.tile = -1; p.BM = 64; p.BN = 64; p.G = 32; p.NG = 8; }
     else {
         p.G = 64; p.NG = d.r * d.s * d.c / 64;
@@ -1263,11 +1448,16 @@ int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, h16*
     a.split_stride = rn50_wgrad_acc_floats(d);
     a.out = partials;
     const int grid = p.tiles * p.nsplit;
+    if (p.strip) {      // the reduction runs over slabs of whole frame rows: P = frame rows per slab, Q = slabs per image
+        a.P = wstrip_rps(d); a.Q = wstrip_spi(d);
+        a.npix = d.n * a.Q;
+    }
     {
         const double bytes = 2.0 * ((double)d.n * d.h * d.w * d.c + (double)d.n * P * Q * d.k) + 4.0 * d.k * d.r * d.s * d.c;
         static_assert(RN50_K_WGRAD_TILE_LAST - RN50_K_WGRAD_TILE0 + 1 == RN50_NUM_WGRAD_TILES, "one profile id per tile variant");
         ProfScope ps(p.stem ? RN50_K_WGRAD_STEM : RN50_K_WGRAD_TILE0 + p.tile, conv_flops(d, P, Q), bytes, s);
-        switch (p.tile) {
+        if (p.strip) wgrad_strip_kernel<<<grid, kThreads, 0, s>>>(a);
+        else switch (p.tile) {
             case -1: wgrad_kernel<64, 64, 4, 32, true, 32><<<grid, kThreads, 0, s>>>(a); break;
             case 0: launch_wgrad_tile<0>(a, grid, s); break;
             case 1: launch_wgrad_tile<1>(a, grid, s); break;

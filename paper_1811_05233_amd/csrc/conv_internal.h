@@ -24,9 +24,13 @@ enum {
     RN50_TILE_STRIP_256,       // 3x3 / stride 1 only: 256 pixels x 64 columns, one input strip per 32-channel slab for all 9 taps
     RN50_TILE_STRIP_128,       //   the same with 128 pixels
     RN50_TILE_STRIP_64,        //   the same with 64 pixels
+    RN50_TILE_STRIP_256_S1,    //   single-stage forms of the three (smaller LDS footprint: 2-3 workgroups per compute unit
+    RN50_TILE_STRIP_128_S1,    //   overlap each other's loads and MFMAs instead of a two-stage ring inside one)
+    RN50_TILE_STRIP_64_S1,
     RN50_NUM_GATHER_TILES,
     RN50_TILE_STRICT = 0x1000,  // flag on a tile id: fail with RN50_ERR_SHAPE instead of falling back when it does not apply
-    RN50_NUM_WGRAD_TILES = 10,
+    RN50_WGRAD_TILE_STRIP = 10, // filter-gradient tile index of the 3x3 strip kernel (the ten before it: kWgradTiles)
+    RN50_NUM_WGRAD_TILES = 11,
     RN50_NUM_WGRAD_VARIANTS = 3 * RN50_NUM_WGRAD_TILES      // tile x split target
 };
 

@@ -5,10 +5,10 @@
 
 enum Rn50Kernel {
     RN50_K_GATHER_TILE0 = 0,        // conv forward / data gradient: one id per tile variant (RN50_TILE_* order)
-    RN50_K_GATHER_TILE_LAST = 17,
+    RN50_K_GATHER_TILE_LAST = 20,
     RN50_K_GATHER_STEM,             // stem forward (128x64 tile, 32-wide K slabs)
     RN50_K_WGRAD_TILE0,             // filter gradient: one id per tile variant
-    RN50_K_WGRAD_TILE_LAST = RN50_K_WGRAD_TILE0 + 9,
+    RN50_K_WGRAD_TILE_LAST = RN50_K_WGRAD_TILE0 + 10,
     RN50_K_WGRAD_STEM,
     RN50_K_WGRAD_REDUCE,
     RN50_K_BN_STATS,

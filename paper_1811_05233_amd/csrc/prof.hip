@@ -11,12 +11,13 @@ const char* const kNames[RN50_K_COUNT] = {
     "gather_gemm_kernel<128,128,32,2,3>", "gather_gemm_kernel<256,64,32,3,2>", "gather_gemm_kernel<128,64,64,3,2>",
     "gather_gemm_kernel<64,64,128,2,2>", "gather_gemm_kernel<128,64,128,2,1>", "gather_gemm_kernel<64,64,256,2,1>",
     "gather_gemm_kernel<128,128,64,2,2>", "gather_gemm_kernel<256,64,64,2,2>", "gather_gemm_kernel<256,128,64,2,1>",
-    "strip_gemm_kernel<256,4,1>", "strip_gemm_kernel<128,2,2>", "strip_gemm_kernel<64,2,2>",
+    "strip_gemm_kernel<256,4,1,2,1>", "strip_gemm_kernel<128,2,2,2,1>", "strip_gemm_kernel<64,2,2,2,1>",
+    "strip_gemm_kernel<256,4,1,1,2>", "strip_gemm_kernel<128,2,2,1,3>", "strip_gemm_kernel<64,2,2,1,3>",
     "gather_gemm_kernel<128,64,32,4,2> (stem)",
     "wgrad_kernel<128,128,4,64,false,32>", "wgrad_kernel<64,64,4,64,false,32>", "wgrad_kernel<64,128,4,64,false,32>",
     "wgrad_kernel<128,64,4,64,false,32>", "wgrad_kernel<64,64,3,64,false,64>", "wgrad_kernel<64,64,2,64,false,64>",
     "wgrad_kernel<64,64,2,64,false,128>", "wgrad_kernel<64,128,3,64,false,64>", "wgrad_kernel<128,64,3,64,false,64>",
-    "wgrad_kernel<128,128,2,64,false,64>", "wgrad_kernel<64,64,4,32,true,32> (stem)",
+    "wgrad_kernel<128,128,2,64,false,64>", "wgrad_strip_kernel", "wgrad_kernel<64,64,4,32,true,32> (stem)",
     "wgrad_reduce_kernel",
     "bn_stats_kernel", "bn_finalize_kernel<0,*> (forward statistics)", "bn_apply_kernel", "bn_fused_apply_kernel (finalize + apply)",
     "bn_bwd_reduce_kernel", "bn_finalize_kernel<1,*> (backward sums)", "bn_bwd_apply_kernel", "bn_bwd_fused_apply_kernel (finalize + apply)",

@@ -180,7 +180,7 @@ def test_step_two_blocks_per_stage_ragged_batch():
 
 
 def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, loss_scale=1024.0, classes=1000,
-                       autotune=False, lars=None, plan_check=False, mutate=None):
+                       autotune=False, lars=None, plan_check=False, mutate=None, tuning=None):
     """Every kernel launch inside one rn50_step call, checked where it ran: the oracle recomputes
     each layer's result from the GPU's OWN input tensors of that layer (read back from the workspace,
     keep_grads=1), so rounding differences cannot pile up over the depth of the network and the
@@ -196,7 +196,9 @@ def check_step_in_situ(batch, image_hw, has_stem, blocks, n_img=None, n_k=None, 
     cfg.keep_grads = 1
     lr, mu, wd_ = 0.1, 0.9, 1e-4
     hp = P.rn50_hparams(lr, mu, wd_, 1.0 / loss_scale, *(lars or (0.0, 0.0)))
-    ctx, out = run_gpu(cfg, w, x, lab, hp, autotune)
+    ctx, out = run_gpu(cfg, w, x, lab, hp, autotune, tuning)
+    if tuning is not None:
+        assert ctx.get_tuning() == list(tuning)
     tg = gpu_forward_tensors(ctx, net, x, batch)
     w64 = w.astype(f64)
     w16 = O.round_binary16(w64)
@@ -345,12 +347,19 @@ def test_step_resnet50_batch2_in_situ():
 
 
 def test_step_resnet50_batch32_in_situ_sampled():
-    """The benchmarked configuration (batch 32, 224x224, kernel variants autotuned as bench.py does; afterwards
-    the benchmark's buffer plan is required to reproduce the checked results bit for bit): every
+    """The benchmarked configuration (batch 32, 224x224, the shipped kernel-variant table that bench.py loads;
+    afterwards the benchmark's buffer plan is required to reproduce the checked results bit for bit): every
     BN / pooling / loss / FC result in full,
     convolution outputs and data gradients for 2 sampled images, filter gradients for 8 sampled output
     channels per layer (each computed by the oracle from the GPU's own layer inputs)."""
-    check_step_in_situ(32, (224, 224), True, (3, 4, 6, 3), n_img=2, n_k=8, autotune=True, plan_check=True)
+    table = P.shipped_tuning(32)
+    assert table is not None, "no variant table shipped for batch 32"
+    check_step_in_situ(32, (224, 224), True, (3, 4, 6, 3), n_img=2, n_k=8, tuning=table, plan_check=True)
+
+
+def test_step_resnet50_batch8_in_situ_autotuned():
+    """Full topology with the variants chosen by rn50_autotune (isolated timing), checked the same way."""
+    check_step_in_situ(8, (224, 224), True, (3, 4, 6, 3), n_img=1, n_k=2, autotune=True, plan_check=True)
 
 
 def test_step_small_in_situ_ragged():
