@@ -121,6 +121,41 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
     constexpr int EP = BN + 8;                   // row pitch of the staged tile in halfs
     constexpr int OCPR = BN / 8;                 // output chunks per row
     constexpr int ORPP = kThreads / OCPR;
+    constexpr int NR = BM / ORPP;                // rows per thread
+    constexpr int CH = NR < 2 ? NR : 2;          // rows whose extra operands are requested together
+    constexpr int NC = NR / CH;
+    static_assert(NR % CH == 0, "rows per thread must split into whole chunks");
+    const int oc = tid % OCPR, orl = tid / OCPR;
+    const bool bwd_stats = a.bn_x != nullptr;
+    const bool second = bwd_stats && a.bn_x2 != nullptr;
+    const bool masked = a.mask_y != nullptr;
+    // The extra operands of the data gradient's epilogue (ReLU mask source, BN inputs) are requested a chunk of rows
+    // ahead of their use -- the first chunk before the tile is staged -- so that a workgroup has one round trip to
+    // memory per chunk in flight instead of one per row.
+    size_t gidx[2][CH];
+    bool ok[2][CH];
+    h16x8 yv[2][CH], xv[2][CH], xw[2][CH];
+    auto request = [&](int c, int buf) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int n, oh, ow;
+            ok[buf][i] = row_pix(orl + (c * CH + i) * ORPP, n, oh, ow);
+            gidx[buf][i] = ok[buf][i] ? (((size_t)n * a.OH + oh) * a.OW + ow) * a.NO + nt * BN + oc * 8 : 0;
+        }
+        if (masked) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i) yv[buf][i] = *reinterpret_cast<const h16x8*>(a.mask_y + gidx[buf][i]);
+        }
+        if (bwd_stats) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i) xv[buf][i] = *reinterpret_cast<const h16x8*>(a.bn_x + gidx[buf][i]);
+        }
+        if (second) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i) xw[buf][i] = *reinterpret_cast<const h16x8*>(a.bn_x2 + gidx[buf][i]);
+        }
+    };
+    request(0, 0);
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -133,48 +168,37 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
                 *reinterpret_cast<h16x4*>(lds + (wm0 + tm * 32 + li) * EP + wn0 + tn * 32 + q * 8 + lg * 4) = v;
             }
     __syncthreads();
-    const int oc = tid % OCPR, orl = tid / OCPR;
-    float st[16], mu[8], is[8], st2[8], mu2[8], is2[8];
+    // Backward sums are taken as sum g and sum g*x over the tile; xhat = (x - mean) * invstd is linear in x, so the
+    // tile's sum g*xhat = invstd * (sum g*x - mean * sum g) is formed once per column below.
+    float st[16], st2[8];
 #pragma unroll
     for (int j = 0; j < 16; ++j) st[j] = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) st2[j] = 0.f;
-    const bool bwd_stats = a.bn_x != nullptr;
-    const bool second = bwd_stats && a.bn_x2 != nullptr;
-    if (bwd_stats) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { mu[j] = a.bn_mean[nt * BN + oc * 8 + j]; is[j] = a.bn_invstd[nt * BN + oc * 8 + j]; }
-    }
-    if (second) {
+    for (int c = 0; c < NC; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < NC) request(c + 1, buf ^ 1);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { mu2[j] = a.bn_mean2[nt * BN + oc * 8 + j]; is2[j] = a.bn_invstd2[nt * BN + oc * 8 + j]; }
-    }
-#pragma unroll
-    for (int i = 0; i < BM / ORPP; ++i) {
-        const int row = orl + i * ORPP;
-        int n, oh, ow;
-        if (row_pix(row, n, oh, ow)) {
-            const size_t opix = ((size_t)n * a.OH + oh) * a.OW + ow;
-            const size_t gidx = opix * a.NO + nt * BN + oc * 8;
+        for (int i = 0; i < CH; ++i) {
+            if (!ok[buf][i]) continue;           // a row past the end of the tensor (an invalid row's requests read element 0)
+            const int row = orl + (c * CH + i) * ORPP;
             h16x8 v = *reinterpret_cast<const h16x8*>(lds + row * EP + oc * 8);
-            if (a.mask_y) {
-                const h16x8 yv = *reinterpret_cast<const h16x8*>(a.mask_y + gidx);
+            if (masked) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = (float)yv[j] > 0.f ? v[j] : (h16)0.f;
+                for (int j = 0; j < 8; ++j) v[j] = (float)yv[buf][i][j] > 0.f ? v[j] : (h16)0.f;
             }
-            *reinterpret_cast<h16x8*>(a.out + gidx) = v;
+            *reinterpret_cast<h16x8*>(a.out + gidx[buf][i]) = v;
             if (bwd_stats) {
-                const h16x8 xv = *reinterpret_cast<const h16x8*>(a.bn_x + gidx);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const float g = (float)v[j];
                     st[j] += g;
-                    st[8 + j] += g * (((float)xv[j] - mu[j]) * is[j]);
+                    st[8 + j] += g * (float)xv[buf][i][j];
                 }
                 if (second) {
-                    const h16x8 xw = *reinterpret_cast<const h16x8*>(a.bn_x2 + gidx);
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) st2[j] += (float)v[j] * (((float)xw[j] - mu2[j]) * is2[j]);
+                    for (int j = 0; j < 8; ++j) st2[j] += (float)v[j] * (float)xw[buf][i][j];
                 }
             } else {
 #pragma unroll
@@ -192,10 +216,15 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
             red[(orl * 2 + 1) * BN + oc * 8 + j] = st[8 + j];
         }
         __syncthreads();
+        float sum_g = 0.f;                  // kept by the threads of the second half for the second BN
         if (tid < 2 * BN) {
             const int which = tid / BN, col = tid % BN;
             float sum = 0.f;
             for (int r = 0; r < ORPP; ++r) sum += red[(r * 2 + which) * BN + col];
+            if (bwd_stats) {
+                for (int r = 0; r < ORPP; ++r) sum_g += red[(r * 2) * BN + col];
+                if (which == 1) sum = a.bn_invstd[nt * BN + col] * (sum - a.bn_mean[nt * BN + col] * sum_g);
+            }
             a.stats_part[((size_t)tile_row * 2 + which) * a.NO + nt * BN + col] = sum;
             if (second && which == 0) a.stats_part2[((size_t)tile_row * 2) * a.NO + nt * BN + col] = sum;
         }
@@ -204,10 +233,12 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
 #pragma unroll
             for (int j = 0; j < 8; ++j) red[orl * BN + oc * 8 + j] = st2[j];
             __syncthreads();
-            if (tid < BN) {
+            if (tid >= BN && tid < 2 * BN) {
+                const int col = tid - BN;
                 float sum = 0.f;
-                for (int r = 0; r < ORPP; ++r) sum += red[r * BN + tid];
-                a.stats_part2[((size_t)tile_row * 2 + 1) * a.NO + nt * BN + tid] = sum;
+                for (int r = 0; r < ORPP; ++r) sum += red[r * BN + col];
+                a.stats_part2[((size_t)tile_row * 2 + 1) * a.NO + nt * BN + col] =
+                    a.bn_invstd2[nt * BN + col] * (sum - a.bn_mean2[nt * BN + col] * sum_g);
             }
         }
     }
