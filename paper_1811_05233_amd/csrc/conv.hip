@@ -108,54 +108,71 @@ __device__ __forceinline__ void gather_init_acc(const GatherArgs& a, f32x16 (&ac
     }
 }
 
+// The extra operands of the data gradient's epilogue for one chunk of a thread's rows: ReLU mask source and BN inputs.
+template <int CH>
+struct EpiOperands {
+    size_t gidx[CH];
+    bool ok[CH];
+    h16x8 yv[CH], xv[CH], xw[CH];
+};
+template <int BM, int BN>
+struct EpiShape {
+    static constexpr int OCPR = BN / 8;                 // output chunks per row
+    static constexpr int ORPP = kThreads / OCPR;        // rows covered by one pass of the workgroup
+    static constexpr int NR = BM / ORPP;                // rows per thread
+    static constexpr int CH = NR < 2 ? NR : 2;          // rows whose extra operands are requested together
+    static constexpr int NC = NR / CH;
+    static_assert(NR % CH == 0, "rows per thread must split into whole chunks");
+};
+// Requests chunk c of this thread's rows.  A row past the end of the tensor reads element 0 (never used).
+template <int BM, int BN, class RowPix>
+__device__ __forceinline__ void gather_epi_request(const GatherArgs& a, EpiOperands<EpiShape<BM, BN>::CH>& o, int c, int tid,
+                                                   int nt, RowPix row_pix)
+{
+    using S = EpiShape<BM, BN>;
+    const int oc = tid % S::OCPR, orl = tid / S::OCPR;
+#pragma unroll
+    for (int i = 0; i < S::CH; ++i) {
+        int n, oh, ow;
+        o.ok[i] = row_pix(orl + (c * S::CH + i) * S::ORPP, n, oh, ow);
+        o.gidx[i] = o.ok[i] ? (((size_t)n * a.OH + oh) * a.OW + ow) * a.NO + nt * BN + oc * 8 : 0;
+    }
+    if (a.mask_y) {
+#pragma unroll
+        for (int i = 0; i < S::CH; ++i) o.yv[i] = *reinterpret_cast<const h16x8*>(a.mask_y + o.gidx[i]);
+    }
+    if (a.bn_x) {
+#pragma unroll
+        for (int i = 0; i < S::CH; ++i) o.xv[i] = *reinterpret_cast<const h16x8*>(a.bn_x + o.gidx[i]);
+        if (a.bn_x2) {
+#pragma unroll
+            for (int i = 0; i < S::CH; ++i) o.xw[i] = *reinterpret_cast<const h16x8*>(a.bn_x2 + o.gidx[i]);
+        }
+    }
+}
+
 // Epilogue: FP32 -> half, through LDS so that global stores are full 16-byte rows, plus the optional per-channel
 // sums over the tile's rows.  Forward: sum and sum of squares of the stored halves (BN statistics of the layer that
 // follows).  Data gradient with bn_x set: the stored gradient g is first masked by the ReLU of the tensor it belongs
 // to (mask_y), then sum g and sum g*xhat are formed for the backward pass of the BN that produced that tensor.
 // The caller has made sure that no wave still reads the part of LDS used here.  tile_row: index of the row tile
 // (first index of the partial sums).
+// first: the operands of the thread's first chunk of rows, requested by the caller at the start of the kernel (they
+// arrive with the first K-slab); later chunks are requested here, one chunk ahead of their use.
 template <int BM, int BN, int TM, int TN, int LDS_HALFS, class RowPix>
 __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f32x16 (&acc)[TM][TN], int wm0, int wn0, int li,
-                                                int lg, int tid, int nt, int tile_row, RowPix row_pix)
+                                                int lg, int tid, int nt, int tile_row, RowPix row_pix,
+                                                EpiOperands<EpiShape<BM, BN>::CH>& first)
 {
+    using S = EpiShape<BM, BN>;
     constexpr int EP = BN + 8;                   // row pitch of the staged tile in halfs
-    constexpr int OCPR = BN / 8;                 // output chunks per row
-    constexpr int ORPP = kThreads / OCPR;
-    constexpr int NR = BM / ORPP;                // rows per thread
-    constexpr int CH = NR < 2 ? NR : 2;          // rows whose extra operands are requested together
-    constexpr int NC = NR / CH;
-    static_assert(NR % CH == 0, "rows per thread must split into whole chunks");
-    const int oc = tid % OCPR, orl = tid / OCPR;
+    constexpr int ORPP = S::ORPP, CH = S::CH, NC = S::NC;
+    const int oc = tid % S::OCPR, orl = tid / S::OCPR;
     const bool bwd_stats = a.bn_x != nullptr;
     const bool second = bwd_stats && a.bn_x2 != nullptr;
     const bool masked = a.mask_y != nullptr;
-    // The extra operands of the data gradient's epilogue (ReLU mask source, BN inputs) are requested a chunk of rows
-    // ahead of their use -- the first chunk before the tile is staged -- so that a workgroup has one round trip to
-    // memory per chunk in flight instead of one per row.
-    size_t gidx[2][CH];
-    bool ok[2][CH];
-    h16x8 yv[2][CH], xv[2][CH], xw[2][CH];
-    auto request = [&](int c, int buf) {
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            int n, oh, ow;
-            ok[buf][i] = row_pix(orl + (c * CH + i) * ORPP, n, oh, ow);
-            gidx[buf][i] = ok[buf][i] ? (((size_t)n * a.OH + oh) * a.OW + ow) * a.NO + nt * BN + oc * 8 : 0;
-        }
-        if (masked) {
-#pragma unroll
-            for (int i = 0; i < CH; ++i) yv[buf][i] = *reinterpret_cast<const h16x8*>(a.mask_y + gidx[buf][i]);
-        }
-        if (bwd_stats) {
-#pragma unroll
-            for (int i = 0; i < CH; ++i) xv[buf][i] = *reinterpret_cast<const h16x8*>(a.bn_x + gidx[buf][i]);
-        }
-        if (second) {
-#pragma unroll
-            for (int i = 0; i < CH; ++i) xw[buf][i] = *reinterpret_cast<const h16x8*>(a.bn_x2 + gidx[buf][i]);
-        }
-    };
-    request(0, 0);
+    EpiOperands<CH> other;
+    if (NC > 1) gather_epi_request<BM, BN>(a, other, 1, tid, nt, row_pix);
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -177,34 +194,34 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
     for (int j = 0; j < 8; ++j) st2[j] = 0.f;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        const int buf = c & 1;
-        if (c + 1 < NC) request(c + 1, buf ^ 1);
+        EpiOperands<CH>& cur = (c & 1) ? other : first;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            if (!ok[buf][i]) continue;           // a row past the end of the tensor (an invalid row's requests read element 0)
+            if (!cur.ok[i]) continue;            // a row past the end of the tensor
             const int row = orl + (c * CH + i) * ORPP;
             h16x8 v = *reinterpret_cast<const h16x8*>(lds + row * EP + oc * 8);
             if (masked) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = (float)yv[buf][i][j] > 0.f ? v[j] : (h16)0.f;
+                for (int j = 0; j < 8; ++j) v[j] = (float)cur.yv[i][j] > 0.f ? v[j] : (h16)0.f;
             }
-            *reinterpret_cast<h16x8*>(a.out + gidx[buf][i]) = v;
+            *reinterpret_cast<h16x8*>(a.out + cur.gidx[i]) = v;
             if (bwd_stats) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const float g = (float)v[j];
                     st[j] += g;
-                    st[8 + j] += g * (float)xv[buf][i][j];
+                    st[8 + j] += g * (float)cur.xv[i][j];
                 }
                 if (second) {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) st2[j] += (float)v[j] * (float)xw[buf][i][j];
+                    for (int j = 0; j < 8; ++j) st2[j] += (float)v[j] * (float)cur.xw[i][j];
                 }
             } else {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) { const float f = (float)v[j]; st[j] += f; st[8 + j] += f * f; }
             }
         }
+        if (c + 2 < NC) gather_epi_request<BM, BN>(a, cur, c + 2, tid, nt, row_pix);     // two chunks stay in flight
     }
     if (a.stats_part) {
         // per-channel sums of this row tile, added in a fixed order: [tile][first | second sum][channel]
@@ -373,6 +390,11 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     };
     f32x16 acc[TM][TN];
     gather_init_acc<BN>(a, acc, wm0, wn0, li, lg, nt, row_pix);
+    // The epilogue's extra operands for the thread's first rows are requested here, so that they arrive together
+    // with the first K-slab -- except in the variant whose five workgroups per compute unit leave no registers for it.
+    constexpr bool kEarlyEpi = !(BM == 64 && BN == 64 && BK == 64 && OCC == 4);
+    EpiOperands<EpiShape<BM, BN>::CH> epi_first;
+    if (kEarlyEpi) gather_epi_request<BM, BN>(a, epi_first, 0, tid, nt, row_pix);
 
     int cur = 0;
     for (int kit = 0; kit < kiters; ++kit) {
@@ -420,10 +442,11 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
         }
         if (++cur == NST) cur = 0;
     }
+    if (!kEarlyEpi) gather_epi_request<BM, BN>(a, epi_first, 0, tid, nt, row_pix);
     RN50_WAIT_LGKMCNT0();
     __builtin_amdgcn_s_barrier();             // all waves are done reading the ring before it is reused
 
-    gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, tile_row, row_pix);
+    gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, tile_row, row_pix, epi_first);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -543,6 +566,7 @@ __global__ __launch_bounds__(kThreads, OCC) void strip_gemm_kernel(const GatherA
 
     f32x16 acc[TM][TN];
     gather_init_acc<BN>(a, acc, wm0, wn0, li, lg, nt, row_pix);
+    EpiOperands<EpiShape<BM, BN>::CH> epi_first;
 
     int cur = 0;
     for (int kit = 0; kit < KC; ++kit) {
@@ -594,10 +618,11 @@ __global__ __launch_bounds__(kThreads, OCC) void strip_gemm_kernel(const GatherA
             issue_slab();
         }
     }
+    gather_epi_request<BM, BN>(a, epi_first, 0, tid, nt, row_pix);     // in flight while the tile is staged
     RN50_WAIT_LGKMCNT0();
     __builtin_amdgcn_s_barrier();
 
-    gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, mt, row_pix);
+    gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, mt, row_pix, epi_first);
 }
 
 // ------------------------------------------------------------------------------------------------
