@@ -54,41 +54,46 @@ __global__ __launch_bounds__(kThreads) void maxpool_fwd_kernel(int N, int H, int
 }
 
 // dx[n,h,w,c] = sum of dy over the (at most 4) windows whose recorded first maximum is (h,w).
-__global__ __launch_bounds__(kThreads) void maxpool_bwd_kernel(int N, int H, int W, int C, int P, int Q,
+// One workgroup row (blockIdx.x) per image row; all four candidate windows are requested at once (an even
+// coordinate has one candidate per axis: the second request then repeats the first and is ignored).
+__global__ __launch_bounds__(kThreads) void maxpool_bwd_kernel(int H, int W, int C, int P, int Q,
                                                                const h16* __restrict__ dy,
                                                                const uint8_t* __restrict__ arg, h16* __restrict__ dx)
 {
     const int G = C / 8;
-    const size_t total = (size_t)N * H * W * G;
-    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (size_t)gridDim.x * kThreads) {
-        const int g = (int)(i % G);
-        size_t t = i / G;
-        const int w = (int)(t % W); t /= W;
-        const int h = (int)(t % H);
-        const int n = (int)(t / H);
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int p = h / 2; p <= (h + 1) / 2; ++p) {        // windows with 2p-1 <= h <= 2p+1
-            if (p >= P) continue;
-            const int r = h - (2 * p - 1);
-            for (int q = w / 2; q <= (w + 1) / 2; ++q) {
-                if (q >= Q) continue;
-                const int s = w - (2 * q - 1);
-                const size_t o = (((size_t)n * P + p) * Q + q) * C + g * 8;
-                const uint2 packed = *reinterpret_cast<const uint2*>(arg + o);
-                const h16x8 d = *reinterpret_cast<const h16x8*>(dy + o);
-                const uint32_t me = (uint32_t)(r * 3 + s);
+    const int idx = blockIdx.y * kThreads + threadIdx.x;
+    if (idx >= W * G) return;
+    const int w = idx / G, g = idx - w * G;
+    const int n = blockIdx.x / H, h = blockIdx.x - n * H;
+    // windows p with 2p-1 <= h <= 2p+1: h/2 and, for odd h, (h+1)/2
+    const int p0 = h >> 1, p1 = (h + 1) >> 1, q0 = w >> 1, q1 = (w + 1) >> 1;
+    const bool vp[2] = {p0 < P, p1 != p0 && p1 < P};
+    const bool vq[2] = {q0 < Q, q1 != q0 && q1 < Q};
+    const int pp[2] = {vp[0] ? p0 : 0, vp[1] ? p1 : 0}, qq[2] = {vq[0] ? q0 : 0, vq[1] ? q1 : 0};
+    uint2 packed[4];
+    h16x8 d[4];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t a = ((j < 4 ? packed.x : packed.y) >> ((j & 3) * 8)) & 0xffu;
-                    if (a == me) acc[j] += (float)d[j];
-                }
-            }
-        }
-        h16x8 o;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = (h16)acc[j];
-        *reinterpret_cast<h16x8*>(dx + i * 8) = o;
+    for (int k = 0; k < 4; ++k) {
+        const size_t o = (((size_t)n * P + pp[k >> 1]) * Q + qq[k & 1]) * C + g * 8;
+        packed[k] = *reinterpret_cast<const uint2*>(arg + o);
+        d[k] = *reinterpret_cast<const h16x8*>(dy + o);
     }
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {                           // same order as the window loops: p outer, q inner
+        if (!(vp[k >> 1] && vq[k & 1])) continue;
+        const int r = h - (2 * pp[k >> 1] - 1), sx = w - (2 * qq[k & 1] - 1);
+        const uint32_t me = (uint32_t)(r * 3 + sx);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t a = ((j < 4 ? packed[k].x : packed[k].y) >> ((j & 3) * 8)) & 0xffu;
+            if (a == me) acc[j] += (float)d[k][j];
+        }
+    }
+    h16x8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (h16)acc[j];
+    *reinterpret_cast<h16x8*>(dx + (((size_t)n * H + h) * W + w) * C + g * 8) = o;
 }
 
 __global__ __launch_bounds__(kThreads) void avgpool_fwd_kernel(int N, int HW, int C, const h16* __restrict__ x,
@@ -256,7 +261,8 @@ int rn50_maxpool_bwd(int N, int H, int W, int C, const h16* dy, const uint8_t* a
 {
     const int P = (H + 2 - 3) / 2 + 1, Q = (W + 2 - 3) / 2 + 1;
     ProfScope ps(RN50_K_POOL, 0.0, 2.0 * N * C * ((double)H * W + 1.5 * P * Q), s);
-    maxpool_bwd_kernel<<<grid_for((size_t)N * H * W * (C / 8)), kThreads, 0, s>>>(N, H, W, C, P, Q, dy, arg, dx);
+    const dim3 grid((unsigned)(N * H), (unsigned)rn50_cdiv((long long)W * (C / 8), kThreads));
+    maxpool_bwd_kernel<<<grid, kThreads, 0, s>>>(H, W, C, P, Q, dy, arg, dx);
     return rn50_check_launch();
 }
 
