@@ -159,7 +159,9 @@ __device__ __forceinline__ void gather_epi_request(const GatherArgs& a, EpiOpera
 // (first index of the partial sums).
 // first: the operands of the thread's first chunk of rows, requested by the caller at the start of the kernel (they
 // arrive with the first K-slab); later chunks are requested here, one chunk ahead of their use.
-template <int BM, int BN, int TM, int TN, int LDS_HALFS, class RowPix>
+// kAlias: the statistics scratch takes the place of the staged tile (one more barrier, less LDS) instead of lying
+// behind it.
+template <int BM, int BN, int TM, int TN, int LDS_HALFS, bool kAlias, class RowPix>
 __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f32x16 (&acc)[TM][TN], int wm0, int wn0, int li,
                                                 int lg, int tid, int nt, int tile_row, RowPix row_pix,
                                                 EpiOperands<EpiShape<BM, BN>::CH>& first)
@@ -224,9 +226,12 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
         if (c + 2 < NC) gather_epi_request<BM, BN>(a, cur, c + 2, tid, nt, row_pix);     // two chunks stay in flight
     }
     if (a.stats_part) {
-        // per-channel sums of this row tile, added in a fixed order: [tile][first | second sum][channel]
-        float* red = reinterpret_cast<float*>(lds + BM * EP);          // ORPP x 2 x BN floats behind the staged tile
-        static_assert(BM * EP * 2 + ORPP * 2 * BN * 4 <= LDS_HALFS * 2, "statistics scratch must fit in LDS");
+        // per-channel sums of this row tile, added in a fixed order: [tile][first | second sum][channel].  The
+        // scratch (ORPP x 2 x BN floats) lies behind the staged tile, or takes its place once every thread has
+        // read its rows.
+        float* red = reinterpret_cast<float*>(kAlias ? lds : lds + BM * EP);
+        static_assert((kAlias ? 0 : BM * EP * 2) + ORPP * 2 * BN * 4 <= LDS_HALFS * 2, "statistics scratch must fit in LDS");
+        if (kAlias) __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             red[(orl * 2 + 0) * BN + oc * 8 + j] = st[j];
@@ -277,7 +282,9 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     constexpr int KS = BK / 16;
     constexpr int STAGE = (BM + BN) * BK;
     constexpr int EP = BN + 8;             // epilogue row pitch in halfs (see gather_epilogue)
-    constexpr int EPI_HALFS = BM * EP + (kThreads / (BN / 8)) * 2 * BN * 2;   // staged tile + statistics scratch (floats)
+    constexpr int EPI_STATS = (kThreads / (BN / 8)) * 2 * BN * 2;            // statistics scratch (floats) in halfs
+    constexpr bool kAliasStats = BN == 128 && OCC == 4;                      // the variant that needs 4 x its LDS per unit
+    constexpr int EPI_HALFS = kAliasStats ? (BM * EP > EPI_STATS ? BM * EP : EPI_STATS) : BM * EP + EPI_STATS;
     constexpr int LDS_HALFS = (NST * STAGE > EPI_HALFS) ? NST * STAGE : EPI_HALFS;
     constexpr unsigned kOutOfRange = 0x80000000u;
     __shared__ __attribute__((aligned(16))) h16 lds[LDS_HALFS];
@@ -391,8 +398,8 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     f32x16 acc[TM][TN];
     gather_init_acc<BN>(a, acc, wm0, wn0, li, lg, nt, row_pix);
     // The epilogue's extra operands for the thread's first rows are requested here, so that they arrive together
-    // with the first K-slab -- except in the variant whose five workgroups per compute unit leave no registers for it.
-    constexpr bool kEarlyEpi = !(BM == 64 && BN == 64 && BK == 64 && OCC == 4);
+    // with the first K-slab -- except in the variants whose occupancy leaves no registers for it.
+    constexpr bool kEarlyEpi = !(BM == 64 && BN == 64 && BK == 64 && OCC == 4) && !(BN == 128 && OCC == 4);
     EpiOperands<EpiShape<BM, BN>::CH> epi_first;
     if (kEarlyEpi) gather_epi_request<BM, BN>(a, epi_first, 0, tid, nt, row_pix);
 
@@ -446,7 +453,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gather_gemm_kernel(const Gather
     RN50_WAIT_LGKMCNT0();
     __builtin_amdgcn_s_barrier();             // all waves are done reading the ring before it is reused
 
-    gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, tile_row, row_pix, epi_first);
+    gather_epilogue<BM, BN, TM, TN, LDS_HALFS, kAliasStats>(a, lds, acc, wm0, wn0, li, lg, tid, nt, tile_row, row_pix, epi_first);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -622,7 +629,7 @@ __global__ __launch_bounds__(kThreads, OCC) void strip_gemm_kernel(const GatherA
     RN50_WAIT_LGKMCNT0();
     __builtin_amdgcn_s_barrier();
 
-    gather_epilogue<BM, BN, TM, TN, LDS_HALFS>(a, lds, acc, wm0, wn0, li, lg, tid, nt, mt, row_pix, epi_first);
+    gather_epilogue<BM, BN, TM, TN, LDS_HALFS, false>(a, lds, acc, wm0, wn0, li, lg, tid, nt, mt, row_pix, epi_first);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1127,7 +1134,7 @@ bool gather_tile_ok(const GatherArgs& a, int tile)
     if (tile == RN50_TILE_256x64_K64) return a.CR % 64 == 0;
     if (tile == RN50_TILE_64x64_K128 || tile == RN50_TILE_128x64_K128) return a.CR % 128 == 0;
     if (tile == RN50_TILE_64x64_K256) return a.CR % 256 == 0;
-    return (tile != RN50_TILE_128x128 && tile != RN50_TILE_128x128_SHORT) || a.NO % 128 == 0;
+    return (tile != RN50_TILE_128x128 && tile != RN50_TILE_128x128_SHORT && tile != RN50_TILE_128x128_OCC4) || a.NO % 128 == 0;
 }
 
 // default choice when no tuned tile is given (what the autotuner picks most often for such shapes): the large
@@ -1179,6 +1186,7 @@ int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, in
         case RN50_TILE_STRIP_256_S1: return launch_strip<256, 4, 1, 1, 2>(a, s, kid, flops, bytes);
         case RN50_TILE_STRIP_128_S1: return launch_strip<128, 2, 2, 1, 3>(a, s, kid, flops, bytes);
         case RN50_TILE_STRIP_64_S1: return launch_strip<64, 2, 2, 1, 3>(a, s, kid, flops, bytes);
+        case RN50_TILE_128x128_OCC4: return launch_gather<128, 128, 32, 2, 4>(a, s, kid, flops, bytes);
         default: tile = RN50_TILE_64x64_K32; return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_TILE0 + tile, flops, bytes);
     }
 }

@@ -27,6 +27,7 @@ enum {
     RN50_TILE_STRIP_256_S1,    //   single-stage forms of the three (smaller LDS footprint: 2-3 workgroups per compute unit
     RN50_TILE_STRIP_128_S1,    //   overlap each other's loads and MFMAs instead of a two-stage ring inside one)
     RN50_TILE_STRIP_64_S1,
+    RN50_TILE_128x128_OCC4,    // 128x128, 32-wide slabs, 2 stages, 4 workgroups per compute unit (784 tiles fit one round of 1024)
     RN50_NUM_GATHER_TILES,
     RN50_TILE_STRICT = 0x1000,  // flag on a tile id: fail with RN50_ERR_SHAPE instead of falling back when it does not apply
     RN50_WGRAD_TILE_STRIP = 10, // filter-gradient tile index of the 3x3 strip kernel (the ten before it: kWgradTiles)

@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--min-gain-us", type=float, default=2.5, help="a trial must beat the incumbent by this much to be re-measured")
     ap.add_argument("--passes", type=int, default=1)
     ap.add_argument("--roles", default="0,1,2", help="which entries to search: 0 forward, 1 data gradient, 2 filter gradient")
+    ap.add_argument("--candidates", default="", help="comma-separated variant ids to try instead of all of them "
+                                                     "(a quick pass after adding a variant)")
     args = ap.parse_args()
 
     import torch
@@ -85,8 +87,9 @@ def main():
                 incumbent = table[idx]
                 cur = measure(table, args.steps)              # re-measured per entry: the clock drifts a little
                 tried = []
-                for cand in [-1] + list(range(counts[role])):
-                    if cand == incumbent:
+                cands = [int(v) for v in args.candidates.split(",")] if args.candidates else [-1] + list(range(counts[role]))
+                for cand in cands:
+                    if cand == incumbent or cand >= counts[role]:
                         continue
                     trial = list(table)
                     trial[idx] = cand
