@@ -301,7 +301,11 @@ int rn50_autotune(rn50_ctx* ctx, const void* images, const int32_t* labels, floa
  * gradient; -1 = shape heuristic), so that a tuning can be stored and a later context (another process, a
  * profiler run) executes exactly the same kernels.  rn50_get_tuning(ctx, NULL, 0) returns the table length; with
  * a table it fills it and returns the length (RN50_ERR_SHAPE if capacity is too small).  rn50_set_tuning checks
- * the length and every entry's range.  rn50_tuning_report copies the text of what the last rn50_autotune measured
+ * the length and every entry's range.  An entry whose variant does not apply to its convolution's shape is not an
+ * error: the library runs the shape heuristic (forward, data gradient) or a fallback tile with the same pixel split
+ * (filter gradient) instead, and rn50_get_tuning reports what actually runs (the filter-gradient entries at once,
+ * the others after the first rn50_step).  paper_1811_05233_amd/tune_in_situ.py searches the table by the measured
+ * time of the whole step; the table it found for full ResNet-50 at batch 32 ships beside it.  rn50_tuning_report copies the text of what the last rn50_autotune measured
  * (one line per launch site and candidate, microseconds) into buf (host, at most cap-1 characters, NUL-terminated)
  * and returns its full length. */
 int rn50_get_tuning(rn50_ctx* ctx, int* table /* host */, int capacity);

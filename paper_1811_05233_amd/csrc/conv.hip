@@ -230,21 +230,22 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
         // scratch (ORPP x 2 x BN floats) lies behind the staged tile, or takes its place once every thread has
         // read its rows.
         float* red = reinterpret_cast<float*>(kAlias ? lds : lds + BM * EP);
-        static_assert((kAlias ? 0 : BM * EP * 2) + ORPP * 2 * BN * 4 <= LDS_HALFS * 2, "statistics scratch must fit in LDS");
+        constexpr int RP = 2 * BN;          // (an odd pitch would spread the scalar writes over the banks; measured slower)
+        static_assert((kAlias ? 0 : BM * EP * 2) + ORPP * RP * 4 <= LDS_HALFS * 2, "statistics scratch must fit in LDS");
         if (kAlias) __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            red[(orl * 2 + 0) * BN + oc * 8 + j] = st[j];
-            red[(orl * 2 + 1) * BN + oc * 8 + j] = st[8 + j];
+            red[orl * RP + oc * 8 + j] = st[j];
+            red[orl * RP + BN + oc * 8 + j] = st[8 + j];
         }
         __syncthreads();
         float sum_g = 0.f;                  // kept by the threads of the second half for the second BN
         if (tid < 2 * BN) {
             const int which = tid / BN, col = tid % BN;
             float sum = 0.f;
-            for (int r = 0; r < ORPP; ++r) sum += red[(r * 2 + which) * BN + col];
+            for (int r = 0; r < ORPP; ++r) sum += red[r * RP + which * BN + col];
             if (bwd_stats) {
-                for (int r = 0; r < ORPP; ++r) sum_g += red[(r * 2) * BN + col];
+                for (int r = 0; r < ORPP; ++r) sum_g += red[r * RP + col];
                 if (which == 1) sum = a.bn_invstd[nt * BN + col] * (sum - a.bn_mean[nt * BN + col] * sum_g);
             }
             a.stats_part[((size_t)tile_row * 2 + which) * a.NO + nt * BN + col] = sum;
@@ -253,12 +254,12 @@ __device__ __forceinline__ void gather_epilogue(const GatherArgs& a, h16* lds, f
         if (second) {                       // the second BN's sum g*xhat2, through the same scratch
             __syncthreads();
 #pragma unroll
-            for (int j = 0; j < 8; ++j) red[orl * BN + oc * 8 + j] = st2[j];
+            for (int j = 0; j < 8; ++j) red[orl * RP + oc * 8 + j] = st2[j];
             __syncthreads();
             if (tid >= BN && tid < 2 * BN) {
                 const int col = tid - BN;
                 float sum = 0.f;
-                for (int r = 0; r < ORPP; ++r) sum += red[r * BN + col];
+                for (int r = 0; r < ORPP; ++r) sum += red[r * RP + col];
                 a.stats_part2[((size_t)tile_row * 2 + 1) * a.NO + nt * BN + col] =
                     a.bn_invstd2[nt * BN + col] * (sum - a.bn_mean2[nt * BN + col] * sum_g);
             }
@@ -1477,6 +1478,14 @@ size_t rn50_wgrad_partial_floats(const conv_desc& d)
         if (f > most) most = f;
     }
     return most;
+}
+
+// A filter-gradient variant whose tile does not apply to the shape runs a fallback tile with the same split target;
+// this returns the id of what actually runs (so that a stored table names it).
+int rn50_wgrad_canonical_variant(const conv_desc& d, int variant)
+{
+    if (variant < 0 || rn50_conv_is_stem(d)) return variant;
+    return wgrad_plan(d, variant).tile * 3 + variant % 3;
 }
 
 // bytes of partial tiles that variant `variant` writes (and the sum kernel reads back)

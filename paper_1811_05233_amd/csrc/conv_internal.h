@@ -126,6 +126,7 @@ size_t rn50_dgrad_stats_floats(const conv_desc& d);
 size_t rn50_wgrad_acc_floats(const conv_desc& d);
 size_t rn50_wgrad_partial_floats(const conv_desc& d);
 size_t rn50_wgrad_variant_partial_bytes(const conv_desc& d, int variant);
+int rn50_wgrad_canonical_variant(const conv_desc& d, int variant);
 // sum of the per-split partial tiles -> out16 (half) or out32 (FP32); exactly one of the two is given
 int rn50_conv_wgrad_launch(const conv_desc& d, const h16* x, const h16* dy, h16* out16, float* out32, float* partials,
                            hipStream_t s, int variant);

@@ -456,7 +456,15 @@ template <class F, class G = float (*)(int)>
 int launch_or_tune(rn50_ctx& c, hipStream_t s, int ncand, int* choice, F launch, const char* what = "", const char* layer = "",
                    G penalty_ms = no_penalty, int cand_flag = 0)
 {
-    if (!c.tuning) return launch(*choice);
+    if (!c.tuning) {
+        if (*choice >= 0 && cand_flag) {
+            // a table entry that does not apply to this shape is replaced by the heuristic, visibly (rn50_get_tuning)
+            const int rc = launch(*choice | cand_flag);
+            if (rc != RN50_ERR_SHAPE) return rc;
+            *choice = RN50_TILE_AUTO;
+        }
+        return launch(*choice);
+    }
     char line[160];
     float best_ms = 1e30f;
     int best = RN50_TILE_AUTO;
@@ -725,7 +733,8 @@ extern "C" int rn50_get_tuning(rn50_ctx* ctx, int* table, int capacity)
     if (capacity < n) return RN50_ERR_SHAPE;
     for (size_t i = 0; i < ctx->L.layers.size(); ++i) {
         const ConvLayer& l = ctx->L.layers[i];
-        table[3 * i] = l.fwd_tile; table[3 * i + 1] = l.dgrad_tile; table[3 * i + 2] = l.wgrad_variant;
+        table[3 * i] = l.fwd_tile; table[3 * i + 1] = l.dgrad_tile;
+        table[3 * i + 2] = rn50_wgrad_canonical_variant(l.d, l.wgrad_variant);      // an autotuned pick may be an alias
     }
     return n;
 }
@@ -740,7 +749,8 @@ extern "C" int rn50_set_tuning(rn50_ctx* ctx, const int* table, int n)
     }
     for (size_t i = 0; i < ctx->L.layers.size(); ++i) {
         ConvLayer& l = ctx->L.layers[i];
-        l.fwd_tile = table[3 * i]; l.dgrad_tile = table[3 * i + 1]; l.wgrad_variant = table[3 * i + 2];
+        l.fwd_tile = table[3 * i]; l.dgrad_tile = table[3 * i + 1];
+        l.wgrad_variant = rn50_wgrad_canonical_variant(l.d, table[3 * i + 2]);     // the variant that will actually run
     }
     return RN50_OK;
 }

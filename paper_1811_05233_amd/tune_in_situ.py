@@ -111,6 +111,7 @@ def main():
         if not changed:
             break
     final = measure(table, 4 * args.confirm_steps)
+    table = ctx.get_tuning()        # as the library runs it: ids that do not apply to a shape read -1 / the fallback's id
     print("final: %.1f us per step" % final, flush=True)
     json.dump({"batch": B, "table": table, "us_per_step_when_tuned": round(final, 1)}, open(args.out, "w"))
     ctx.close()
