@@ -259,6 +259,68 @@ def tail(args):
                      "eta": 0.01, "eps": 1e-6}}
 
 
+def probes(args):
+    """Machine figures that the kernel design is argued from, measured with the library's probe kernels and torch events:
+    register-only MFMA rate, tile loads out of L2 / the Infinity Cache / HBM (LDS-DMA and vector loads), a streaming
+    copy, the cost of a dependent empty kernel, and one large plain GEMM through the convolution kernels."""
+    import torch
+    import paper_1811_05233_amd as P
+    dev = "cuda:0"
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps          # seconds per call
+
+    out = torch.zeros(4096 * 256, dtype=torch.float32, device=dev)
+    res = {"mfma_register_only_tflops": {}, "tile_load_tbs": {}}
+    for blocks in (256, 1024, 2048):
+        iters = 20000
+        t = timed(lambda: P.probe_mfma(blocks, iters, out), 3)
+        res["mfma_register_only_tflops"]["%d workgroups" % blocks] = round(blocks * 4 * iters * 4 * 32768.0 / t / 1e12, 1)
+    src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+    # (name, working set, workgroups, tiles per workgroup, start stride in tiles): a 2 MiB set stays in every XCD's
+    # 4 MB L2 (starts spread so that workgroups sharing a compute unit are not on the same tile); 64 MiB exceeds the
+    # L2s and stays in the 256 MB Infinity Cache; the last case reads each tile of 1 GiB exactly once.
+    cases = (("2 MiB working set (L2)", 2 << 20, 2048, 512, 37), ("64 MiB working set (Infinity Cache)", 64 << 20, 2048, 512, 1031),
+             ("1 GiB read once (HBM)", 1 << 30, 2048, 32, 32))
+    for name, nbytes, blocks, iters, stride in cases:
+        for lds in (1, 0):
+            t = timed(lambda: P.probe_tile_load(src, nbytes, blocks, iters, stride, lds, out), 3)
+            res["tile_load_tbs"][name + (", global->LDS" if lds else ", vector loads")] = round(blocks * iters * 16384.0 / t / 1e12, 2)
+    t = timed(lambda: P.probe_tile_load(src, 2 << 20, 1, 4096, 0, 1, out), 3)
+    res["tile_load_one_workgroup_gbs"] = round(4096 * 16384.0 / t / 1e9, 1)
+    t = timed(lambda: P.probe_tile_load(src, 2 << 20, 256, 2048, 37, 1, out), 3)
+    res["tile_load_one_workgroup_per_cu_tbs"] = round(256 * 2048 * 16384.0 / t / 1e12, 2)
+    dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    t = timed(lambda: P.probe_copy(src, dst, 1 << 30), 5)
+    res["stream_copy_tbs_read_plus_write"] = round(2.0 * (1 << 30) / t / 1e12, 2)
+    del dst
+    res["dependent_empty_kernel_us"] = round(timed(lambda: P.probe_empty(2000), 3) / 2000 * 1e6, 2)
+    del src
+    # one large plain GEMM (1x1 convolution, 100352 x 1024 x 1024) through every forward variant that applies
+    d = P.make_conv_desc(32, 56, 56, 1024, 1024, 1, 1, 1, 0)
+    x = torch.randn(32 * 56 * 56 * 1024, device=dev).to(torch.float16)
+    w = (torch.randn(1024 * 1024, device=dev) * 0.03).to(torch.float16)
+    y = torch.empty(32 * 56 * 56 * 1024, dtype=torch.float16, device=dev)
+    gemm = {}
+    for v in range(P.conv_variant_count(P.CONV_FWD)):
+        if not P.conv_variant_applies(d, P.CONV_FWD, v):
+            continue
+        t = timed(lambda: P.conv_fwd(d, x, w, y, variant=v), 5)
+        gemm["variant %d" % v] = round(2.0 * 100352 * 1024 * 1024 / t / 1e12, 1)
+    best = max(gemm, key=gemm.get)
+    res["gemm_100352x1024x1024_tflops"] = {"best": gemm[best], "best_variant": best, "frac_of_peak": round(gemm[best] / PEAK_FP16_TFLOPS, 3),
+                                           "all": gemm}
+    return {"metric": "hardware probes (MI355X)", "data": "synthetic", "n_gpus": 1, "probes": res}
+
+
 def extras(args):
     """The other workloads of the configuration list in short form, outside the timed region of the step: the
     update tail (100 steps), the convolution sweep (warm and cold operands: totals and the three shapes furthest
@@ -286,7 +348,7 @@ def extras(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--mode", choices=["step", "conv-sweep", "batch-sweep", "tail"], default="step")
+    ap.add_argument("--mode", choices=["step", "conv-sweep", "batch-sweep", "tail", "probes"], default="step")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
@@ -317,7 +379,7 @@ def main():
         sys.exit(2)
 
     if args.mode != "step":
-        print(json.dumps({"conv-sweep": conv_sweep, "batch-sweep": batch_sweep, "tail": tail}[args.mode](args)))
+        print(json.dumps({"conv-sweep": conv_sweep, "batch-sweep": batch_sweep, "tail": tail, "probes": probes}[args.mode](args)))
         return
 
     import numpy as np

@@ -71,6 +71,9 @@ enum { RN50_CONV_FWD = 0, RN50_CONV_DGRAD = 1, RN50_CONV_WGRAD = 2 };
  * of range or does not fit the shape leaves the heuristic in charge. */
 size_t conv_workspace_bytes(const conv_desc* d, int which);
 int rn50_conv_variant_count(int which);
+/* 1 if variant is a kernel of its own for this convolution (which: 0 forward, 1 data gradient, 2 filter gradient),
+ * 0 if the shape heuristic or a fallback would run in its place (or d is invalid).  Host only, launches nothing. */
+int rn50_conv_variant_applies(const conv_desc* d, int which, int variant);
 
 /* y[n,p,q,k] = sum_{r,s,c} x[n,p*stride+r-pad,q*stride+s-pad,c] * w[k,r,s,c]  (zero padding) */
 int conv_fwd(const conv_desc* d, const void* x, const void* w, void* y,
@@ -341,6 +344,31 @@ typedef struct {
 } rn50_profile_entry;
 int rn50_profile_begin(void);
 int rn50_profile_end(rn50_profile_entry* out, int max_entries, int* n_out);
+
+/* ------------------------------------------------------------------------------------------
+ * Hardware probes (measurement aids, not part of the training path): the machine figures that
+ * the tile shapes of the convolutions (Sec. 3.2: FP16 forward/backward) are weighed against.
+ * All pointers are device pointers owned by the caller; every call only enqueues one kernel.
+ *   rn50_probe_mfma: blocks workgroups of 4 wavefronts, each issuing 4*iters independent
+ *     32x32x16 FP16 MFMAs from registers (flops = blocks*4*iters*4*32768); out: blocks*256 floats.
+ *   rn50_probe_tile_load: workgroup b fetches iters consecutive tiles of 16 KB out of src, starting at
+ *     tile (b * start_stride) mod (src_bytes / 16384) and wrapping (src_bytes a multiple of 16384, at most
+ *     2 GiB - 16 KB; the working-set size and the stride decide whether the tiles come from L2, the Infinity
+ *     Cache or HBM: start_stride = iters with blocks*iters tiles in src reads every tile exactly once),
+ *     through_lds != 0: global -> LDS directly with three tiles in flight (out[b*256+t] = sum over the tiles of
+ *     half t*8 of the tile), else with 16-byte vector loads into registers (out, read as unsigned: XOR of all
+ *     32-bit words the thread loaded: words t*4..t*4+3 of each 4 KB quarter of each tile);
+ *     bytes moved = blocks*iters*16384; out: blocks*256 elements.
+ *   rn50_probe_copy: streaming copy of bytes (a multiple of 16) from src to dst.
+ *   rn50_probe_empty: count kernels that do nothing, one after the other on the stream (cost of a
+ *     dependent launch).
+ * RN50_ERR_SHAPE for sizes outside the stated ranges (blocks 1..65536, iters >= 1).
+ * ---------------------------------------------------------------------------------------- */
+int rn50_probe_mfma(int blocks, int iters, float* out, void* stream);
+int rn50_probe_tile_load(const void* src, size_t src_bytes, int blocks, int iters, int start_stride, int through_lds,
+                         float* out, void* stream);
+int rn50_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+int rn50_probe_empty(int count, void* stream);
 
 #ifdef __cplusplus
 }

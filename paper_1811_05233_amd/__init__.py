@@ -66,6 +66,7 @@ _SIGNATURES = {
     "conv_dgrad": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv_wgrad": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "rn50_conv_variant_count": (_i, [_i]),
+    "rn50_conv_variant_applies": (_i, [ctypes.POINTER(conv_desc), _i, _i]),
     "conv_fwd_variant": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _i, _vp]),
     "conv_dgrad_variant": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _i, _vp]),
     "conv_wgrad_variant": (_i, [ctypes.POINTER(conv_desc), _vp, _vp, _vp, _vp, _sz, _i, _vp]),
@@ -103,6 +104,10 @@ _SIGNATURES = {
     "rn50_set_tuning": (_i, [_vp, ctypes.POINTER(_i), _i]),
     "rn50_tuning_report": (_sz, [_vp, ctypes.c_char_p, _sz]),
     "rn50_tensor": (_i, [_vp, ctypes.c_char_p, ctypes.POINTER(_vp), ctypes.POINTER(_sz), ctypes.POINTER(_i)]),
+    "rn50_probe_mfma": (_i, [_i, _i, _vp, _vp]),
+    "rn50_probe_tile_load": (_i, [_vp, _sz, _i, _i, _i, _i, _vp, _vp]),
+    "rn50_probe_copy": (_i, [_vp, _vp, _sz, _vp]),
+    "rn50_probe_empty": (_i, [_i, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -350,6 +355,29 @@ def rn50_param_layout(cfg):
 
 def rn50_workspace_bytes(cfg):
     return int(lib().rn50_workspace_bytes(ctypes.byref(cfg)))
+
+
+def probe_mfma(blocks, iters, out):
+    """Register-only MFMA loop (rn50_probe_mfma); out: float tensor of blocks*256 elements."""
+    _check(lib().rn50_probe_mfma(int(blocks), int(iters), _ptr(out), _stream()), "rn50_probe_mfma")
+
+
+def probe_tile_load(src, src_bytes, blocks, iters, start_stride, through_lds, out):
+    _check(lib().rn50_probe_tile_load(_ptr(src), int(src_bytes), int(blocks), int(iters), int(start_stride),
+                                      int(bool(through_lds)), _ptr(out), _stream()), "rn50_probe_tile_load")
+
+
+def probe_copy(src, dst, nbytes):
+    _check(lib().rn50_probe_copy(_ptr(src), _ptr(dst), int(nbytes), _stream()), "rn50_probe_copy")
+
+
+def probe_empty(count=1):
+    _check(lib().rn50_probe_empty(int(count), _stream()), "rn50_probe_empty")
+
+
+def conv_variant_applies(d, which, variant):
+    """True if the variant id names a kernel of its own for this shape (no GPU needed)."""
+    return bool(lib().rn50_conv_variant_applies(ctypes.byref(d), int(which), int(variant)))
 
 
 def shipped_tuning_path(batch):

@@ -1155,15 +1155,20 @@ int gather_tile_heuristic(const GatherArgs& a)
 
 int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, int tile)
 {
-    if (a.CR == 32)                 // stem forward
-        return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
-    // RN50_TILE_STRICT (tuning): a variant that does not apply to this shape is an error instead of a fallback
+    // RN50_TILE_STRICT (tuning): a variant that does not apply to this shape is an error instead of a fallback;
+    // RN50_TILE_QUERY: only say whether it applies
     const bool strict = tile >= 0 && (tile & RN50_TILE_STRICT) != 0;
-    if (tile >= 0) tile &= ~RN50_TILE_STRICT;
+    const bool query = tile >= 0 && (tile & RN50_TILE_QUERY) != 0;
+    if (tile >= 0) tile &= ~(RN50_TILE_STRICT | RN50_TILE_QUERY);
+    if (a.CR == 32) {               // stem forward: one kernel, whatever the variant
+        if (query) return RN50_OK;
+        return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
+    }
     if (!gather_tile_ok(a, tile)) {
-        if (strict) return RN50_ERR_SHAPE;
+        if (strict || query) return RN50_ERR_SHAPE;
         tile = gather_tile_heuristic(a);
     }
+    if (query) return RN50_OK;
     static_assert(RN50_K_GATHER_TILE_LAST - RN50_K_GATHER_TILE0 + 1 == RN50_NUM_GATHER_TILES, "one profile id per tile variant");
     const int kid = RN50_K_GATHER_TILE0 + tile;
     switch (tile) {
@@ -1360,7 +1365,8 @@ int rn50_conv_dgrad_launch(const conv_desc& d, const h16* dy, const h16* wt, con
     // plain zeros.  Without an addend or a fused epilogue they are cleared by a fill of the whole tensor and only the
     // first class goes through the GEMM.
     if (d.r == 1 && d.stride == 2 && !addend && !fuse) {
-        RN50_TRY(rn50_fill_zero(reinterpret_cast<float*>(dx), (size_t)d.n * d.h * d.w * d.c / 2, s));
+        const bool query = tile >= 0 && (tile & RN50_TILE_QUERY) != 0;       // a query launches nothing
+        if (!query) RN50_TRY(rn50_fill_zero(reinterpret_cast<float*>(dx), (size_t)d.n * d.h * d.w * d.c / 2, s));
         a.ncls = 1;
     }
     // a strided 1x1 data gradient still writes every pixel of dx
@@ -1618,6 +1624,24 @@ extern "C" int conv_fwd_variant(const conv_desc* d, const void* x, const void* w
     }
     return rn50_conv_fwd_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(w), static_cast<h16*>(y), s, nullptr,
                                 nullptr, variant);
+}
+
+// 1 if the variant id is a kernel of its own for this shape, 0 if the heuristic (forward, data gradient) or a
+// fallback tile (filter gradient) would run in its place.
+extern "C" int rn50_conv_variant_applies(const conv_desc* d, int which, int variant)
+{
+    if (!d || rn50_conv_validate(d) != RN50_OK || variant < 0) return 0;
+    if (which == RN50_CONV_FWD) {
+        if (variant >= RN50_NUM_GATHER_TILES) return 0;
+        return rn50_conv_fwd_launch(*d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, variant | RN50_TILE_QUERY) == RN50_OK;
+    }
+    if (which == RN50_CONV_DGRAD) {
+        if (variant >= RN50_NUM_GATHER_TILES || rn50_conv_is_stem(*d)) return 0;
+        return rn50_conv_dgrad_launch(*d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, variant | RN50_TILE_QUERY) ==
+               RN50_OK;
+    }
+    if (which == RN50_CONV_WGRAD) return variant < RN50_NUM_WGRAD_VARIANTS && rn50_wgrad_canonical_variant(*d, variant) == variant;
+    return 0;
 }
 
 extern "C" int conv_fwd(const conv_desc* d, const void* x, const void* w, void* y, void* ws, size_t ws_bytes, void* stream)

@@ -30,6 +30,7 @@ enum {
     RN50_TILE_128x128_OCC4,    // 128x128, 32-wide slabs, 2 stages, 4 workgroups per compute unit (784 tiles fit one round of 1024)
     RN50_NUM_GATHER_TILES,
     RN50_TILE_STRICT = 0x1000,  // flag on a tile id: fail with RN50_ERR_SHAPE instead of falling back when it does not apply
+    RN50_TILE_QUERY = 0x2000,   // flag on a tile id: launch nothing, only report RN50_OK / RN50_ERR_SHAPE (pointers may be null)
     RN50_WGRAD_TILE_STRIP = 10, // filter-gradient tile index of the 3x3 strip kernel (the ten before it: kWgradTiles)
     RN50_NUM_WGRAD_TILES = 11,
     RN50_NUM_WGRAD_VARIANTS = 3 * RN50_NUM_WGRAD_TILES      // tile x split target

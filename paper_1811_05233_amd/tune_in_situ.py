@@ -4,8 +4,8 @@ rn50_autotune times every convolution's variants one launch site at a time, in i
 kernels of the two streams share the compute units and the L2, and the variant that wins alone is not always the
 one that gives the shortest step.  This tool searches the variant table (three entries per convolution: forward,
 data gradient, filter gradient) by coordinate descent on the measured step time itself: for one entry after the
-other it tries every variant id (ids that do not apply to the shape fall back to the shape heuristic inside the
-library, i.e. they time like -1), and keeps a change only if a second, longer measurement confirms the gain.
+other it tries every variant id that is a kernel of its own for the shape (rn50_conv_variant_applies), and keeps
+a change only if a second, longer measurement confirms the gain.
 
     python -m paper_1811_05233_amd.tune_in_situ --out paper_1811_05233_amd/tuning_resnet50_b32.json
 
@@ -73,6 +73,22 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e6 / steps      # microseconds per step
 
+    # the convolutions in network order (stem; per block conv1, conv2, conv3 and, in a stage's first block, the
+    # projection), to ask the library which variant ids are kernels of their own for each shape
+    descs = [P.make_conv_desc(B, 224, 224, 3, 64, 7, 7, 2, 3)]
+    hw, cin = 56, 64
+    for stage, nblocks in enumerate((3, 4, 6, 3)):
+        width = 64 << stage
+        for b in range(nblocks):
+            stride = 2 if (b == 0 and stage > 0) else 1
+            descs.append(P.make_conv_desc(B, hw, hw, cin, width, 1, 1, 1, 0))
+            descs.append(P.make_conv_desc(B, hw, hw, width, width, 3, 3, stride, 1))
+            descs.append(P.make_conv_desc(B, hw // stride, hw // stride, width, 4 * width, 1, 1, 1, 0))
+            if b == 0:
+                descs.append(P.make_conv_desc(B, hw, hw, cin, 4 * width, 1, 1, stride, 0))
+            hw //= stride
+            cin = 4 * width
+    assert 3 * len(descs) == len(table)
     roles = [int(r) for r in args.roles.split(",")]
     best = measure(table, args.confirm_steps)
     print("start: %.1f us per step" % best, flush=True)
@@ -89,7 +105,7 @@ def main():
                 tried = []
                 cands = [int(v) for v in args.candidates.split(",")] if args.candidates else [-1] + list(range(counts[role]))
                 for cand in cands:
-                    if cand == incumbent or cand >= counts[role]:
+                    if cand == incumbent or cand >= counts[role] or (cand >= 0 and not P.conv_variant_applies(descs[site], role, cand)):
                         continue
                     trial = list(table)
                     trial[idx] = cand

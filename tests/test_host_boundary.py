@@ -139,3 +139,31 @@ def test_schedule_functions_match_the_oracle():
     for bad in [(5, 1.0), (-1, 1.0), (2, -0.5), (2, 90.5), (2, float("nan"))]:
         with pytest.raises(P.Rn50Error):
             P.sched_batch(*bad)
+
+
+def test_which_variants_apply_to_which_shapes():
+    """rn50_conv_variant_applies launches nothing: the strip kernels are for 3x3 / stride 1 / pad 1 up to 56 columns,
+    128-column tiles need the output width of the GEMM to be a multiple of 128, wide K-slabs a matching reduction
+    length; out-of-range ids and the stem's data gradient never apply."""
+    nf = P.conv_variant_count(P.CONV_FWD)
+    nw = P.conv_variant_count(P.CONV_WGRAD)
+    c33 = P.make_conv_desc(4, 56, 56, 64, 64, 3, 3, 1, 1)
+    c33s2 = P.make_conv_desc(4, 56, 56, 128, 128, 3, 3, 2, 1)
+    c11 = P.make_conv_desc(4, 14, 14, 1024, 256, 1, 1, 1, 0)
+    stem = P.make_conv_desc(4, 224, 224, 3, 64, 7, 7, 2, 3)
+    strips = [v for v in range(nf) if P.conv_variant_applies(c33, P.CONV_FWD, v) and not P.conv_variant_applies(c33s2, P.CONV_FWD, v)
+              and not P.conv_variant_applies(c11, P.CONV_FWD, v)]
+    assert len(strips) == 6                                  # three tile heights x (ring, single stage)
+    for v in strips:
+        assert P.conv_variant_applies(c33, P.CONV_DGRAD, v) and not P.conv_variant_applies(c33s2, P.CONV_DGRAD, v)
+    # 64 output channels: no 128-column tile; 256 output channels (forward) / 1024 (data gradient): all of them
+    n64 = sum(P.conv_variant_applies(c33, P.CONV_FWD, v) for v in range(nf))
+    n256 = sum(P.conv_variant_applies(c11, P.CONV_FWD, v) for v in range(nf))
+    assert 0 < n64 - 6 < n256 == nf - 6
+    assert all(P.conv_variant_applies(stem, P.CONV_FWD, v) for v in range(nf))
+    assert not any(P.conv_variant_applies(stem, P.CONV_DGRAD, v) for v in range(nf))
+    for d in (c33, c11):
+        assert not P.conv_variant_applies(d, P.CONV_FWD, -1) and not P.conv_variant_applies(d, P.CONV_FWD, nf)
+        assert not P.conv_variant_applies(d, P.CONV_WGRAD, nw)
+    wstrips = [v for v in range(nw) if P.conv_variant_applies(c33, P.CONV_WGRAD, v) and not P.conv_variant_applies(c11, P.CONV_WGRAD, v)]
+    assert len(wstrips) >= 3 and all(not P.conv_variant_applies(c33s2, P.CONV_WGRAD, v) for v in wstrips[-3:])
