@@ -479,6 +479,15 @@ def main():
         # all convolution kernels together: MFMA rate while they run, and over the whole step
         roof["traffic"] = measured_traffic(dom["name"]) if shipped else None     # the committed counters describe the shipped table
         roof["algorithmic_bytes_per_launch"] = int(dom["bytes"] / dom["launches"])
+        if dom["flops"] > 0 and dom["bytes"] > 0:
+            # where this kernel's launches sit on the roofline: their aggregate arithmetic intensity caps them at
+            # intensity x HBM peak if that is below the MFMA peak
+            inten = dom["flops"] / dom["bytes"]
+            own = min(PEAK_FP16_TFLOPS, inten * PEAK_HBM_GBS / 1e3)
+            roof["intensity_flops_per_byte"] = round(inten, 1)
+            roof["own_roof_tflops"] = round(own, 1)
+            roof["frac_of_own_roof"] = round(ach / own, 4)
+            roof["hbm_gbs_algorithmic"] = round(dom["bytes"] / (dom["total_ms"] * 1e-3) / 1e9, 1)
         # what an event pair reads around an (almost) empty launch: the dispatch latency that avg_launch_us includes
         # and that a profiler's begin/end timestamps of the kernel do not
         tiny = torch.empty(8, dtype=torch.float16, device=dev)
@@ -487,7 +496,7 @@ def main():
             P.rn50_cast_params(8, w, tiny)
         floor = P.rn50_profile_end()
         roof["event_floor_us"] = round(1e3 * floor[0]["total_ms"] / floor[0]["launches"], 2)
-        conv = [e for e in prof if e["flops"] > 0 and ("gather" in e["name"] or "wgrad_kernel" in e["name"])]
+        conv = [e for e in prof if e["flops"] > 0 and any(t in e["name"] for t in ("gather", "strip_gemm", "wgrad_kernel", "wgrad_strip"))]
         conv_fl = sum(e["flops"] for e in conv)
         conv_ms = sum(e["total_ms"] for e in conv)
         roof["conv_mfma_util_pct"] = round(100.0 * conv_fl / (conv_ms * 1e-3) / 1e12 / PEAK_FP16_TFLOPS, 2)
