@@ -1160,9 +1160,16 @@ int dispatch_gather(GatherArgs& a, hipStream_t s, double flops, double bytes, in
     const bool strict = tile >= 0 && (tile & RN50_TILE_STRICT) != 0;
     const bool query = tile >= 0 && (tile & RN50_TILE_QUERY) != 0;
     if (tile >= 0) tile &= ~(RN50_TILE_STRICT | RN50_TILE_QUERY);
-    if (a.CR == 32) {               // stem forward: one kernel, whatever the variant
-        if (query) return RN50_OK;
-        return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
+    if (a.CR == 32) {               // stem forward (one 32-wide slab per filter row): the 32-wide tiles with 64 columns
+        const bool ok = tile == RN50_TILE_128x64 || tile == RN50_TILE_128x64_SHORT || tile == RN50_TILE_64x64_K32 ||
+                        tile == RN50_TILE_256x64;
+        if (query || (strict && !ok)) return ok ? RN50_OK : RN50_ERR_SHAPE;
+        switch (ok ? tile : RN50_TILE_128x64) {
+            case RN50_TILE_128x64_SHORT: return launch_gather<128, 64, 32, 2, 4>(a, s, RN50_K_GATHER_STEM, flops, bytes);
+            case RN50_TILE_64x64_K32: return launch_gather<64, 64, 32, 4, 4>(a, s, RN50_K_GATHER_STEM, flops, bytes);
+            case RN50_TILE_256x64: return launch_gather<256, 64, 32, 3, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
+            default: return launch_gather<128, 64, 32, 4, 2>(a, s, RN50_K_GATHER_STEM, flops, bytes);
+        }
     }
     if (!gather_tile_ok(a, tile)) {
         if (strict || query) return RN50_ERR_SHAPE;
@@ -1620,7 +1627,7 @@ extern "C" int conv_fwd_variant(const conv_desc* d, const void* x, const void* w
         h16* packed = reinterpret_cast<h16*>(static_cast<char*>(ws) + rn50_stem_padded_bytes(*d));
         RN50_TRY(rn50_stem_pad_image(*d, static_cast<const h16*>(x), padded, s));
         RN50_TRY(rn50_stem_pack_filter(*d, static_cast<const h16*>(w), packed, s));
-        return rn50_conv_fwd_launch(*d, padded, packed, static_cast<h16*>(y), s, nullptr, nullptr, RN50_TILE_AUTO);
+        return rn50_conv_fwd_launch(*d, padded, packed, static_cast<h16*>(y), s, nullptr, nullptr, variant);
     }
     return rn50_conv_fwd_launch(*d, static_cast<const h16*>(x), static_cast<const h16*>(w), static_cast<h16*>(y), s, nullptr,
                                 nullptr, variant);

@@ -6,7 +6,7 @@
 enum Rn50Kernel {
     RN50_K_GATHER_TILE0 = 0,        // conv forward / data gradient: one id per tile variant (RN50_TILE_* order)
     RN50_K_GATHER_TILE_LAST = 21,
-    RN50_K_GATHER_STEM,             // stem forward (128x64 tile, 32-wide K slabs)
+    RN50_K_GATHER_STEM,             // stem forward (32-wide K slabs, any of the tiles that fit it)
     RN50_K_WGRAD_TILE0,             // filter gradient: one id per tile variant
     RN50_K_WGRAD_TILE_LAST = RN50_K_WGRAD_TILE0 + 10,
     RN50_K_WGRAD_STEM,

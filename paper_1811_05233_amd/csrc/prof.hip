@@ -14,7 +14,7 @@ const char* const kNames[RN50_K_COUNT] = {
     "strip_gemm_kernel<256,4,1,2,1>", "strip_gemm_kernel<128,2,2,2,1>", "strip_gemm_kernel<64,2,2,2,1>",
     "strip_gemm_kernel<256,4,1,1,2>", "strip_gemm_kernel<128,2,2,1,3>", "strip_gemm_kernel<64,2,2,1,3>",
     "gather_gemm_kernel<128,128,32,2,4>",
-    "gather_gemm_kernel<128,64,32,4,2> (stem)",
+    "gather_gemm_kernel (stem forward)",
     "wgrad_kernel<128,128,4,64,false,32>", "wgrad_kernel<64,64,4,64,false,32>", "wgrad_kernel<64,128,4,64,false,32>",
     "wgrad_kernel<128,64,4,64,false,32>", "wgrad_kernel<64,64,3,64,false,64>", "wgrad_kernel<64,64,2,64,false,64>",
     "wgrad_kernel<64,64,2,64,false,128>", "wgrad_kernel<64,128,3,64,false,64>", "wgrad_kernel<128,64,3,64,false,64>",

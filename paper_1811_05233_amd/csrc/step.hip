@@ -528,10 +528,10 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
     auto conv_bn_fwd = [&](ConvLayer& l, const h16* x, const h16* wts, bool relu, const h16* residual,
                            hipStream_t st, float* part) -> int {
         int tiles = 0;
-        RN50_TRY(launch_or_tune(c, st, l.d.c == 3 ? 1 : RN50_NUM_GATHER_TILES, &l.fwd_tile, [&](int tile) {
+        RN50_TRY(launch_or_tune(c, st, RN50_NUM_GATHER_TILES, &l.fwd_tile, [&](int tile) {
             return rn50_conv_fwd_launch(l.d, x, wts, l.conv_out, st, part, &tiles, tile);
         }, "fwd", l.name.c_str(), [&](int tile) { return finalize_penalty((long long)l.d.n * l.P * l.Q, tile); },
-        l.d.c == 3 ? 0 : RN50_TILE_STRICT));
+        RN50_TILE_STRICT));
         return rn50_bn_fwd_from_partials_launch((long long)l.d.n * l.P * l.Q, l.d.k, cfg.bn_eps, relu, l.conv_out,
                                                 master_w + l.gamma_off, master_w + l.beta_off, residual, l.bn_out,
                                                 l.mean, l.invstd, part, tiles, st);

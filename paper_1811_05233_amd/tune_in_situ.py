@@ -97,8 +97,8 @@ def main():
         changed = 0
         for site in range(nsites):
             for role in roles:
-                if site == 0 and role != 2:
-                    continue                                  # the stem has one forward kernel and no data gradient
+                if site == 0 and role == 1:
+                    continue                                  # the stem has no data gradient
                 idx = 3 * site + role
                 incumbent = table[idx]
                 cur = measure(table, args.steps)              # re-measured per entry: the clock drifts a little

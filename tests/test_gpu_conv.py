@@ -103,6 +103,26 @@ def test_conv_every_gather_tile(tile):
         assert e <= TOL16, "dgrad err %g (tile %d, shape %d)" % (e, tile, i)
 
 
+def test_stem_forward_through_every_tile_that_fits_it():
+    """The 7x7 / stride 2 stem goes through the 32-wide tiles with 64 columns; every id runs (the others fall back)."""
+    shapes = [(3, 34, 30, 3, 64, 7, 2, 3), (2, 64, 64, 3, 64, 7, 2, 3)]
+    applies = [v for v in range(P.conv_variant_count(P.CONV_FWD))
+               if P.conv_variant_applies(P.make_conv_desc(*shapes[0][:5], 7, 7, 2, 3), P.CONV_FWD, v)]
+    assert len(applies) == 4
+    for i, (n, h, w, cin, cout, r, stride, pad) in enumerate(shapes):
+        x = synth.normal_f16(780 + i, (n, h, w, cin))
+        wt = synth.he_normal_f16(790 + i, (cout, r, r, cin), cin * r * r)
+        ref = O.conv_fwd(x.astype(np.float64), wt.astype(np.float64), stride, pad)
+        p, q = O.out_hw(h, w, r, r, stride, pad)
+        d = P.make_conv_desc(n, h, w, cin, cout, r, r, stride, pad)
+        for v in applies + [applies[0] + 1]:
+            print("[case] stem tile=%d shape %d" % (v, i), flush=True)
+            y = torch.full((n, p, q, cout), float("nan"), dtype=torch.float16, device=DEV)
+            P.conv_fwd(d, dev_h(x), dev_h(wt), y, variant=v)
+            e = rel_err(host(y), ref)
+            assert e <= TOL16, "stem fwd err %g (tile %d, shape %d)" % (e, v, i)
+
+
 @pytest.mark.parametrize("variant", range(MAX_WGRAD_VARIANTS))
 def test_conv_every_wgrad_variant(variant):
     if variant >= P.conv_variant_count(P.CONV_WGRAD):
