@@ -333,7 +333,9 @@ int rn50_tensor(rn50_ctx* ctx, const char* name, void** ptr, size_t* elems, int*
  * its stream.  rn50_profile_end synchronises the device and returns, per kernel, the number of
  * launches, the summed event-to-event time, and the summed ALGORITHMIC work of those launches:
  * flops = 2*M*N*K of the convolution as defined (live taps only), bytes = compulsory HBM
- * traffic (each operand read once, each result written once).  Process-wide, not thread-safe.
+ * traffic (each operand read once, each result written once).  An event pair of a launch on a
+ * context's second stream also contains the time the launch waited for compute units held by
+ * the caller's stream.  Process-wide, not thread-safe.
  * ---------------------------------------------------------------------------------------- */
 typedef struct {
     const char* name;   /* kernel name as it appears in a rocprofv3 kernel trace (abbreviated) */
@@ -341,6 +343,7 @@ typedef struct {
     double total_ms;
     double flops;
     double bytes;
+    long long side_launches;   /* how many of the launches ran on a context's second stream, next to the caller's chain */
 } rn50_profile_entry;
 int rn50_profile_begin(void);
 int rn50_profile_end(rn50_profile_entry* out, int max_entries, int* n_out);

@@ -39,7 +39,7 @@ class rn50_config(ctypes.Structure):
 
 class rn50_profile_entry(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_longlong), ("total_ms", ctypes.c_double),
-                ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
+                ("flops", ctypes.c_double), ("bytes", ctypes.c_double), ("side_launches", ctypes.c_longlong)]
 
 
 RN50_KIND_CONV, RN50_KIND_GAMMA, RN50_KIND_BETA, RN50_KIND_FCW, RN50_KIND_FCB = 0, 1, 2, 3, 4
@@ -321,12 +321,13 @@ def rn50_profile_begin():
 
 
 def rn50_profile_end():
-    """List of dicts (name, launches, total_ms, flops, bytes), one per kernel that ran."""
+    """List of dicts (name, launches, total_ms, flops, bytes, side_launches), one per kernel that ran."""
     buf = (rn50_profile_entry * 64)()
     n = _i()
     _check(lib().rn50_profile_end(buf, 64, ctypes.byref(n)), "rn50_profile_end")
     return [dict(name=buf[i].name.decode(), launches=int(buf[i].launches), total_ms=float(buf[i].total_ms),
-                 flops=float(buf[i].flops), bytes=float(buf[i].bytes)) for i in range(n.value)]
+                 flops=float(buf[i].flops), bytes=float(buf[i].bytes), side_launches=int(buf[i].side_launches))
+            for i in range(n.value)]
 
 
 # ------------------------------------------------------------------ whole step

@@ -34,6 +34,8 @@ enum Rn50Kernel {
 };
 
 bool rn50_prof_active();
+// a context's second stream is announced (add) and withdrawn (!add), so that launches on it can be told apart
+void rn50_prof_note_side_stream(hipStream_t s, bool add);
 void rn50_prof_record_begin(int kernel, double flops, double bytes, hipStream_t s);
 void rn50_prof_record_end(hipStream_t s);
 

@@ -25,12 +25,13 @@ const char* const kNames[RN50_K_COUNT] = {
     "sgd_momentum_kernel", "lars_norm_kernel", "lars_rate_kernel", "lars_update_kernel", "cast_f32_to_h16_kernel", "fill_zero_kernel", "transpose_all_kernel",
     "maxpool/avgpool kernels", "fc kernels", "ls_xent_kernel", "stem pad/pack/unpack kernels"};
 
-struct Span { int kernel; double flops, bytes; hipEvent_t e0, e1; };
+struct Span { int kernel; double flops, bytes; hipEvent_t e0, e1; bool side; };
 
 struct Profiler {
     bool active = false;
     std::vector<hipEvent_t> pool;     // recycled events
     std::vector<Span> spans;
+    std::vector<hipStream_t> side_streams;   // library-owned second streams (their launches overlap the caller's chain)
     Span cur;
 };
 
@@ -48,9 +49,19 @@ hipEvent_t take_event()
 
 bool rn50_prof_active() { return g_prof.active; }
 
+void rn50_prof_note_side_stream(hipStream_t s, bool add)
+{
+    std::vector<hipStream_t>& v = g_prof.side_streams;
+    for (size_t i = 0; i < v.size(); ++i)
+        if (v[i] == s) { if (!add) v.erase(v.begin() + i); return; }
+    if (add) v.push_back(s);
+}
+
 void rn50_prof_record_begin(int kernel, double flops, double bytes, hipStream_t s)
 {
-    g_prof.cur = {kernel, flops, bytes, take_event(), take_event()};
+    bool side = false;
+    for (hipStream_t t : g_prof.side_streams) side = side || t == s;
+    g_prof.cur = {kernel, flops, bytes, take_event(), take_event(), side};
     (void)hipEventRecord(g_prof.cur.e0, s);
 }
 
@@ -75,12 +86,12 @@ extern "C" int rn50_profile_end(rn50_profile_entry* out, int max_entries, int* n
     hipError_t e = hipDeviceSynchronize();
     if (e != hipSuccess) return rn50_hip_fail(e);
     double ms[RN50_K_COUNT] = {0}, fl[RN50_K_COUNT] = {0}, by[RN50_K_COUNT] = {0};
-    long long cnt[RN50_K_COUNT] = {0};
+    long long cnt[RN50_K_COUNT] = {0}, side[RN50_K_COUNT] = {0};
     for (Span& sp : g_prof.spans) {
         float t = 0.f;
         e = hipEventElapsedTime(&t, sp.e0, sp.e1);
         if (e != hipSuccess) return rn50_hip_fail(e);
-        ms[sp.kernel] += t; fl[sp.kernel] += sp.flops; by[sp.kernel] += sp.bytes; cnt[sp.kernel] += 1;
+        ms[sp.kernel] += t; fl[sp.kernel] += sp.flops; by[sp.kernel] += sp.bytes; cnt[sp.kernel] += 1; side[sp.kernel] += sp.side ? 1 : 0;
         g_prof.pool.push_back(sp.e0); g_prof.pool.push_back(sp.e1);
     }
     g_prof.spans.clear();
@@ -92,6 +103,7 @@ extern "C" int rn50_profile_end(rn50_profile_entry* out, int max_entries, int* n
         out[n].total_ms = ms[k];
         out[n].flops = fl[k];
         out[n].bytes = by[k];
+        out[n].side_launches = side[k];
         ++n;
     }
     *n_out = n;

@@ -384,6 +384,7 @@ extern "C" int rn50_create(rn50_ctx** out, const rn50_config* cfg, void* workspa
     for (size_t i = 0; e == hipSuccess && i < c->fork_events.size(); ++i)
         e = hipEventCreateWithFlags(&c->fork_events[i], hipEventDisableTiming);
     if (e != hipSuccess) { rn50_destroy(c); return rn50_hip_fail(e); }
+    rn50_prof_note_side_stream(c->side, true);
     *out = c;
     return RN50_OK;
 }
@@ -397,7 +398,7 @@ extern "C" void rn50_destroy(rn50_ctx* ctx)
     if (ctx->transpose_done) (void)hipEventDestroy(ctx->transpose_done);
     if (ctx->tune_e0) (void)hipEventDestroy(ctx->tune_e0);
     if (ctx->tune_e1) (void)hipEventDestroy(ctx->tune_e1);
-    if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    if (ctx->side) { rn50_prof_note_side_stream(ctx->side, false); (void)hipStreamDestroy(ctx->side); }
     lars_plan_destroy(ctx->lars);
     delete ctx;
 }
