@@ -324,7 +324,7 @@ def probes(args):
 def extras(args):
     """The other workloads of the configuration list in short form, outside the timed region of the step: the
     update tail (100 steps), the convolution sweep (warm and cold operands: totals and the three shapes furthest
-    from their own roofline) and the step at the other batch-size-control sizes (few steps each)."""
+    from their own roofline), the step at the other batch-size-control sizes (few steps each) and the hardware probes."""
     import copy
     out = {}
     t = tail(args)
@@ -343,6 +343,10 @@ def extras(args):
     a = copy.copy(args)
     a.steps, a.warmup, a.no_autotune = 8, 2, False
     out["batch_sweep"] = batch_sweep(a, (16, 64, 128))["batches"]
+    pr = probes(args)["probes"]
+    g = pr.pop("gemm_100352x1024x1024_tflops")
+    pr["gemm_100352x1024x1024_tflops"] = {k: g[k] for k in ("best", "best_variant", "frac_of_peak")}
+    out["hardware_probes"] = pr
     return out
 
 
