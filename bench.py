@@ -32,19 +32,32 @@ PEAK_FP16_TFLOPS = 2500.0     # MI355X dense FP16 MFMA peak
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak
 
 
-def measured_traffic(kernel_name):
-    """HBM-side bytes per launch of a kernel from the committed rocprofv3 counter summary (FETCH_SIZE and
-    WRITE_SIZE, calibrated against a plain copy), or None if the summary does not list the kernel."""
+def kernel_family(name):
+    """Kernel template of a profile entry: the name up to its template arguments or remark."""
+    return name.split("<")[0].split(" (")[0].strip()
+
+
+def measured_traffic(family):
+    """HBM-side bytes per launch of a kernel template (all its instantiations, weighted by their launches) from the
+    committed rocprofv3 counter summary (FETCH_SIZE and WRITE_SIZE, calibrated against a plain copy), or None if the
+    summary does not list it."""
     path = os.path.join(ROOT, "profiles", "rn50_step_batch32_hbm_traffic.txt")
-    key = kernel_name.replace(" ", "")
+    launches = kib = 0.0
     try:
         for line in open(path):
             parts = line.split()
-            if len(parts) >= 4 and "".join(parts[:-3]).replace(" ", "") == key:
-                return int((float(parts[-2]) + float(parts[-1])) * 1024)
+            if len(parts) < 4:
+                continue
+            try:
+                n, rd, wr = float(parts[-3]), float(parts[-2]), float(parts[-1])
+            except ValueError:
+                continue
+            if kernel_family("".join(parts[:-3])) == family:
+                launches += n
+                kib += n * (rd + wr)
     except OSError:
         pass
-    return None
+    return int(kib / launches * 1024) if launches else None
 
 
 def _cpu_step_seconds(batch):
@@ -470,34 +483,43 @@ def main():
         # the dominant kernel is looked for on the caller's stream, the dependent chain that sets the step time (an
         # event pair of a side-stream launch also contains its wait for compute units); the side stream's largest
         # kernel is reported next to it
-        chain = [e for e in prof if 2 * e["side_launches"] < e["launches"]]
-        side = [e for e in prof if 2 * e["side_launches"] >= e["launches"] and e["flops"] > 0]
+        def by_family(entries):
+            fam = {}
+            for e in entries:
+                f = fam.setdefault(kernel_family(e["name"]), {"name": kernel_family(e["name"]), "total_ms": 0.0, "launches": 0,
+                                                              "flops": 0.0, "bytes": 0.0, "instantiations": 0})
+                for k in ("total_ms", "launches", "flops", "bytes"):
+                    f[k] += e[k]
+                f["instantiations"] += 1
+            return list(fam.values())
+
+        def roof_of(d):
+            if d["flops"] > 0:
+                a = d["flops"] / (d["total_ms"] * 1e-3) / 1e12
+                r = {"kernel": d["name"], "bound": "mfma", "achieved": round(a, 2), "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(a / PEAK_FP16_TFLOPS, 4)}
+            else:
+                a = d["bytes"] / (d["total_ms"] * 1e-3) / 1e9
+                r = {"kernel": d["name"], "bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(a / PEAK_HBM_GBS, 4)}
+            r["traffic"] = measured_traffic(d["name"]) if shipped else None     # the committed counters describe the shipped table
+            r["avg_launch_us"] = round(1e3 * d["total_ms"] / d["launches"], 2)
+            r["launches_per_step"] = d["launches"] / args.steps
+            r["instantiations"] = d["instantiations"]
+            r["algorithmic_bytes_per_launch"] = int(d["bytes"] / d["launches"])
+            return r, a
+
+        # A kernel is its template: the tile variants of one kernel (chosen per layer by the tuning table) count
+        # together.  The dominant kernel is looked for on the caller's stream, the dependent chain that sets the step
+        # time (an event pair of a side-stream launch also contains its wait for compute units); the side stream's
+        # largest kernel is reported next to it.
+        chain = by_family([e for e in prof if 2 * e["side_launches"] < e["launches"]])
+        side = by_family([e for e in prof if 2 * e["side_launches"] >= e["launches"] and e["flops"] > 0])
         dom = max(chain, key=lambda e: e["total_ms"])
-        if dom["flops"] > 0:
-            ach = dom["flops"] / (dom["total_ms"] * 1e-3) / 1e12
-            roof = {"kernel": dom["name"], "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_FP16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(ach / PEAK_FP16_TFLOPS, 4), "traffic": None,
-                    "avg_launch_us": round(1e3 * dom["total_ms"] / dom["launches"], 2),
-                    "launches_per_step": dom["launches"] / args.steps}
-        else:
-            ach = dom["bytes"] / (dom["total_ms"] * 1e-3) / 1e9
-            roof = {"kernel": dom["name"], "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
-                    "avg_launch_us": round(1e3 * dom["total_ms"] / dom["launches"], 2),
-                    "launches_per_step": dom["launches"] / args.steps}
-        # all convolution kernels together: MFMA rate while they run, and over the whole step
-        roof["traffic"] = measured_traffic(dom["name"]) if shipped else None     # the committed counters describe the shipped table
-        roof["algorithmic_bytes_per_launch"] = int(dom["bytes"] / dom["launches"])
+        roof, ach = roof_of(dom)
         roof["stream"] = "caller's stream (dependent chain)"
         if side:
-            sd = max(side, key=lambda e: e["total_ms"])
-            sa = sd["flops"] / (sd["total_ms"] * 1e-3) / 1e12
-            roof["side_stream_largest"] = {"kernel": sd["name"], "achieved": round(sa, 2), "unit": "TFLOP/s",
-                                           "frac": round(sa / PEAK_FP16_TFLOPS, 4),
-                                           "avg_launch_us": round(1e3 * sd["total_ms"] / sd["launches"], 2),
-                                           "launches_per_step": sd["launches"] / args.steps,
-                                           "traffic": measured_traffic(sd["name"]) if shipped else None,
-                                           "algorithmic_bytes_per_launch": int(sd["bytes"] / sd["launches"])}
+            roof["side_stream_largest"] = roof_of(max(side, key=lambda e: e["total_ms"]))[0]
         if dom["flops"] > 0 and dom["bytes"] > 0:
             # where this kernel's launches sit on the roofline: their aggregate arithmetic intensity caps them at
             # intensity x HBM peak if that is below the MFMA peak
@@ -515,6 +537,7 @@ def main():
             P.rn50_cast_params(8, w, tiny)
         floor = P.rn50_profile_end()
         roof["event_floor_us"] = round(1e3 * floor[0]["total_ms"] / floor[0]["launches"], 2)
+        # all convolution kernels together: MFMA rate while they run, and over the whole step
         conv = [e for e in prof if e["flops"] > 0 and any(t in e["name"] for t in ("gather", "strip_gemm", "wgrad_kernel", "wgrad_strip"))]
         conv_fl = sum(e["flops"] for e in conv)
         conv_ms = sum(e["total_ms"] for e in conv)
