@@ -60,6 +60,20 @@ def measured_traffic(family):
     return int(kib / launches * 1024) if launches else None
 
 
+def trace_average_us(family):
+    """Average duration of a kernel template on the caller's stream in the committed rocprofv3 kernel trace summary
+    (begin/end timestamps, i.e. without the dispatch latency that an event pair includes), or None."""
+    path = os.path.join(ROOT, "profiles", "rn50_step_batch32_kernel_stats.txt")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 8 and parts[0] == family and parts[2] == "launches" and parts[-1] == "average":
+                return float(parts[-3])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def _cpu_step_seconds(batch):
     import numpy as np
     from oracle import resnet50 as R
@@ -518,6 +532,11 @@ def main():
         dom = max(chain, key=lambda e: e["total_ms"])
         roof, ach = roof_of(dom)
         roof["stream"] = "caller's stream (dependent chain)"
+        tr = trace_average_us(dom["name"]) if shipped else None
+        if tr:
+            # the same kernel by the committed rocprofv3 trace: an event pair adds the dispatch latency of the launch
+            roof["trace_avg_us"] = tr
+            roof["frac_by_trace_duration"] = round(roof["frac"] * roof["avg_launch_us"] / tr, 4)
         if side:
             roof["side_stream_largest"] = roof_of(max(side, key=lambda e: e["total_ms"]))[0]
         if dom["flops"] > 0 and dom["bytes"] > 0:
