@@ -8,7 +8,7 @@ int rn50_avgpool_fwd(int N, int HW, int C, const h16* x, h16* y, hipStream_t s);
 int rn50_fc_fwd(int B, int Cin, int Cout, const h16* a, const h16* Wt, const float* bias, float* z, hipStream_t s);
 // dWt, db: half (slices of the flat FP16 gradient)
 int rn50_fc_bwd(int B, int Cin, int Cout, int HW, const h16* a, const h16* Wt, const h16* dz, h16* dWt, h16* db,
-                h16* dx, hipStream_t s);
+                h16* dx, hipStream_t s_weights, hipStream_t s);
 
 int rn50_bn_fwd_launch(long long m, int c, float eps, bool relu, const h16* x, const float* gamma, const float* beta,
                        const h16* res, h16* y, float* save_mean, float* save_invstd, float* ws, hipStream_t s);

@@ -281,11 +281,16 @@ int rn50_fc_fwd(int B, int Cin, int Cout, const h16* a, const h16* Wt, const flo
     return rn50_check_launch();
 }
 
+// The two halves of the FC backward pass only share dz: the weight gradient (dWt, db) may run on another stream than
+// the activation gradient that the rest of the backward pass waits for.
 int rn50_fc_bwd(int B, int Cin, int Cout, int HW, const h16* a, const h16* Wt, const h16* dz, h16* dWt, h16* db,
-                h16* dx, hipStream_t s)
+                h16* dx, hipStream_t s_weights, hipStream_t s)
 {
-    ProfScope ps(RN50_K_FC, 4.0 * B * Cin * Cout, 2.0 * Cin * (B + Cout) + 4.0 * Cin * Cout + 2.0 * B * Cin * HW, s);
-    fc_bwd_w_kernel<<<rn50_cdiv((long long)Cout * (Cin / 8), kThreads), kThreads, 0, s>>>(B, Cin, Cout, a, dz, dWt, db);
+    {
+        ProfScope ps(RN50_K_FC, 2.0 * B * Cin * Cout, 2.0 * Cin * B + 2.0 * Cin * Cout, s_weights);
+        fc_bwd_w_kernel<<<rn50_cdiv((long long)Cout * (Cin / 8), kThreads), kThreads, 0, s_weights>>>(B, Cin, Cout, a, dz, dWt, db);
+    }
+    ProfScope ps(RN50_K_FC, 2.0 * B * Cin * Cout, 2.0 * Cin * Cout + 2.0 * B * Cin * HW, s);
     const int slabs = (Cin / 8 + 15) / 16;
     fc_bwd_a_avgpool_bwd_kernel<<<B * slabs, kThreads, 0, s>>>(Cin, Cout, HW, Wt, dz, dx);
     return rn50_check_launch();

@@ -588,8 +588,13 @@ extern "C" int rn50_step(rn50_ctx* ctx, const void* images, const int32_t* label
         hipError_t e = hipStreamWaitEvent(s, c.transpose_done, 0);
         if (e != hipSuccess) return rn50_hip_fail(e);
     }
+    {   // the FC weight gradient joins the filter gradients on the side stream (dlogits is ready from here on)
+        hipError_t e = hipEventRecord(c.transpose_fork, s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(c.side, c.transpose_fork, 0);
+        if (e != hipSuccess) return rn50_hip_fail(e);
+    }
     RN50_TRY(rn50_fc_bwd(B, L.feat, cfg.classes, HW, c.feat, w16 + L.fcw_off, c.dlogits, g16 + L.fcw_off, g16 + L.fcb_off,
-                         c.head_din, s));
+                         c.head_din, c.side, s));
 
     // The filter gradient of a conv is queued on the side stream as soon as d(conv output) exists (it only
     // needs that and forward activations), so that it overlaps with the data-gradient / BN-backward chain.
